@@ -1,0 +1,234 @@
+/*
+ * hmoe.h -- C ABI of the MI355X (gfx950) MoE-layer forward over an HBM expert cache.
+ *
+ * The library evaluates the MoE layer of HybriMoE, Section II-A, Eq. (1)
+ *
+ *     y = sum_{i<N} Softmax(TopK(x . W_g))_i * E_i(x)          (N experts, K activated)
+ *
+ * plus the always-on shared experts of Section II-A, over experts that are resident in a
+ * fixed number of GPU cache slots (the GPU expert cache of Sections I, IV-D and V), with
+ * missing experts copied on demand from host memory (Section I, "on demand" loading over
+ * PCIe).  One call per step:
+ *
+ *     hmoe_router_logits   x . W_g                       (helper)
+ *     hmoe_route           Softmax(TopK(.))
+ *     hmoe_permute         token-to-expert permutation (+ row gather)
+ *     hmoe_cache_stage     make an expert resident in a slot
+ *     hmoe_expert_ffn_grouped   E_i(.) for every expert with rows, from its slot
+ *     hmoe_combine         the gate-weighted sum of Eq. (1) (+ shared experts)
+ *
+ * Conventions
+ *   - Plain C.  Every call returns an int32 status (HMOE_OK = 0, negative = error), never
+ *     throws and never allocates or frees device memory: the caller owns every buffer.
+ *     The only library-owned objects are the small host-side hmoe_cache and its HIP events.
+ *   - Pointers are DEVICE pointers unless the name starts with h_ (HOST).  Tensors are
+ *     row-major with the innermost dimension contiguous and must be 16-byte aligned;
+ *     slot storage must be 256-byte aligned.
+ *   - `stream` arguments are hipStream_t passed as void* (NULL = the default stream).  All
+ *     device work is enqueued on that stream; no call synchronises the device unless it
+ *     says so.
+ *   - T = tokens, H = hidden, F = expert FFN dim, E = routed experts, K = top_k,
+ *     A = T*K assignments, S = cache slots.
+ *   - dtype HMOE_BF16: activations/weights are bfloat16, accumulation fp32 (MFMA), the
+ *     intermediate h = silu(g)*u and the per-assignment outputs are rounded to bf16.
+ *     dtype HMOE_F32: everything fp32.
+ *   - Errors detectable on the host are reported before anything is enqueued:
+ *     NULL / negative / K > E / S > E / misaligned -> HMOE_ERR_INVALID_ARG; a shape or dtype
+ *     the kernels are not built for -> HMOE_ERR_UNSUPPORTED; workspace too small ->
+ *     HMOE_ERR_WORKSPACE; a failing HIP call -> HMOE_ERR_HIP (text via hmoe_last_error).
+ */
+#ifndef HMOE_H
+#define HMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  HMOE_OK = 0,
+  HMOE_ERR_INVALID_ARG = -1,
+  HMOE_ERR_UNSUPPORTED = -2,
+  HMOE_ERR_WORKSPACE = -3,
+  HMOE_ERR_NOT_RESIDENT = -4,
+  HMOE_ERR_SLOT_BUSY = -5,
+  HMOE_ERR_HIP = -6
+};
+
+enum { HMOE_F32 = 0, HMOE_BF16 = 1 };
+
+/* Which FFN kernels hmoe_expert_ffn_grouped uses.  AUTO picks by token count. */
+enum {
+  HMOE_FFN_AUTO = 0,
+  HMOE_FFN_REFERENCE = 1, /* one wave per output element; any shape; fp32 and bf16          */
+  HMOE_FFN_SKINNY = 2,    /* decode: weight-streaming MFMA GEMV, <= 32 rows per expert pass */
+  HMOE_FFN_TILED = 3      /* prefill: LDS-tiled grouped MFMA GEMM                           */
+};
+
+/* Limits of this build. */
+#define HMOE_MAX_EXPERTS 256
+#define HMOE_MAX_TOP_K 32
+
+/* Shape of one MoE layer (Table II of the paper lists such shapes per model). */
+typedef struct hmoe_layer_desc {
+  int32_t hidden;    /* H                                          */
+  int32_t ffn;       /* F                                          */
+  int32_t n_experts; /* E, 1..HMOE_MAX_EXPERTS                     */
+  int32_t top_k;     /* K, 1..min(E, HMOE_MAX_TOP_K)               */
+  int32_t n_slots;   /* S, 1..E                                    */
+  int32_t dtype;     /* HMOE_F32 or HMOE_BF16                      */
+} hmoe_layer_desc;
+
+/* Host-side cache object: slot table mirror, use ticks, events.  Opaque. */
+typedef struct hmoe_cache hmoe_cache;
+
+const char* hmoe_status_string(int32_t status);
+/* Text of the last failing HIP call on this thread ("" if none). */
+const char* hmoe_last_error(void);
+
+/* ------------------------------------------------------------------------------------
+ * Router logits, the x . W_g of Eq. (1).
+ *   x      [T, H]  layer dtype
+ *   w_g    [E, H]  layer dtype (row e is expert e's router vector)
+ *   logits [T, E]  fp32 out; fp32 accumulation.
+ * T = 0 is a no-op.  bf16 needs H % 16 == 0.
+ */
+int32_t hmoe_router_logits(const hmoe_layer_desc* desc, const void* x, const void* w_g, int32_t T,
+                           float* logits, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Softmax(TopK(.)) of Eq. (1).
+ *   logits   [T, E] fp32, finite (NaN/inf: result unspecified, memory-safe)
+ *   topk_idx [T, K] int32 out: the K largest logits' expert ids, by descending logit;
+ *                              equal logits (+0 == -0) -> lower expert id first
+ *   topk_w   [T, K] fp32 out: softmax over the K kept logits (sums to 1 per token)
+ */
+int32_t hmoe_route(const hmoe_layer_desc* desc, const float* logits, int32_t T, int32_t* topk_idx,
+                   float* topk_w, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Token-to-expert permutation: stable counting sort of the A = T*K flat assignments
+ * a = t*K + j by expert id topk_idx[a] (per-expert load is what the paper's scheduler and
+ * cache consume, Section IV-B; here it is expert_offsets).
+ *   expert_offsets [E+1] int32 out: rows of expert e are [offsets[e], offsets[e+1])
+ *   perm           [A]   int32 out: perm[p] = a (sorted position -> assignment)
+ *   inv_perm       [A]   int32 out: inv_perm[a] = p
+ *   x [T, H] / x_perm [A, H] (layer dtype): when both non-NULL, x_perm[p] = x[perm[p] / K]
+ *   h_counts_pinned [E] int32, HOST pinned memory or NULL: when given, the per-expert row
+ *       counts are also copied there asynchronously on `stream` (valid after the stream or
+ *       an event recorded after this call has completed).
+ *   workspace: hmoe_permute_workspace_bytes(desc, T) bytes of device scratch.
+ * Expert ids outside [0, E) are a precondition violation (memory-safe: such assignments
+ * are clamped to expert E-1).
+ */
+size_t hmoe_permute_workspace_bytes(const hmoe_layer_desc* desc, int32_t T);
+int32_t hmoe_permute(const hmoe_layer_desc* desc, const int32_t* topk_idx, int32_t T, const void* x,
+                     void* x_perm, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
+                     int32_t* h_counts_pinned, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Expert weights.  An expert is three bias-free matrices (SwiGLU; the paper gives only
+ * the sizes, Table II): W_gate [F, H], W_up [F, H], W_down [H, F], row-major.
+ * hmoe_pack_expert rewrites them (HOST to HOST) into the library-private slot layout of
+ * hmoe_slot_bytes(desc) bytes; that blob is what lives in pinned host memory and in the
+ * HBM slots.  bf16 needs H % 64 == 0 and F % 64 == 0 (MFMA tile packing); fp32 takes any.
+ */
+size_t hmoe_slot_bytes(const hmoe_layer_desc* desc);
+int32_t hmoe_pack_expert(const hmoe_layer_desc* desc, const void* h_w_gate, const void* h_w_up,
+                         const void* h_w_down, void* h_packed_out);
+
+/* ------------------------------------------------------------------------------------
+ * GPU expert cache: S slots of hmoe_slot_bytes each in `slot_storage` (device, 256-byte
+ * aligned, S * slot_bytes) and the device table d_slot_of [E] int32 (expert -> slot,
+ * -1 = not resident) that the FFN kernels read.  hmoe_cache_create fills d_slot_of with -1
+ * (synchronously) and keeps a host mirror.  The cache must be used with ONE compute stream.
+ */
+int32_t hmoe_cache_create(const hmoe_layer_desc* desc, void* slot_storage, int32_t* d_slot_of,
+                          hmoe_cache** out);
+int32_t hmoe_cache_destroy(hmoe_cache* cache);
+/* Host mirror: slot of an expert (-1 = not resident), expert in a slot (-1 = free). */
+int32_t hmoe_cache_lookup(const hmoe_cache* cache, int32_t expert_id, int32_t* slot_out);
+int32_t hmoe_cache_occupant(const hmoe_cache* cache, int32_t slot, int32_t* expert_out);
+/* Drop an expert (no-op if not resident); the table changes in compute-stream order. */
+int32_t hmoe_cache_evict(hmoe_cache* cache, int32_t expert_id, void* compute_stream);
+/* Protect a slot from hmoe_cache_stage (pinned != 0) or release it. */
+int32_t hmoe_cache_pin_slot(hmoe_cache* cache, int32_t slot, int32_t pinned);
+
+/*
+ * Make expert_id resident in `slot` (-1 = lowest-numbered free slot; none free ->
+ * HMOE_ERR_SLOT_BUSY) from its packed blob in PINNED HOST memory (on-demand expert load,
+ * Section I).  Enqueues, without blocking the host:
+ *   copy_stream:    wait until the last FFN call that read this slot has finished,
+ *                   hipMemcpyAsync host -> slot, record "ready"
+ *   compute_stream: wait "ready", then update d_slot_of (new expert -> slot, previous
+ *                   occupant -> -1)
+ * so FFN calls enqueued on compute_stream afterwards see the new expert, and FFN calls
+ * enqueued before are not disturbed; the copy overlaps whatever compute does not touch
+ * the slot.  The previous occupant, if any, is evicted.  A pinned slot -> HMOE_ERR_SLOT_BUSY.
+ * If the expert is already resident elsewhere it is first dropped from that slot.
+ * h_packed_pinned must stay valid until the copy has completed.
+ * h_packed_pinned == NULL marks the slot's current device contents as expert_id without
+ * copying (for weights written into slot storage by the caller).
+ */
+int32_t hmoe_cache_stage(hmoe_cache* cache, int32_t expert_id, int32_t slot,
+                         const void* h_packed_pinned, void* compute_stream, void* copy_stream);
+
+/*
+ * Host-only LRU planning for one call (LRU is the replacement policy the paper compares
+ * against, Section IV-D).  h_counts [E]: rows per expert for this call (needed = count > 0).
+ * Outputs, each [E]: h_wave[e] = wave in which e is computed (-1 = not needed; 0 = already
+ * resident), h_slot[e] = slot e will occupy, h_victim[e] = expert it replaces (-1 none).
+ * *n_waves = 1 + the largest wave.  Rules: misses in ascending id; lowest free slot, else the
+ * slot whose occupant has the oldest use tick (ties -> lowest slot); a miss that replaces an
+ * expert needed by this call runs one wave after it.  Updates the use ticks and the clock;
+ * the slot table itself changes only through hmoe_cache_stage.
+ */
+int32_t hmoe_cache_plan(hmoe_cache* cache, const int32_t* h_counts, int32_t* h_wave, int32_t* h_slot,
+                        int32_t* h_victim, int32_t* n_waves);
+
+/* ------------------------------------------------------------------------------------
+ * Grouped SwiGLU expert FFN over resident experts: for every expert e that is active,
+ * has rows and sits in a slot,
+ *     rows = x_perm[offsets[e] : offsets[e+1]]
+ *     o_perm[rows] = (silu(rows . W_gate^T) * (rows . W_up^T)) . W_down^T
+ *   x_perm [A, H], o_perm [A, H] layer dtype; expert_offsets [E+1] device int32
+ *   h_active (HOST) / n_active: the experts of this call ("wave"); NULL = every resident
+ *       expert.  An expert named here that is not resident (host mirror) ->
+ *       HMOE_ERR_NOT_RESIDENT, nothing enqueued.  Rows of experts that are not active or not
+ *       resident are left untouched.
+ *   workspace: hmoe_ffn_workspace_bytes(desc, A) bytes of device scratch (holds h [A, F]).
+ *   path: HMOE_FFN_*; AUTO = SKINNY when T = A/K <= 32 else TILED (bf16), REFERENCE (fp32).
+ * Shared experts (Section II-A) use the same call with a 1-expert layer (E = K = S = 1,
+ * offsets {0, T}).
+ */
+size_t hmoe_ffn_workspace_bytes(const hmoe_layer_desc* desc, int32_t A);
+int32_t hmoe_expert_ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x_perm,
+                                const int32_t* expert_offsets, int32_t A, const int32_t* h_active,
+                                int32_t n_active, void* o_perm, void* workspace, size_t workspace_bytes,
+                                int32_t path, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * The sum of Eq. (1) in gather form:
+ *     y[t] = sum_{j<K} topk_w[t, j] * o_perm[inv_perm[t*K + j]]  (+ o_shared[t])
+ * j in ascending order, then the shared term; fp32 accumulation, one rounding.
+ *   o_perm [A, H], o_shared [T, H] or NULL, y [T, H]: layer dtype.
+ */
+int32_t hmoe_combine(const hmoe_layer_desc* desc, const void* o_perm, const int32_t* inv_perm,
+                     const float* topk_w, const void* o_shared, int32_t T, void* y, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Timing probe for benchmarks: while armed, every hmoe_expert_ffn_grouped call brackets
+ * its first (gate/up) kernel launch with a pair of HIP events on the call's stream.
+ * hmoe_probe_arm(max_pairs) creates the events; hmoe_probe_read synchronises them and
+ * writes the elapsed milliseconds of each recorded pair to h_ms (up to max), returns the
+ * count in *n, and disarms.
+ */
+int32_t hmoe_probe_arm(int32_t max_pairs);
+int32_t hmoe_probe_read(float* h_ms, int32_t max, int32_t* n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HMOE_H */

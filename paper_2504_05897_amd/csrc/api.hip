@@ -1,0 +1,377 @@
+// Host side of libhmoe: argument checks, weight packing, the expert cache (slot table, LRU
+// planning, staging streams and events) and the FFN dispatcher.
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <string>
+
+#include "common.h"
+
+namespace hmoe {
+
+static thread_local std::string g_last_error;
+
+int set_hip_error(hipError_t err, const char* what) {
+  g_last_error = std::string(what) + ": " + hipGetErrorString(err);
+  (void)hipGetLastError();  // clear the sticky error state
+  return HMOE_ERR_HIP;
+}
+
+int check_desc(const hmoe_layer_desc* d) {
+  if (!d) return HMOE_ERR_INVALID_ARG;
+  if (d->hidden <= 0 || d->ffn <= 0 || d->n_experts <= 0 || d->top_k <= 0 || d->n_slots <= 0)
+    return HMOE_ERR_INVALID_ARG;
+  if (d->top_k > d->n_experts || d->n_slots > d->n_experts) return HMOE_ERR_INVALID_ARG;
+  if (d->dtype != HMOE_F32 && d->dtype != HMOE_BF16) return HMOE_ERR_INVALID_ARG;
+  if (d->n_experts > HMOE_MAX_EXPERTS || d->top_k > HMOE_MAX_TOP_K) return HMOE_ERR_UNSUPPORTED;
+  return HMOE_OK;
+}
+
+static int check_ffn_shape(const hmoe_layer_desc* d) {
+  int rc = check_desc(d);
+  if (rc != HMOE_OK) return rc;
+  if (d->dtype == HMOE_BF16 && (d->hidden % 64 != 0 || d->ffn % 64 != 0)) return HMOE_ERR_UNSUPPORTED;
+  return HMOE_OK;
+}
+
+// ---- timing probe ----------------------------------------------------------------------
+static std::vector<hipEvent_t> g_probe_ev;  // pairs
+static int g_probe_used = 0;
+static bool g_probe_armed = false;
+
+void probe_before(hipStream_t s) {
+  if (g_probe_armed && 2 * g_probe_used + 1 < (int)g_probe_ev.size()) (void)hipEventRecord(g_probe_ev[2 * g_probe_used], s);
+}
+void probe_after(hipStream_t s) {
+  if (g_probe_armed && 2 * g_probe_used + 1 < (int)g_probe_ev.size()) {
+    (void)hipEventRecord(g_probe_ev[2 * g_probe_used + 1], s);
+    ++g_probe_used;
+  }
+}
+
+__global__ void set_slot_kernel(int32_t* slot_of, int e_new, int slot, int e_old) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    if (e_old >= 0) slot_of[e_old] = -1;
+    if (e_new >= 0) slot_of[e_new] = slot;
+  }
+}
+
+}  // namespace hmoe
+
+using namespace hmoe;
+
+extern "C" const char* hmoe_status_string(int32_t status) {
+  switch (status) {
+    case HMOE_OK: return "ok";
+    case HMOE_ERR_INVALID_ARG: return "invalid argument";
+    case HMOE_ERR_UNSUPPORTED: return "shape or dtype not supported by this build";
+    case HMOE_ERR_WORKSPACE: return "workspace too small";
+    case HMOE_ERR_NOT_RESIDENT: return "expert not resident in the cache";
+    case HMOE_ERR_SLOT_BUSY: return "no usable cache slot";
+    case HMOE_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+extern "C" const char* hmoe_last_error(void) { return g_last_error.c_str(); }
+
+extern "C" int32_t hmoe_probe_arm(int32_t max_pairs) {
+  if (max_pairs <= 0) return HMOE_ERR_INVALID_ARG;
+  for (hipEvent_t e : g_probe_ev) (void)hipEventDestroy(e);
+  g_probe_ev.clear();
+  g_probe_ev.resize(2 * (size_t)max_pairs);
+  for (auto& e : g_probe_ev) HMOE_HIP(hipEventCreate(&e));
+  g_probe_used = 0;
+  g_probe_armed = true;
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_probe_read(float* h_ms, int32_t max, int32_t* n) {
+  if (!h_ms || !n || max < 0) return HMOE_ERR_INVALID_ARG;
+  g_probe_armed = false;
+  const int cnt = std::min<int>(g_probe_used, max);
+  for (int i = 0; i < cnt; ++i) {
+    HMOE_HIP(hipEventSynchronize(g_probe_ev[2 * i + 1]));
+    HMOE_HIP(hipEventElapsedTime(&h_ms[i], g_probe_ev[2 * i], g_probe_ev[2 * i + 1]));
+  }
+  *n = cnt;
+  for (hipEvent_t e : g_probe_ev) (void)hipEventDestroy(e);
+  g_probe_ev.clear();
+  g_probe_used = 0;
+  return HMOE_OK;
+}
+
+// ---- weights ---------------------------------------------------------------------------
+extern "C" size_t hmoe_slot_bytes(const hmoe_layer_desc* desc) {
+  if (check_desc(desc) != HMOE_OK) return 0;
+  const size_t elem = desc->dtype == HMOE_BF16 ? 2 : 4;
+  const size_t raw = 3 * (size_t)desc->hidden * desc->ffn * elem;
+  return (raw + 255) & ~(size_t)255;
+}
+
+// rows [n0, n0+32) of src [*, K] -> one 32-row group of tiles at dst
+static void pack_row_group(const bf16_t* src, int n0, int K, bf16_t* dst) {
+  const int kt = K / TILE_K;
+  for (int kb = 0; kb < kt; ++kb) {
+    bf16_t* tile = dst + (size_t)kb * TILE_ELEMS;
+    for (int lane = 0; lane < 64; ++lane) {
+      const bf16_t* s = src + (size_t)(n0 + lane % TILE_N) * K + kb * TILE_K + 8 * (lane / TILE_N);
+      memcpy(tile + lane * 8, s, 16);
+    }
+  }
+}
+
+extern "C" int32_t hmoe_pack_expert(const hmoe_layer_desc* desc, const void* h_w_gate, const void* h_w_up,
+                                    const void* h_w_down, void* h_packed_out) {
+  int rc = check_ffn_shape(desc);
+  if (rc != HMOE_OK) return rc;
+  if (!h_w_gate || !h_w_up || !h_w_down || !h_packed_out) return HMOE_ERR_INVALID_ARG;
+  const size_t H = desc->hidden, F = desc->ffn;
+  if (desc->dtype == HMOE_F32) {
+    float* out = (float*)h_packed_out;
+    memcpy(out, h_w_gate, F * H * 4);
+    memcpy(out + F * H, h_w_up, F * H * 4);
+    memcpy(out + 2 * F * H, h_w_down, F * H * 4);
+    return HMOE_OK;
+  }
+  bf16_t* out = (bf16_t*)h_packed_out;
+  const size_t group = (size_t)TILE_N * H;  // elements of one packed 32-row group of the gate/up matrix
+  for (size_t q = 0; q < F / TILE_N; ++q) {
+    pack_row_group((const bf16_t*)h_w_gate, (int)(q * TILE_N), (int)H, out + (2 * q) * group);
+    pack_row_group((const bf16_t*)h_w_up, (int)(q * TILE_N), (int)H, out + (2 * q + 1) * group);
+  }
+  bf16_t* down = out + 2 * F * H;
+  for (size_t nb = 0; nb < H / TILE_N; ++nb)
+    pack_row_group((const bf16_t*)h_w_down, (int)(nb * TILE_N), (int)F, down + nb * (size_t)TILE_N * F);
+  return HMOE_OK;
+}
+
+// ---- cache -----------------------------------------------------------------------------
+extern "C" int32_t hmoe_cache_create(const hmoe_layer_desc* desc, void* slot_storage, int32_t* d_slot_of,
+                                     hmoe_cache** out) {
+  int rc = check_desc(desc);
+  if (rc != HMOE_OK) return rc;
+  if (!slot_storage || !d_slot_of || !out) return HMOE_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(slot_storage) & 255u) return HMOE_ERR_INVALID_ARG;
+  hmoe_cache* c = new (std::nothrow) hmoe_cache();
+  if (!c) return HMOE_ERR_INVALID_ARG;
+  c->desc = *desc;
+  c->slots = (char*)slot_storage;
+  c->slot_bytes = hmoe_slot_bytes(desc);
+  c->d_slot_of = d_slot_of;
+  c->slot_of.assign(desc->n_experts, -1);
+  c->expert_in.assign(desc->n_slots, -1);
+  c->tick.assign(desc->n_experts, 0);
+  c->clock = 1;
+  c->pinned.assign(desc->n_slots, 0);
+  c->use_seq = 0;
+  c->track_reads = desc->n_slots < desc->n_experts;
+  c->slot_last_read.assign(desc->n_slots, 0);
+  c->ready_ev.assign(desc->n_slots, nullptr);
+  for (auto& e : c->use_ev) e = nullptr;
+  c->fence_ev = nullptr;
+  hipError_t err = hipGetDevice(&c->device);
+  for (int i = 0; err == hipSuccess && i < hmoe_cache::RING; ++i)
+    err = hipEventCreateWithFlags(&c->use_ev[i], hipEventDisableTiming);
+  for (int i = 0; err == hipSuccess && i < desc->n_slots; ++i)
+    err = hipEventCreateWithFlags(&c->ready_ev[i], hipEventDisableTiming);
+  if (err == hipSuccess) err = hipEventCreateWithFlags(&c->fence_ev, hipEventDisableTiming);
+  if (err == hipSuccess)
+    err = hipMemcpy(d_slot_of, c->slot_of.data(), sizeof(int32_t) * desc->n_experts, hipMemcpyHostToDevice);
+  if (err != hipSuccess) {
+    hmoe_cache_destroy(c);
+    return set_hip_error(err, "hmoe_cache_create");
+  }
+  *out = c;
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_cache_destroy(hmoe_cache* c) {
+  if (!c) return HMOE_ERR_INVALID_ARG;
+  for (auto e : c->use_ev)
+    if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ready_ev)
+    if (e) (void)hipEventDestroy(e);
+  if (c->fence_ev) (void)hipEventDestroy(c->fence_ev);
+  delete c;
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_cache_lookup(const hmoe_cache* c, int32_t expert_id, int32_t* slot_out) {
+  if (!c || !slot_out || expert_id < 0 || expert_id >= c->desc.n_experts) return HMOE_ERR_INVALID_ARG;
+  *slot_out = c->slot_of[expert_id];
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_cache_occupant(const hmoe_cache* c, int32_t slot, int32_t* expert_out) {
+  if (!c || !expert_out || slot < 0 || slot >= c->desc.n_slots) return HMOE_ERR_INVALID_ARG;
+  *expert_out = c->expert_in[slot];
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_cache_pin_slot(hmoe_cache* c, int32_t slot, int32_t pinned) {
+  if (!c || slot < 0 || slot >= c->desc.n_slots) return HMOE_ERR_INVALID_ARG;
+  c->pinned[slot] = pinned ? 1 : 0;
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_cache_evict(hmoe_cache* c, int32_t expert_id, void* compute_stream) {
+  if (!c || expert_id < 0 || expert_id >= c->desc.n_experts) return HMOE_ERR_INVALID_ARG;
+  const int s = c->slot_of[expert_id];
+  if (s < 0) return HMOE_OK;
+  hipLaunchKernelGGL(set_slot_kernel, dim3(1), dim3(64), 0, (hipStream_t)compute_stream, c->d_slot_of, -1, -1,
+                     expert_id);
+  HMOE_HIP(hipGetLastError());
+  c->slot_of[expert_id] = -1;
+  c->expert_in[s] = -1;
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_cache_stage(hmoe_cache* c, int32_t expert_id, int32_t slot, const void* h_packed_pinned,
+                                    void* compute_stream, void* copy_stream) {
+  if (!c || expert_id < 0 || expert_id >= c->desc.n_experts || slot < -1 || slot >= c->desc.n_slots)
+    return HMOE_ERR_INVALID_ARG;
+  hipStream_t comp = (hipStream_t)compute_stream, copy = (hipStream_t)copy_stream;
+  if (slot < 0) {
+    for (int s = 0; s < c->desc.n_slots && slot < 0; ++s)
+      if (c->expert_in[s] < 0 && !c->pinned[s]) slot = s;
+    if (slot < 0) return HMOE_ERR_SLOT_BUSY;
+  }
+  if (c->pinned[slot]) return HMOE_ERR_SLOT_BUSY;
+  const int prev_slot = c->slot_of[expert_id];
+  if (prev_slot >= 0 && prev_slot != slot) {  // resident elsewhere: drop that copy first
+    int rc = hmoe_cache_evict(c, expert_id, compute_stream);
+    if (rc != HMOE_OK) return rc;
+  }
+  const int e_old = c->expert_in[slot] == expert_id ? -1 : c->expert_in[slot];
+  if (h_packed_pinned) {
+    // the copy may overwrite the slot only after the last FFN call that could read it
+    if (!c->track_reads) {
+      // reads were not tracked so far: order the copy after everything enqueued on compute
+      HMOE_HIP(hipEventRecord(c->fence_ev, comp));
+      HMOE_HIP(hipStreamWaitEvent(copy, c->fence_ev, 0));
+      c->track_reads = true;
+    } else if (c->slot_last_read[slot] != 0) {
+      HMOE_HIP(hipStreamWaitEvent(copy, c->use_ev[c->slot_last_read[slot] % hmoe_cache::RING], 0));
+    }
+    HMOE_HIP(hipMemcpyAsync(c->slots + (size_t)slot * c->slot_bytes, h_packed_pinned, c->slot_bytes,
+                            hipMemcpyHostToDevice, copy));
+    HMOE_HIP(hipEventRecord(c->ready_ev[slot], copy));
+    HMOE_HIP(hipStreamWaitEvent(comp, c->ready_ev[slot], 0));
+  }
+  hipLaunchKernelGGL(set_slot_kernel, dim3(1), dim3(64), 0, comp, c->d_slot_of, expert_id, slot, e_old);
+  HMOE_HIP(hipGetLastError());
+  if (e_old >= 0) c->slot_of[e_old] = -1;
+  c->slot_of[expert_id] = slot;
+  c->expert_in[slot] = expert_id;
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_cache_plan(hmoe_cache* c, const int32_t* h_counts, int32_t* h_wave, int32_t* h_slot,
+                                   int32_t* h_victim, int32_t* n_waves) {
+  if (!c || !h_counts || !h_wave || !h_slot || !h_victim || !n_waves) return HMOE_ERR_INVALID_ARG;
+  const int E = c->desc.n_experts, S = c->desc.n_slots;
+  std::vector<int32_t> occ(c->expert_in);  // planned occupant per slot
+  const int64_t base = c->clock;
+  int last_wave = 0;
+  for (int e = 0; e < E; ++e) {
+    h_wave[e] = -1;
+    h_slot[e] = c->slot_of[e];
+    h_victim[e] = -1;
+    if (h_counts[e] > 0 && c->slot_of[e] >= 0) {
+      h_wave[e] = 0;
+      c->tick[e] = base;
+    }
+  }
+  for (int e = 0; e < E; ++e) {
+    if (h_counts[e] <= 0 || h_wave[e] == 0) continue;
+    int target = -1;
+    for (int s = 0; s < S && target < 0; ++s)
+      if (occ[s] < 0 && !c->pinned[s]) target = s;
+    int wave = 1;
+    if (target < 0) {
+      for (int s = 0; s < S; ++s) {
+        if (c->pinned[s]) continue;
+        if (target < 0 || c->tick[occ[s]] < c->tick[occ[target]]) target = s;
+      }
+      if (target < 0) return HMOE_ERR_SLOT_BUSY;
+      const int victim = occ[target];
+      h_victim[e] = victim;
+      if (h_wave[victim] >= 0) wave = h_wave[victim] + 1;
+      h_slot[victim] = -1;
+    }
+    occ[target] = e;
+    h_slot[e] = target;
+    h_wave[e] = wave;
+    c->tick[e] = base + wave;
+    last_wave = std::max(last_wave, wave);
+  }
+  c->clock = base + last_wave + 1;
+  *n_waves = last_wave + 1;
+  return HMOE_OK;
+}
+
+// ---- FFN dispatch ------------------------------------------------------------------------
+extern "C" size_t hmoe_ffn_workspace_bytes(const hmoe_layer_desc* desc, int32_t A) {
+  if (check_desc(desc) != HMOE_OK || A < 0) return 0;
+  const size_t elem = desc->dtype == HMOE_BF16 ? 2 : 4;
+  return (((size_t)A * desc->ffn * elem) + 255) & ~(size_t)255;
+}
+
+extern "C" int32_t hmoe_expert_ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x_perm,
+                                           const int32_t* expert_offsets, int32_t A, const int32_t* h_active,
+                                           int32_t n_active, void* o_perm, void* workspace, size_t workspace_bytes,
+                                           int32_t path, void* stream) {
+  int rc = check_ffn_shape(desc);
+  if (rc != HMOE_OK) return rc;
+  if (!cache || A < 0 || !expert_offsets) return HMOE_ERR_INVALID_ARG;
+  if (memcmp(desc, &cache->desc, sizeof(*desc)) != 0) return HMOE_ERR_INVALID_ARG;
+  if (path < HMOE_FFN_AUTO || path > HMOE_FFN_TILED) return HMOE_ERR_INVALID_ARG;
+  if (A == 0) return HMOE_OK;
+  if (!x_perm || !o_perm) return HMOE_ERR_INVALID_ARG;
+  if (!aligned16(x_perm) || !aligned16(o_perm) || !aligned16(workspace)) return HMOE_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < hmoe_ffn_workspace_bytes(desc, A)) return HMOE_ERR_WORKSPACE;
+  if (h_active && n_active < 0) return HMOE_ERR_INVALID_ARG;
+
+  FfnArgs a;
+  a.desc = desc;
+  a.x_perm = x_perm;
+  a.offsets = expert_offsets;
+  a.n_rows = A;
+  a.slot_of = cache->d_slot_of;
+  a.slots = cache->slots;
+  a.slot_bytes = cache->slot_bytes;
+  a.o_perm = o_perm;
+  a.h = workspace;
+  a.stream = (hipStream_t)stream;
+  memset(&a.active, 0, sizeof(a.active));
+  if (h_active) {
+    for (int i = 0; i < n_active; ++i) {
+      const int e = h_active[i];
+      if (e < 0 || e >= desc->n_experts) return HMOE_ERR_INVALID_ARG;
+      if (cache->slot_of[e] < 0) return HMOE_ERR_NOT_RESIDENT;
+      a.active.w[e >> 6] |= 1ull << (e & 63);
+    }
+  } else {
+    for (int e = 0; e < desc->n_experts; ++e) a.active.w[e >> 6] |= 1ull << (e & 63);
+  }
+
+  if (path == HMOE_FFN_AUTO) {
+    if (desc->dtype == HMOE_F32) path = HMOE_FFN_REFERENCE;
+    else path = (A / desc->top_k <= 32) ? HMOE_FFN_SKINNY : HMOE_FFN_TILED;
+  }
+  if (desc->dtype == HMOE_F32 && path != HMOE_FFN_REFERENCE) return HMOE_ERR_UNSUPPORTED;
+  if (path == HMOE_FFN_REFERENCE) rc = launch_ffn_reference(a);
+  else if (path == HMOE_FFN_SKINNY) rc = launch_ffn_skinny(a);
+  else rc = launch_ffn_tiled(a);
+  if (rc != HMOE_OK) return rc;
+
+  if (cache->track_reads) {
+    const uint64_t seq = ++cache->use_seq;
+    HMOE_HIP(hipEventRecord(cache->use_ev[seq % hmoe_cache::RING], a.stream));
+    for (int e = 0; e < desc->n_experts; ++e)
+      if (a.active.test(e) && cache->slot_of[e] >= 0) cache->slot_last_read[cache->slot_of[e]] = seq;
+  }
+  return HMOE_OK;
+}

@@ -1,0 +1,115 @@
+// Internal declarations shared by the HIP sources of libhmoe (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "hmoe.h"
+
+namespace hmoe {
+
+typedef uint16_t bf16_t;  // bfloat16 storage
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes = 8 bf16
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));  // MFMA operand
+typedef float f32x16_t __attribute__((ext_vector_type(16)));  // 32x32 MFMA accumulator
+
+// D = A(32x16) * B(16x32) + C.  Lane l supplies A[l%32][8*(l/32) .. +8] and B[8*(l/32) .. +8][l%32];
+// accumulator register r of lane l is D[8*(r/4) + 4*(l/32) + r%4][l%32].
+__device__ __forceinline__ f32x16_t mfma_32x32x16_bf16(u32x4 a, u32x4 b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                 0, 0, 0);
+}
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round to nearest, ties to even (inputs are finite on this path)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + __expf(-g)); }
+
+// Experts taking part in one FFN call, one bit per expert id.
+struct ActiveMask {
+  uint64_t w[HMOE_MAX_EXPERTS / 64];
+  __host__ __device__ bool test(int e) const { return (w[e >> 6] >> (e & 63)) & 1ull; }
+};
+
+// --- packed bf16 weight layout ---------------------------------------------------------
+// A matrix W [N, K] (row = output feature, K contiguous) is cut into tiles of 32 rows x 16 k.
+// A tile is 1 KiB, stored in the register order of one 32x32x16 bf16 MFMA operand: lane l of
+// a wavefront owns the 8 consecutive k values  W[32*nb + l%32][16*kb + 8*(l/32) .. +8].
+// Tiles are ordered [nb][kb] (kb fastest), so one 32-row group is one contiguous K stream.
+// The gate/up matrix of an expert interleaves 32-row groups: packed group 2q is W_gate rows
+// 32q..32q+31, group 2q+1 is W_up rows 32q..32q+31; the SwiGLU product then needs no data
+// movement between lanes.  A slot holds [gate/up: 2F x H][down: H x F].
+constexpr int TILE_N = 32;
+constexpr int TILE_K = 16;
+constexpr int TILE_ELEMS = TILE_N * TILE_K;  // 512 bf16 = 1 KiB
+
+__host__ __device__ inline size_t packed_index(int n, int k, int k_tiles) {
+  const int nb = n / TILE_N, kb = k / TILE_K;
+  const int lane = (n % TILE_N) + TILE_N * ((k % TILE_K) / 8);
+  return ((size_t)nb * k_tiles + kb) * TILE_ELEMS + (size_t)lane * 8 + (k % 8);
+}
+
+int set_hip_error(hipError_t err, const char* what);
+int check_desc(const hmoe_layer_desc* d);
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define HMOE_HIP(call)                                                  \
+  do {                                                                  \
+    hipError_t hmoe_e_ = (call);                                        \
+    if (hmoe_e_ != hipSuccess) return hmoe::set_hip_error(hmoe_e_, #call); \
+  } while (0)
+
+// probe (benchmark timing of the gate/up kernel)
+void probe_before(hipStream_t s);
+void probe_after(hipStream_t s);
+
+// kernel launchers, one per source file ---------------------------------------------------
+struct FfnArgs {
+  const hmoe_layer_desc* desc;
+  const void* x_perm;
+  const int32_t* offsets;   // device [E+1]
+  int32_t n_rows;           // A
+  const int32_t* slot_of;   // device [E]
+  const char* slots;        // device slot storage
+  size_t slot_bytes;
+  ActiveMask active;
+  void* o_perm;
+  void* h;                  // workspace [A, F]
+  hipStream_t stream;
+};
+int launch_ffn_reference(const FfnArgs& a);
+int launch_ffn_skinny(const FfnArgs& a);
+int launch_ffn_tiled(const FfnArgs& a);
+
+}  // namespace hmoe
+
+// The host-side cache object behind the opaque handle of the public header.
+struct hmoe_cache {
+  hmoe_layer_desc desc;
+  char* slots;
+  size_t slot_bytes;
+  int32_t* d_slot_of;
+  int device;
+  std::vector<int32_t> slot_of;    // [E] host mirror
+  std::vector<int32_t> expert_in;  // [S]
+  std::vector<int64_t> tick;       // [E] LRU use ticks
+  int64_t clock;
+  std::vector<uint8_t> pinned;     // [S]
+  // read tracking: FFN calls record one event each; a slot remembers the sequence number of
+  // the last call that may have read it.
+  static const int RING = 16;
+  hipEvent_t use_ev[RING];
+  uint64_t use_seq;
+  bool track_reads;
+  std::vector<uint64_t> slot_last_read;  // [S], 0 = never
+  std::vector<hipEvent_t> ready_ev;      // [S]
+  hipEvent_t fence_ev;
+};

@@ -1,0 +1,225 @@
+// hmoe_permute: stable counting sort of the A = T*K assignments by expert id, then row gather.
+//
+// Per-expert load is the quantity everything downstream consumes (Section IV-B uses it to order
+// the queues); here it becomes expert_offsets.  The sort is stable and uses no order-dependent
+// atomics, so the result is the same on every run:
+//   1. histogram   every block counts its 1024-assignment chunk per expert in LDS
+//   2. scan        one block turns the per-block counts into per-(block, expert) bases and the
+//                  per-expert totals into expert_offsets
+//   3. rank        every block re-reads its chunk; a wave ranks 64 assignments at a time with
+//                  ballots (same-key mask), waves and steps are ordered by per-wave LDS bases
+// For A <= 1024 (every decode shape) one block does all three in one launch.
+//   4. gather      x_perm[p] = x[perm[p] / K], 16 bytes per lane
+#include "common.h"
+
+namespace hmoe {
+
+constexpr int PB_THREADS = 256;
+constexpr int PB_WAVES = PB_THREADS / 64;
+constexpr int PB_CHUNK = 1024;               // assignments per block
+constexpr int PB_STEPS = PB_CHUNK / PB_THREADS;  // 64-wide steps per wave
+
+__device__ __forceinline__ int clamp_key(int key, int n_experts) {
+  return key < 0 ? 0 : (key >= n_experts ? n_experts - 1 : key);
+}
+
+// lanes of this wavefront (among `valid` ones) that hold the same key as the caller
+__device__ __forceinline__ uint64_t same_key_mask(int key, bool valid, int key_bits) {
+  uint64_t m = __ballot(valid);
+  for (int b = 0; b < key_bits; ++b) {
+    const bool bit = (key >> b) & 1;
+    const uint64_t bal = __ballot(bit);
+    m &= bit ? bal : ~bal;
+  }
+  return m;
+}
+
+__global__ __launch_bounds__(PB_THREADS) void permute_hist_kernel(const int32_t* __restrict__ topk_idx, int n_assign,
+                                                                  int n_experts, int32_t* __restrict__ block_counts) {
+  __shared__ int hist[HMOE_MAX_EXPERTS];
+  for (int e = threadIdx.x; e < n_experts; e += PB_THREADS) hist[e] = 0;
+  __syncthreads();
+  const long base = (long)blockIdx.x * PB_CHUNK;
+  for (int i = threadIdx.x; i < PB_CHUNK; i += PB_THREADS) {
+    const long a = base + i;
+    if (a < n_assign) atomicAdd(&hist[clamp_key(topk_idx[a], n_experts)], 1);
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < n_experts; e += PB_THREADS) block_counts[(long)blockIdx.x * n_experts + e] = hist[e];
+}
+
+// one block: block_counts[b][e] -> exclusive base of (b, e) in the sorted order; expert_offsets
+__global__ __launch_bounds__(PB_THREADS) void permute_scan_kernel(int32_t* __restrict__ block_counts, int n_blocks,
+                                                                  int n_experts, int n_assign,
+                                                                  int32_t* __restrict__ expert_offsets,
+                                                                  int32_t* __restrict__ counts_out) {
+  __shared__ int total[HMOE_MAX_EXPERTS];
+  __shared__ int start[HMOE_MAX_EXPERTS];
+  const int e = threadIdx.x;
+  if (e < n_experts) {
+    int run = 0;
+    for (int b = 0; b < n_blocks; ++b) {
+      const int c = block_counts[(long)b * n_experts + e];
+      block_counts[(long)b * n_experts + e] = run;
+      run += c;
+    }
+    total[e] = run;
+    if (counts_out) counts_out[e] = run;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int i = 0; i < n_experts; ++i) { start[i] = run; expert_offsets[i] = run; run += total[i]; }
+    expert_offsets[n_experts] = run;
+  }
+  __syncthreads();
+  if (e < n_experts) {
+    const int s = start[e];
+    for (int b = 0; b < n_blocks; ++b) block_counts[(long)b * n_experts + e] += s;
+  }
+}
+
+// Ranks one chunk.  SINGLE: the chunk is the whole input and this block also builds the offsets.
+template <bool SINGLE>
+__global__ __launch_bounds__(PB_THREADS) void permute_rank_kernel(const int32_t* __restrict__ topk_idx, int n_assign,
+                                                                  int n_experts, int key_bits,
+                                                                  const int32_t* __restrict__ block_bases,
+                                                                  int32_t* __restrict__ expert_offsets,
+                                                                  int32_t* __restrict__ counts_out,
+                                                                  int32_t* __restrict__ perm,
+                                                                  int32_t* __restrict__ inv_perm) {
+  __shared__ int wave_base[PB_WAVES][HMOE_MAX_EXPERTS];  // first counts, then running bases
+  __shared__ int scan_tmp[HMOE_MAX_EXPERTS];
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  for (int i = threadIdx.x; i < PB_WAVES * HMOE_MAX_EXPERTS; i += PB_THREADS) (&wave_base[0][0])[i] = 0;
+  __syncthreads();
+
+  // each wave owns a contiguous quarter of the chunk, in PB_STEPS steps of 64
+  const long wave_first = (long)blockIdx.x * PB_CHUNK + (long)wave * (PB_STEPS * 64);
+  int keys[PB_STEPS];
+#pragma unroll
+  for (int s = 0; s < PB_STEPS; ++s) {
+    const long a = wave_first + s * 64 + lane;
+    keys[s] = a < n_assign ? clamp_key(topk_idx[a], n_experts) : -1;
+    if (keys[s] >= 0) atomicAdd(&wave_base[wave][keys[s]], 1);
+  }
+  __syncthreads();
+
+  // counts -> exclusive bases over (expert, wave)
+  const int e = threadIdx.x;
+  int cnt[PB_WAVES], tot = 0;
+  if (e < n_experts) {
+#pragma unroll
+    for (int w = 0; w < PB_WAVES; ++w) { cnt[w] = wave_base[w][e]; tot += cnt[w]; }
+  }
+  int first;
+  if (SINGLE) {
+    // inclusive Hillis-Steele scan of the per-expert totals over the 256 threads
+    scan_tmp[threadIdx.x] = e < n_experts ? tot : 0;
+    __syncthreads();
+    for (int off = 1; off < HMOE_MAX_EXPERTS; off <<= 1) {
+      const int add = threadIdx.x >= off ? scan_tmp[threadIdx.x - off] : 0;
+      __syncthreads();
+      scan_tmp[threadIdx.x] += add;
+      __syncthreads();
+    }
+    first = scan_tmp[threadIdx.x] - tot;
+    if (e < n_experts) {
+      expert_offsets[e] = first;
+      if (counts_out) counts_out[e] = tot;
+      if (e == n_experts - 1) expert_offsets[n_experts] = first + tot;
+    }
+  } else {
+    first = e < n_experts ? block_bases[(long)blockIdx.x * n_experts + e] : 0;
+  }
+  if (e < n_experts) {
+    int run = first;
+#pragma unroll
+    for (int w = 0; w < PB_WAVES; ++w) { wave_base[w][e] = run; run += cnt[w]; }
+  }
+  __syncthreads();
+
+#pragma unroll
+  for (int s = 0; s < PB_STEPS; ++s) {
+    const int key = keys[s];
+    const bool valid = key >= 0;
+    const uint64_t same = same_key_mask(key, valid, key_bits);
+    if (valid) {
+      const uint64_t below = same & ((1ull << lane) - 1ull);
+      const int pos = wave_base[wave][key] + __popcll(below);
+      const int a = (int)(wave_first + s * 64 + lane);
+      perm[pos] = a;
+      inv_perm[a] = pos;
+    }
+    __syncthreads();  // everyone has read the bases of this step
+    if (valid && (same >> lane) >> 1 == 0) wave_base[wave][key] += __popcll(same);  // highest lane of the group
+    __syncthreads();
+  }
+}
+
+// x_perm[p, :] = x[perm[p] / K, :], rows of row_bytes (multiple of 16)
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ perm,
+                                                          int top_k, int row_vec, int n_assign,
+                                                          uint4* __restrict__ x_perm) {
+  const int p = blockIdx.x;
+  if (p >= n_assign) return;
+  const long src = (long)(perm[p] / top_k) * row_vec, dst = (long)p * row_vec;
+  for (int i = threadIdx.x; i < row_vec; i += blockDim.x) x_perm[dst + i] = x[src + i];
+}
+
+static inline int n_chunks(long n_assign) { return (int)((n_assign + PB_CHUNK - 1) / PB_CHUNK); }
+
+}  // namespace hmoe
+
+extern "C" size_t hmoe_permute_workspace_bytes(const hmoe_layer_desc* desc, int32_t T) {
+  if (hmoe::check_desc(desc) != HMOE_OK || T < 0) return 0;
+  const long A = (long)T * desc->top_k;
+  // per-block counts + one row of counts for the pinned-host copy
+  return ((size_t)hmoe::n_chunks(A) + 1) * desc->n_experts * sizeof(int32_t) + 256;
+}
+
+extern "C" int32_t hmoe_permute(const hmoe_layer_desc* desc, const int32_t* topk_idx, int32_t T, const void* x,
+                                void* x_perm, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
+                                int32_t* h_counts_pinned, void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace hmoe;
+  int rc = check_desc(desc);
+  if (rc != HMOE_OK) return rc;
+  if (T < 0 || !expert_offsets) return HMOE_ERR_INVALID_ARG;
+  const long A = (long)T * desc->top_k;
+  if (A > 0x7fffffffL - PB_CHUNK) return HMOE_ERR_UNSUPPORTED;
+  if (A > 0 && (!topk_idx || !perm || !inv_perm)) return HMOE_ERR_INVALID_ARG;
+  if ((x == nullptr) != (x_perm == nullptr)) return HMOE_ERR_INVALID_ARG;
+  const size_t elem = desc->dtype == HMOE_BF16 ? 2 : 4;
+  const size_t row_bytes = (size_t)desc->hidden * elem;
+  if (x && (row_bytes % 16 != 0)) return HMOE_ERR_UNSUPPORTED;
+  if (x && (!aligned16(x) || !aligned16(x_perm))) return HMOE_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < hmoe_permute_workspace_bytes(desc, T)) return HMOE_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 3u) return HMOE_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  const int E = desc->n_experts;
+  int key_bits = 0;
+  while ((1 << key_bits) < E) ++key_bits;
+  const int nblk = n_chunks(A);
+  int32_t* block_counts = (int32_t*)workspace;
+  int32_t* counts_dev = block_counts + (size_t)(nblk > 0 ? nblk : 0) * E;
+
+  if (nblk <= 1) {
+    hipLaunchKernelGGL((permute_rank_kernel<true>), dim3(1), dim3(PB_THREADS), 0, s, topk_idx, (int)A, E, key_bits,
+                       (const int32_t*)nullptr, expert_offsets, counts_dev, perm, inv_perm);
+  } else {
+    hipLaunchKernelGGL(permute_hist_kernel, dim3(nblk), dim3(PB_THREADS), 0, s, topk_idx, (int)A, E, block_counts);
+    hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(PB_THREADS), 0, s, block_counts, nblk, E, (int)A,
+                       expert_offsets, counts_dev);
+    hipLaunchKernelGGL((permute_rank_kernel<false>), dim3(nblk), dim3(PB_THREADS), 0, s, topk_idx, (int)A, E, key_bits,
+                       (const int32_t*)block_counts, expert_offsets, (int32_t*)nullptr, perm, inv_perm);
+  }
+  HMOE_HIP(hipGetLastError());
+  if (h_counts_pinned)
+    HMOE_HIP(hipMemcpyAsync(h_counts_pinned, counts_dev, (size_t)E * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  if (x && A > 0) {
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)A), dim3(256), 0, s, (const uint4*)x, perm, desc->top_k,
+                       (int)(row_bytes / 16), (int)A, (uint4*)x_perm);
+    HMOE_HIP(hipGetLastError());
+  }
+  return HMOE_OK;
+}

@@ -1,0 +1,331 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, step by step and end to end,
+on seeded inputs small enough for the oracle yet spanning several tiles and a ragged tail.
+Integer results (top-k ids, permutation, offsets, slot maps) must match bit for bit; floating
+point within the stated tolerance."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import moe_oracle as orc
+from hmoe_testlib import TOL, build_layer, desc_of, max_rel_err, oracle_layer, to_device, to_host_f32
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def hm():
+    import paper_2504_05897_amd as hm
+    return hm
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+# ----------------------------------------------------------------------------------------- route
+@pytest.mark.parametrize("T,E,K", [(16, 8, 2), (1, 8, 2), (1, 64, 6), (1000, 64, 8), (333, 60, 4), (77, 200, 9),
+                                   (5, 5, 5), (4097, 16, 3), (64, 256, 32), (9, 1, 1)])
+def test_route_bit_exact(hm, T, E, K):
+    say("route", T, E, K)
+    rng = np.random.default_rng(T * 1000 + E)
+    lg = rng.standard_normal((T, E)).astype(np.float32)
+    lg[::3] = np.round(lg[::3] * 2) / 2              # exact ties
+    if T > 4:
+        lg[1] = 0.0                                   # a whole row of ties
+        lg[2, ::2] = -0.0
+        lg[2, 1::2] = 0.0
+    d = hm.make_desc(64, 64, E, K, E, hm.HMOE_BF16)
+    idx = torch.empty(T, K, dtype=torch.int32, device=DEV)
+    w = torch.empty(T, K, dtype=torch.float32, device=DEV)
+    hm.hmoe_route(d, to_device(lg), T, idx, w)
+    ridx, rw = orc.route(lg, K)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=2e-6, atol=1e-7)
+    np.testing.assert_allclose(w.cpu().numpy().astype(np.float64).sum(axis=1), 1.0, atol=1e-6)
+
+
+# ----------------------------------------------------------------------------------------- permute
+@pytest.mark.parametrize("T,E,K", [(1, 8, 2), (16, 8, 2), (1, 64, 6), (4, 64, 8), (512, 8, 2), (171, 64, 6),
+                                   (1024, 64, 1), (1025, 64, 1), (16384, 64, 6), (3000, 200, 5), (0, 8, 2),
+                                   (2048, 64, 8)])
+def test_permute_bit_exact(hm, T, E, K):
+    say("permute", T, E, K)
+    rng = np.random.default_rng(T + 17 * E)
+    if T:
+        lg = rng.standard_normal((T, E)).astype(np.float32) + wl.zipf_bias(E)[None]
+        idx, _ = orc.route(lg, K)
+    else:
+        idx = np.zeros((0, K), np.int32)
+    H = 64
+    d = hm.make_desc(H, 64, E, K, E, hm.HMOE_BF16)
+    A = T * K
+    x = (rng.standard_normal((T, H)) * 4).astype(np.float32)
+    xb = wl.f32_to_bf16_bits(x)
+    xd = to_device(xb) if T else torch.empty(0, H, dtype=torch.bfloat16, device=DEV)
+    offs = torch.full((E + 1,), -7, dtype=torch.int32, device=DEV)
+    perm = torch.full((max(A, 1),), -7, dtype=torch.int32, device=DEV)
+    inv = torch.full((max(A, 1),), -7, dtype=torch.int32, device=DEV)
+    xp = torch.zeros(max(A, 1), H, dtype=torch.bfloat16, device=DEV)
+    counts = torch.zeros(E, dtype=torch.int32, pin_memory=True)
+    ws_bytes = hm.hmoe_permute_workspace_bytes(d, T)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    for rep in range(2):                                  # twice: results must not depend on scheduling
+        hm.hmoe_permute(d, to_device(idx) if T else None, T, xd if T else None, xp if T else None, offs, perm, inv,
+                        counts, ws, ws_bytes)
+        torch.cuda.synchronize()
+        ro, rp, ri = orc.permute(idx, E)
+        assert np.array_equal(offs.cpu().numpy(), ro)
+        assert np.array_equal(perm.cpu().numpy()[:A], rp)
+        assert np.array_equal(inv.cpu().numpy()[:A], ri)
+        assert np.array_equal(counts.numpy(), np.diff(ro))
+        if T:
+            got = xp.view(torch.int16).cpu().numpy().view(np.uint16)[:A]
+            assert np.array_equal(got, orc.gather_rows(xb, rp, K))
+
+
+def test_permute_workspace_too_small(hm):
+    d = hm.make_desc(64, 64, 8, 2, 8, hm.HMOE_BF16)
+    t = torch.zeros(64, dtype=torch.int32, device=DEV)
+    with pytest.raises(hm.HmoeError) as ei:
+        hm.hmoe_permute(d, t, 4, None, None, t, t, t, None, t, 8)
+    assert ei.value.status == hm.HMOE_ERR_WORKSPACE
+
+
+# ----------------------------------------------------------------------------------------- combine
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F32])
+@pytest.mark.parametrize("T,K,H,shared", [(7, 2, 256, False), (33, 6, 2048, True), (1, 8, 3584, True)])
+def test_combine(hm, dtype, T, K, H, shared):
+    say("combine", dtype, T, K, H, shared)
+    rng = np.random.default_rng(T + K)
+    A = T * K
+    o = wl.store(rng.standard_normal((A, H)).astype(np.float32), dtype)
+    osh = wl.store(rng.standard_normal((T, H)).astype(np.float32), dtype)
+    w = rng.random((T, K)).astype(np.float32)
+    inv = rng.permutation(A).astype(np.int32)
+    d = hm.make_desc(H, 64, 64, K, 64, hm.HMOE_BF16 if dtype == wl.BF16 else hm.HMOE_F32)
+    y = torch.empty(T, H, dtype=torch.bfloat16 if dtype == wl.BF16 else torch.float32, device=DEV)
+    hm.hmoe_combine(d, to_device(o), to_device(inv), to_device(w), to_device(osh) if shared else None, T, y)
+    ref = np.zeros((T, H))
+    of = wl.as_f64(o)
+    for t in range(T):
+        for j in range(K):
+            ref[t] += float(w[t, j]) * of[inv[t * K + j]]
+        if shared:
+            ref[t] += wl.as_f64(osh)[t]
+    assert max_rel_err(to_host_f32(y), ref) < (1e-2 if dtype == wl.BF16 else 1e-6)
+
+
+# ----------------------------------------------------------------------------------------- router logits
+@pytest.mark.parametrize("name,T", [("toy", 16), ("dsv2lite", 50)])
+def test_router_logits(hm, name, T):
+    say("router_logits", name, T)
+    shape = wl.SHAPES[name]
+    x = wl.make_x(shape, 3, T)
+    wg = wl.store(np.random.default_rng(1).standard_normal((shape.n_experts, shape.hidden)).astype(np.float32) * 0.05,
+                  shape.dtype)
+    d = desc_of(hm, shape)
+    lg = torch.empty(T, shape.n_experts, dtype=torch.float32, device=DEV)
+    hm.hmoe_router_logits(d, to_device(x), to_device(wg), T, lg)
+    ref = orc.router_logits(wl.as_f64(x), wl.as_f64(wg))
+    assert np.abs(lg.cpu().numpy() - ref).max() <= 1e-5 * np.abs(ref).max()
+
+
+# ----------------------------------------------------------------------------------------- FFN paths
+def _ffn_case(hm, shape, counts, path, seed=0):
+    """Grouped FFN over hand-made ragged row groups, every kernel path, against the oracle."""
+    E = shape.n_experts
+    lay = wl.make_layer(shape, seed, n_tokens=1)
+    d = desc_of(hm, shape, n_slots=E)
+    offsets = np.zeros(E + 1, np.int32)
+    offsets[1:] = np.cumsum(counts)
+    A = int(offsets[-1])
+    rng = np.random.default_rng(seed + 5)
+    xp = wl.store(rng.standard_normal((A, shape.hidden)).astype(np.float32), shape.dtype)
+    layer = hm.MoELayer(d, lay.experts, (), None, max_tokens=max(1, (A + shape.top_k - 1) // shape.top_k + 1))
+    o = torch.zeros(A, shape.hidden, dtype=layer.dt, device=DEV)
+    ws_bytes = hm.hmoe_ffn_workspace_bytes(d, A)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    hm.hmoe_expert_ffn_grouped(d, layer.cache, to_device(xp), to_device(offsets), A, None, o, ws, ws_bytes, path)
+    torch.cuda.synchronize()
+    got = to_host_f32(o)
+    ref = np.zeros((A, shape.hidden))
+    for e in range(E):
+        lo, hi = offsets[e], offsets[e + 1]
+        if hi > lo:
+            ref[lo:hi] = orc.expert_ffn(wl.as_f64(xp[lo:hi]), *(wl.as_f64(m) for m in lay.experts[e]))
+    layer.close()
+    return got, ref
+
+
+def test_ffn_reference_fp32(hm):
+    say("ffn reference fp32")
+    shape = wl.small_shape(dtype=wl.F32, hidden=72, ffn=100, n_experts=5, top_k=2)
+    got, ref = _ffn_case(hm, shape, [3, 0, 7, 1, 4], 1)
+    assert max_rel_err(got, ref) < 1e-5
+
+
+@pytest.mark.parametrize("path", [1, 2, 3])
+@pytest.mark.parametrize("hidden,ffn,counts", [
+    (128, 192, [3, 0, 7, 1, 40, 0, 9, 2]),
+    (256, 64, [33, 1, 0, 0, 300, 5, 64, 129]),
+    (64, 320, [0, 0, 0, 1, 0, 0, 0, 0]),
+])
+def test_ffn_bf16_paths(hm, path, hidden, ffn, counts):
+    say("ffn bf16 path", path, hidden, ffn, counts)
+    shape = wl.small_shape(dtype=wl.BF16, hidden=hidden, ffn=ffn, n_experts=len(counts), top_k=2)
+    got, ref = _ffn_case(hm, shape, counts, path, seed=hidden + path)
+    assert max_rel_err(got, ref) < TOL[wl.BF16]
+    assert np.abs(ref).max() > 1e-2
+
+
+def test_ffn_inactive_and_non_resident_rows_untouched(hm):
+    say("ffn active list")
+    shape = wl.small_shape(dtype=wl.BF16, hidden=64, ffn=64, n_experts=4, top_k=2, n_slots=2)
+    lay = wl.make_layer(shape, 1, 1)
+    d = desc_of(hm, shape)
+    layer = hm.MoELayer(d, lay.experts, (), None, max_tokens=8)
+    offsets = to_device(np.array([0, 2, 4, 6, 8], np.int32))
+    xp = to_device(wl.store(np.random.default_rng(0).standard_normal((8, 64)).astype(np.float32), wl.BF16))
+    ws_bytes = hm.hmoe_ffn_workspace_bytes(d, 8)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    for path in (1, 2, 3):
+        o = torch.full((8, 64), 7.0, dtype=torch.bfloat16, device=DEV)
+        hm.hmoe_expert_ffn_grouped(d, layer.cache, xp, offsets, 8, np.array([1], np.int32), o, ws, ws_bytes, path)
+        got = to_host_f32(o)
+        assert np.all(got[0:2] == 7.0) and np.all(got[4:8] == 7.0) and not np.any(got[2:4] == 7.0)
+        o.fill_(7.0)
+        hm.hmoe_expert_ffn_grouped(d, layer.cache, xp, offsets, 8, None, o, ws, ws_bytes, path)   # residents: 0, 1
+        got = to_host_f32(o)
+        assert np.all(got[4:8] == 7.0) and not np.any(got[0:4] == 7.0)
+    with pytest.raises(hm.HmoeError) as ei:
+        hm.hmoe_expert_ffn_grouped(d, layer.cache, xp, offsets, 8, np.array([3], np.int32), o, ws, ws_bytes, 1)
+    assert ei.value.status == hm.HMOE_ERR_NOT_RESIDENT
+    with pytest.raises(hm.HmoeError) as ei:
+        hm.hmoe_expert_ffn_grouped(d, layer.cache, xp, offsets, 8, None, o, ws, 16, 1)
+    assert ei.value.status == hm.HMOE_ERR_WORKSPACE
+    layer.close()
+
+
+# ----------------------------------------------------------------------------------------- whole layer, small
+def _layer_case(hm, shape, seed, T, path=0):
+    lay = wl.make_layer(shape, seed, T)
+    layer = build_layer(hm, lay)
+    x = to_device(lay.x)
+    if lay.logits is None:
+        y = layer.forward(x, None, path)
+        logits = layer.logits[:T].cpu().numpy()
+        ref_lg = orc.router_logits(wl.as_f64(lay.x), wl.as_f64(lay.w_router))
+        assert np.abs(logits - ref_lg).max() <= (1e-5 if shape.dtype == wl.F32 else 1e-5) * np.abs(ref_lg).max() + 1e-30
+    else:
+        logits = lay.logits
+        y = layer.forward(x, to_device(logits), path)
+    torch.cuda.synchronize()
+    ridx, rw = orc.route(logits, shape.top_k)
+    ro, rp, ri = orc.permute(ridx, shape.n_experts)
+    A = T * shape.top_k
+    assert np.array_equal(layer.topk_idx[:T].cpu().numpy(), ridx)
+    assert np.array_equal(layer.offsets.cpu().numpy(), ro)
+    assert np.array_equal(layer.perm[:A].cpu().numpy(), rp)
+    assert np.array_equal(layer.inv_perm[:A].cpu().numpy(), ri)
+    y_ref = oracle_layer(lay, logits)
+    err = max_rel_err(to_host_f32(y), y_ref)
+    layer.close()
+    return err
+
+
+def test_toy_workload_fp32(hm):
+    """Workload 1: 16 tokens, hidden 256, 8 experts, FFN 512, top-2, fp32, seed 0, all resident."""
+    say("layer toy fp32")
+    err = _layer_case(hm, wl.TOY, 0, 16)
+    say("  err", err)
+    assert err < TOL[wl.F32]
+
+
+@pytest.mark.parametrize("path", [0, 1, 2, 3])
+@pytest.mark.parametrize("T", [1, 5, 40, 300])
+def test_small_bf16_layer_all_paths(hm, T, path):
+    say("layer small bf16", T, path)
+    shape = wl.small_shape(dtype=wl.BF16, hidden=128, ffn=192, n_experts=8, top_k=2, shared_ffn=(64, 64),
+                           x_mode="rmsnorm")
+    err = _layer_case(hm, shape, 7 + T, T, path)
+    say("  err", err)
+    assert err < TOL[wl.BF16]
+
+
+def test_small_layer_with_drawn_logits_and_many_experts(hm):
+    say("layer small zipf 64 experts")
+    shape = wl.small_shape(dtype=wl.BF16, hidden=64, ffn=128, n_experts=64, top_k=6, shared_ffn=(64,),
+                           logits_mode="zipf", x_mode="rmsnorm")
+    for T in (1, 700):
+        err = _layer_case(hm, shape, 21, T)
+        say("  T", T, "err", err)
+        assert err < TOL[wl.BF16]
+
+
+# ----------------------------------------------------------------------------------------- cache
+def test_cache_slot_maps_and_outputs_follow_the_oracle_over_decode_steps(hm):
+    """Partial cache (4 slots, 8 experts): over a sequence of calls the slot map must equal the
+    oracle's LRU state machine after every call, and outputs must still match (staged weights are
+    the right ones, waves cover every needed expert)."""
+    say("cache sequence")
+    shape = wl.small_shape(dtype=wl.BF16, hidden=64, ffn=64, n_experts=8, top_k=2, n_slots=4, x_mode="rmsnorm")
+    steps = [1, 1, 8, 1, 3, 8, 1, 1, 2, 8]
+    lay0 = wl.make_layer(shape, 2, 8)
+    layer = build_layer(hm, lay0, max_tokens=8)
+    model = orc.ExpertCacheModel(8, 4)
+    for i, T in enumerate(steps):
+        lay = wl.make_layer(shape, 100 + i, T, with_weights=False)
+        lay.experts = lay0.experts
+        x = to_device(lay.x)
+        hm.hmoe_router_logits(layer.desc, x, layer.w_router, T, layer.logits)
+        logits = layer.logits[:T].cpu().numpy()
+        y = layer.forward(x, layer.logits[:T].contiguous())
+        torch.cuda.synchronize()
+        ridx, _ = orc.route(logits, 2)
+        plan = model.serve(np.unique(ridx).tolist())
+        assert layer.slot_map() == model.slot_of, (i, plan)
+        assert np.array_equal(layer.slot_of.cpu().numpy(), np.array(model.slot_of, np.int32))
+        wave, slot, victim, n_waves = layer.last_plan
+        for (e, s, w, v) in plan:
+            assert wave[e] == w and slot[e] == s and victim[e] == v
+        assert n_waves == 1 + max(p[2] for p in plan)
+        lay.w_router = lay0.w_router
+        err = max_rel_err(to_host_f32(y), oracle_layer(lay, logits))
+        say("  step", i, "T", T, "waves", n_waves, "err", err)
+        assert err < TOL[wl.BF16]
+    layer.close()
+
+
+def test_cache_stage_errors_and_pinning(hm):
+    say("cache errors")
+    shape = wl.small_shape(dtype=wl.BF16, hidden=64, ffn=64, n_experts=4, top_k=2, n_slots=2)
+    lay = wl.make_layer(shape, 1, 1)
+    layer = build_layer(hm, lay, max_tokens=4)
+    assert layer.slot_map() == [0, 1, -1, -1]
+    with pytest.raises(hm.HmoeError) as ei:          # no free slot
+        hm.hmoe_cache_stage(layer.cache, 2, -1, layer.h_packed[2], None, layer.copy_stream)
+    assert ei.value.status == hm.HMOE_ERR_SLOT_BUSY
+    hm.hmoe_cache_pin_slot(layer.cache, 0, True)
+    with pytest.raises(hm.HmoeError) as ei:
+        hm.hmoe_cache_stage(layer.cache, 2, 0, layer.h_packed[2], None, layer.copy_stream)
+    assert ei.value.status == hm.HMOE_ERR_SLOT_BUSY
+    hm.hmoe_cache_pin_slot(layer.cache, 0, False)
+    hm.hmoe_cache_stage(layer.cache, 2, 0, layer.h_packed[2], None, layer.copy_stream)
+    hm.hmoe_cache_evict(layer.cache, 1)
+    torch.cuda.synchronize()
+    assert layer.slot_map() == [-1, -1, 0, -1]
+    assert layer.slot_of.cpu().tolist() == [-1, -1, 0, -1]
+    assert hm.hmoe_cache_occupant(layer.cache, 0) == 2 and hm.hmoe_cache_occupant(layer.cache, 1) == -1
+    hm.hmoe_cache_stage(layer.cache, 3, -1, layer.h_packed[3], None, layer.copy_stream)   # lowest free = 1
+    torch.cuda.synchronize()
+    assert layer.slot_map() == [-1, -1, 0, 1]
+    # slot contents are the packed blobs
+    got = layer.slots.cpu()
+    sb = layer.slot_bytes
+    assert torch.equal(got[:sb], layer.h_packed[2]) and torch.equal(got[sb:2 * sb], layer.h_packed[3])
+    layer.close()
