@@ -179,7 +179,8 @@ int32_t hmoe_cache_stage(hmoe_cache* cache, int32_t expert_id, int32_t slot,
  * Host-only LRU planning for one call (LRU is the replacement policy the paper compares
  * against, Section IV-D).  h_counts [E]: rows per expert for this call (needed = count > 0).
  * Outputs, each [E]: h_wave[e] = wave in which e is computed (-1 = not needed; 0 = already
- * resident), h_slot[e] = slot e will occupy, h_victim[e] = expert it replaces (-1 none).
+ * resident), h_slot[e] = slot e is computed from (-1 = not needed), h_victim[e] = expert it
+ * replaces (-1 none).
  * *n_waves = 1 + the largest wave.  Rules: misses in ascending id; lowest free slot, else the
  * slot whose occupant has the oldest use tick (ties -> lowest slot); a miss that replaces an
  * expert needed by this call runs one wave after it.  Updates the use ticks and the clock;

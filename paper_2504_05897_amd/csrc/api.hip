@@ -277,10 +277,11 @@ extern "C" int32_t hmoe_cache_plan(hmoe_cache* c, const int32_t* h_counts, int32
   int last_wave = 0;
   for (int e = 0; e < E; ++e) {
     h_wave[e] = -1;
-    h_slot[e] = c->slot_of[e];
+    h_slot[e] = -1;
     h_victim[e] = -1;
     if (h_counts[e] > 0 && c->slot_of[e] >= 0) {
       h_wave[e] = 0;
+      h_slot[e] = c->slot_of[e];
       c->tick[e] = base;
     }
   }
@@ -299,7 +300,6 @@ extern "C" int32_t hmoe_cache_plan(hmoe_cache* c, const int32_t* h_counts, int32
       const int victim = occ[target];
       h_victim[e] = victim;
       if (h_wave[victim] >= 0) wave = h_wave[victim] + 1;
-      h_slot[victim] = -1;
     }
     occ[target] = e;
     h_slot[e] = target;
