@@ -65,30 +65,83 @@ __global__ __launch_bounds__(256) void combine_f32_kernel(const float* __restric
   }
 }
 
-// logits[t, e] = sum_h x[t,h] * w_g[e,h]; one wave per (token, expert) pair group, fp32 accumulate.
-// Block = 4 waves = 4 tokens; every wave walks all experts for its token.
-template <typename T>
-__device__ __forceinline__ float load_as_f32(const T* p);
-template <>
-__device__ __forceinline__ float load_as_f32<float>(const float* p) { return *p; }
-template <>
-__device__ __forceinline__ float load_as_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
-
-template <typename T>
-__global__ __launch_bounds__(256) void router_logits_kernel(const T* __restrict__ x, const T* __restrict__ w_g,
-                                                            int n_tokens, int n_experts, int hidden,
-                                                            float* __restrict__ logits) {
+// logits[t, e] = sum_h x[t,h] * w_g[e,h], fp32 accumulate.
+// fp32 layers: one wavefront per (token, expert) dot product.
+__global__ __launch_bounds__(256) void router_logits_f32_kernel(const float* __restrict__ x, const float* __restrict__ w_g,
+                                                                int n_tokens, int n_experts, int hidden,
+                                                                float* __restrict__ logits) {
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-  const long t = (long)blockIdx.x * 4 + wave;
-  if (t >= n_tokens) return;
-  const T* xr = x + t * hidden;
-  for (int e = 0; e < n_experts; ++e) {
-    const T* wr = w_g + (long)e * hidden;
-    float acc = 0.0f;
-    for (int h = lane; h < hidden; h += 64) acc += load_as_f32(xr + h) * load_as_f32(wr + h);
+  const long pair = (long)blockIdx.x * 4 + wave;
+  if (pair >= (long)n_tokens * n_experts) return;
+  const long t = pair / n_experts;
+  const int e = (int)(pair % n_experts);
+  const float* xr = x + t * hidden;
+  const float* wr = w_g + (long)e * hidden;
+  float acc = 0.0f;
+  for (int h = lane; h < hidden; h += 64) acc = fmaf(xr[h], wr[h], acc);
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-    if (lane == 0) logits[t * n_experts + e] = acc;
+  for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+  if (lane == 0) logits[pair] = acc;
+}
+
+// bf16 layers: a block takes 32 tokens and all experts; both operands are K-contiguous rows, so
+// lanes load MFMA fragments straight from global memory (token or expert row = lane%32, 8 k values
+// at 8*(lane/32)).  The 4 waves split K and meet in LDS.  NF = ceil(E/32) expert fragments.
+template <int NF>
+__global__ __launch_bounds__(256) void router_logits_bf16_kernel(const bf16_t* __restrict__ x,
+                                                                 const bf16_t* __restrict__ w_g, int n_tokens,
+                                                                 int n_experts, int hidden, float* __restrict__ logits) {
+  __shared__ float red[3 * NF * 16 * 64];
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, half = lane / 32, col = lane % 32;
+  const long t0 = (long)blockIdx.x * 32;
+  const int kt = hidden / 16, per_wave = (kt + 3) / 4;
+  const int kb0 = min(wave * per_wave, kt), kb1 = min(kb0 + per_wave, kt);
+  const bool has_tok = t0 + col < n_tokens;
+  const u32x4* xp = (const u32x4*)(x + (t0 + (has_tok ? col : 0)) * hidden) + half;
+  const u32x4* wp[NF];
+  bool has_exp[NF];
+#pragma unroll
+  for (int j = 0; j < NF; ++j) {
+    has_exp[j] = j * 32 + col < n_experts;
+    wp[j] = (const u32x4*)(w_g + (long)(has_exp[j] ? j * 32 + col : 0) * hidden) + half;
+  }
+  f32x16_t acc[NF];
+#pragma unroll
+  for (int j = 0; j < NF; ++j) acc[j] = f32x16_t{0};
+  constexpr int U = 4;
+  for (int kb = kb0; kb < kb1; kb += U) {
+    u32x4 xa[U], wb[U][NF];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool in_range = kb + u < kb1;
+      xa[u] = (in_range && has_tok) ? xp[(long)(kb + u) * 2] : u32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int j = 0; j < NF; ++j) wb[u][j] = (in_range && has_exp[j]) ? wp[j][(long)(kb + u) * 2] : u32x4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int j = 0; j < NF; ++j) acc[j] = mfma_32x32x16_bf16(xa[u], wb[u][j], acc[j]);
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int j = 0; j < NF; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[(((wave - 1) * NF + j) * 16 + r) * 64 + lane] = acc[j][r];
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int j = 0; j < NF; ++j) {
+      const int e = j * 32 + col;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = acc[j][r];
+        for (int w = 0; w < 3; ++w) v += red[((w * NF + j) * 16 + r) * 64 + lane];
+        const long t = t0 + (r / 4) * 8 + half * 4 + (r % 4);
+        if (t < n_tokens && e < n_experts) logits[t * n_experts + e] = v;
+      }
+    }
   }
 }
 
@@ -125,13 +178,22 @@ extern "C" int32_t hmoe_router_logits(const hmoe_layer_desc* desc, const void* x
   if (T == 0) return HMOE_OK;
   if (!x || !w_g || !logits) return HMOE_ERR_INVALID_ARG;
   hipStream_t s = (hipStream_t)stream;
-  const unsigned blocks = (unsigned)((T + 3) / 4);
-  if (desc->dtype == HMOE_BF16)
-    hipLaunchKernelGGL((router_logits_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, (const bf16_t*)x,
-                       (const bf16_t*)w_g, T, desc->n_experts, desc->hidden, logits);
-  else
-    hipLaunchKernelGGL((router_logits_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float*)x,
-                       (const float*)w_g, T, desc->n_experts, desc->hidden, logits);
+  const int E = desc->n_experts, H = desc->hidden;
+  if (desc->dtype == HMOE_BF16) {
+    if (H % 16 != 0) return HMOE_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(w_g)) return HMOE_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)((T + 31) / 32)), block(256);
+    const bf16_t* xb = (const bf16_t*)x;
+    const bf16_t* wb = (const bf16_t*)w_g;
+    if (E <= 32) hipLaunchKernelGGL((router_logits_bf16_kernel<1>), grid, block, 0, s, xb, wb, T, E, H, logits);
+    else if (E <= 64) hipLaunchKernelGGL((router_logits_bf16_kernel<2>), grid, block, 0, s, xb, wb, T, E, H, logits);
+    else if (E <= 128) hipLaunchKernelGGL((router_logits_bf16_kernel<4>), grid, block, 0, s, xb, wb, T, E, H, logits);
+    else hipLaunchKernelGGL((router_logits_bf16_kernel<8>), grid, block, 0, s, xb, wb, T, E, H, logits);
+  } else {
+    const long pairs = (long)T * E;
+    hipLaunchKernelGGL(router_logits_f32_kernel, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, s, (const float*)x,
+                       (const float*)w_g, T, E, H, logits);
+  }
   HMOE_HIP(hipGetLastError());
   return HMOE_OK;
 }

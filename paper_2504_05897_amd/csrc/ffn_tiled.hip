@@ -6,15 +6,19 @@
 // expert-id -> slot table.  All dispatch happens on the device: a block turns its index into
 // (expert, m-tile, n-tile) by walking expert_offsets, so the host never reads the routing result.
 //
-// Block tile BM x BN, K step 64, WM x WN waves, each wave owns (BM/WM) x (BN/WN) of the tile as
+// Block tile BM x BN, K step BKT, WM x WN waves, each wave owns (BM/WM) x (BN/WN) of the tile as
 // 32x32x16 bf16 MFMA fragments with fp32 accumulators.
+//   * Tiles travel global -> LDS without passing through registers (global_load_lds_dwordx4: every
+//     lane supplies a global address, the wave's 64 x 16 bytes land contiguously in LDS), into a
+//     ring of STAGES buffers.  A wave waits (s_waitcnt vmcnt) only for the loads of the K step it is
+//     about to consume, so STAGES-1 steps of loads stay in flight per block; one barrier per step.
 //   * Weights arrive pre-tiled (packed slot layout): a 32-row x 16-k tile is 1 KiB in MFMA operand
-//     order, so it is copied to LDS verbatim and read back with one conflict-free 16-byte read per
-//     lane.
-//   * Activation rows are row-major; they are stored in LDS with their 16-byte chunks XOR-swizzled
-//     by (row/2)%8 so that both the stores and the fragment reads spread over all banks.
-//   * Global loads of K step t+1 are issued before the MFMAs of step t and written to the other LDS
-//     buffer afterwards (one barrier per K step).
+//     order, so it is copied verbatim and read back with one conflict-free 16-byte read per lane.
+//   * Activation rows are row-major; the lane that fills LDS chunk (row, slot) fetches global chunk
+//     slot ^ f(row), an XOR swizzle that spreads the fragment reads over all banks.
+//   * Rows past the end of an expert and weight groups past N are loaded from a clamped (valid)
+//     address instead of being zero-filled; their products land in accumulators that are never
+//     stored.
 //   * Gate and up rows are interleaved in 32-row groups, so a wave's even fragments are gate and
 //     its odd fragments the matching up columns: SwiGLU is applied to registers.
 //   * Tiles are numbered expert-major, then n-tile, then m-tile, and block ids are dealt to the
@@ -24,8 +28,6 @@
 #include "common.h"
 
 namespace hmoe {
-
-constexpr int BK = 64;  // K elements per step
 
 struct TiledCtx {
   const int32_t* offsets;
@@ -38,22 +40,41 @@ struct TiledCtx {
   int grid_padded;
 };
 
-template <bool GATEUP, int BM, int BN, int WM, int WN>
+// One 16-byte global -> LDS copy per lane; the wave's 64 chunks land at lds_base .. +1024 in lane
+// order.  lds_base must be wave-uniform.  Completion is tracked by vmcnt like any vector load.
+__device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gptr), "s"(__builtin_amdgcn_readfirstlane(lds_base))
+               : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <bool GATEUP, int BM, int BN, int BKT, int STAGES, int WM, int WN>
 __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, const bf16_t* __restrict__ in,
                                                                   bf16_t* __restrict__ out) {
-  constexpr int NT = 64 * WM * WN;         // threads
+  constexpr int NWAVES = WM * WN;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int FM = WTM / 32, FN = WTN / 32;
-  constexpr int A_CHUNKS = BM * (BK / 8) / NT;   // 16-byte chunks per thread per step
-  constexpr int B_CHUNKS = BN * (BK / 8) / NT;
-  static_assert(FM >= 1 && FN >= 1 && A_CHUNKS >= 1 && B_CHUNKS >= 1, "tile too small for the block");
-  static_assert(!GATEUP || FN % 2 == 0, "a wave needs gate/up fragment pairs");
-  __shared__ u32x4 lds_a[2][BM * BK / 8];
-  __shared__ u32x4 lds_b[2][BN * BK / 8];
+  constexpr int CPR = BKT / 8;              // 16-byte chunks per activation row per step
+  constexpr int RP = 256 / (BKT * 2);       // rows per 256 bytes of LDS
+  constexpr int KK = BKT / TILE_K;          // MFMA k-substeps per step
+  constexpr int A_CHUNKS = BM * CPR;        // per stage
+  constexpr int B_CHUNKS = BN * CPR;
+  constexpr int A_OPS = A_CHUNKS / (64 * NWAVES);  // wave-wide copies per wave per step
+  constexpr int B_OPS = B_CHUNKS / (64 * NWAVES);
+  constexpr int LPS = A_OPS + B_OPS;        // loads per lane per step
+  static_assert(A_OPS >= 1 && B_OPS >= 1 && A_OPS * 64 * NWAVES == A_CHUNKS && B_OPS * 64 * NWAVES == B_CHUNKS, "");
+  static_assert(FM >= 1 && FN >= 1 && (!GATEUP || FN % 2 == 0), "a wave needs gate/up fragment pairs");
+  static_assert(STAGES >= 2 && (STAGES - 2) * LPS <= 63, "vmcnt range");
+  __shared__ u32x4 lds[STAGES * (A_CHUNKS + B_CHUNKS)];
 
   // ---- which tile -------------------------------------------------------------------
-  // XCD-aware numbering: hardware deals consecutive block ids round-robin to the 8 XCDs;
-  // give each XCD one contiguous range of the logical tile list.
+  // Hardware deals consecutive block ids round-robin to the 8 XCDs; give each XCD one
+  // contiguous range of the logical tile list.
   const int per_xcd = c.grid_padded / 8;
   const int tile_id = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   int e = -1, row_first = 0, m_rows = 0, mt = 0, nt = 0;
@@ -73,10 +94,10 @@ __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, con
       cum += tiles;
     }
   }
-  if (e < 0) return;  // uniform
+  if (e < 0) return;  // uniform over the block
 
   const int K = GATEUP ? c.hidden : c.ffn;
-  const int n_out = GATEUP ? c.ffn : c.hidden;   // row length of out
+  const int n_out = GATEUP ? c.ffn : c.hidden;                    // row length of out
   const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;  // packed 32-row groups of W
   const int kt16 = K / TILE_K;
   const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
@@ -87,38 +108,35 @@ __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, con
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
   const int wm = wave / WN, wn = wave % WN;
   const int half = lane / 32, col = lane % 32;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;  // LDS byte address of the ring
 
-  // ---- global -> register staging -----------------------------------------------------
-  u32x4 ra[A_CHUNKS], rb[B_CHUNKS];
-  const u32x4* a_src[A_CHUNKS];
-  bool a_ok[A_CHUNKS];
-  int a_dst[A_CHUNKS];
+  // ---- per-lane source addresses of the copies this wave issues every step ------------------
+  const u32x4* a_src[A_OPS];
 #pragma unroll
-  for (int i = 0; i < A_CHUNKS; ++i) {
-    const int ci = tid + i * NT, r = ci / 8, cc = ci % 8;
-    a_ok[i] = m0 + r < m_rows;
-    a_src[i] = (const u32x4*)(in + (size_t)(row_first + m0 + (a_ok[i] ? r : 0)) * K) + cc;
-    a_dst[i] = r * 8 + (cc ^ ((r >> 1) & 7));
+  for (int i = 0; i < A_OPS; ++i) {
+    const int ci = (i * NWAVES + wave) * 64 + lane;      // LDS chunk this lane fills
+    const int r = ci / CPR, s = ci % CPR;
+    const int chunk = s ^ ((r / RP) % CPR);
+    const int row = m0 + r < m_rows ? m0 + r : m_rows - 1;  // clamp: never stored
+    a_src[i] = (const u32x4*)(in + (size_t)(row_first + row) * K) + chunk;
   }
-  const u32x4* b_src[B_CHUNKS];
-  bool b_ok[B_CHUNKS];
+  const u32x4* b_src[B_OPS];
 #pragma unroll
-  for (int i = 0; i < B_CHUNKS; ++i) {
-    const int ci = tid + i * NT, g = ci / 256, within = ci % 256;  // 256 chunks = 4 tiles of one group
-    b_ok[i] = group0 + g < n_groups;
-    b_src[i] = w + ((size_t)(b_ok[i] ? group0 + g : 0) * kt16) * 64 + within;
+  for (int i = 0; i < B_OPS; ++i) {
+    const int ci = (i * NWAVES + wave) * 64 + lane;
+    const int g = ci / (KK * 64), within = ci % (KK * 64);  // KK tiles of one group per step
+    const int grp = group0 + g < n_groups ? group0 + g : 0;
+    b_src[i] = w + ((size_t)grp * kt16) * 64 + within;
   }
-  auto load_step = [&](int kstep) {
+  auto issue = [&](int stage, int kstep) {
+    const uint32_t base = lds0 + (uint32_t)stage * (A_CHUNKS + B_CHUNKS) * 16;
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) ra[i] = a_ok[i] ? a_src[i][(size_t)kstep * (BK / 8)] : u32x4{0, 0, 0, 0};
+    for (int i = 0; i < A_OPS; ++i)
+      load_to_lds_16(a_src[i] + (size_t)kstep * CPR, base + (uint32_t)((i * NWAVES + wave) * 64) * 16);
 #pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) rb[i] = b_ok[i] ? b_src[i][(size_t)kstep * 256] : u32x4{0, 0, 0, 0};
-  };
-  auto store_step = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) lds_a[buf][a_dst[i]] = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) lds_b[buf][tid + i * NT] = rb[i];
+    for (int i = 0; i < B_OPS; ++i)
+      load_to_lds_16(b_src[i] + (size_t)kstep * (KK * 64),
+                     base + (uint32_t)(A_CHUNKS + (i * NWAVES + wave) * 64) * 16);
   };
 
   f32x16_t acc[FM][FN];
@@ -127,30 +145,36 @@ __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, con
 #pragma unroll
     for (int j = 0; j < FN; ++j) acc[i][j] = f32x16_t{0};
 
-  const int k_steps = K / BK;
-  load_step(0);
-  store_step(0);
-  __syncthreads();
-  for (int ks = 0; ks < k_steps; ++ks) {
-    const int buf = ks & 1;
-    if (ks + 1 < k_steps) load_step(ks + 1);
+  const int k_steps = K / BKT;
 #pragma unroll
-    for (int kk = 0; kk < BK / TILE_K; ++kk) {
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < k_steps) issue(s, s);
+
+  int stage = 0;
+  for (int ks = 0; ks < k_steps; ++ks) {
+    const bool more = ks + STAGES - 1 < k_steps;
+    // loads of step ks have landed once at most the younger STAGES-2 steps' loads are outstanding
+    if (more) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();  // everyone's part of step ks is in LDS; everyone left step ks-1's buffer
+    if (more) issue(stage == 0 ? STAGES - 1 : stage - 1, ks + STAGES - 1);
+    const u32x4* sa = lds + stage * (A_CHUNKS + B_CHUNKS);
+    const u32x4* sb = sa + A_CHUNKS;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
       u32x4 fa[FM], fb[FN];
 #pragma unroll
       for (int i = 0; i < FM; ++i) {
         const int r = wm * WTM + i * 32 + col;
-        fa[i] = lds_a[buf][r * 8 + ((kk * 2 + half) ^ ((r >> 1) & 7))];
+        fa[i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
       }
 #pragma unroll
-      for (int j = 0; j < FN; ++j) fb[j] = lds_b[buf][((wn * FN + j) * 4 + kk) * 64 + lane];
+      for (int j = 0; j < FN; ++j) fb[j] = sb[((wn * FN + j) * KK + kk) * 64 + lane];
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[i], fb[j], acc[i][j]);
     }
-    if (ks + 1 < k_steps) store_step(buf ^ 1);
-    __syncthreads();
+    stage = stage + 1 == STAGES ? 0 : stage + 1;
   }
 
   // ---- epilogue -----------------------------------------------------------------------
@@ -179,7 +203,7 @@ __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, con
   }
 }
 
-template <bool GATEUP, int BM, int BN, int WM, int WN>
+template <bool GATEUP, int BM, int BN, int BKT, int STAGES, int WM, int WN>
 static void launch_cfg(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
   const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
   c.n_tiles_n = (n_total + BN - 1) / BN;
@@ -187,8 +211,8 @@ static void launch_cfg(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hi
   const long m_tiles_max = n_rows / BM + busy_max;  // sum over experts of ceil(rows/BM) is at most this
   const long tiles = m_tiles_max * c.n_tiles_n;
   c.grid_padded = (int)((tiles + 7) / 8 * 8);
-  hipLaunchKernelGGL((ffn_tiled_kernel<GATEUP, BM, BN, WM, WN>), dim3((unsigned)c.grid_padded), dim3(64 * WM * WN), 0, s,
-                     c, in, out);
+  hipLaunchKernelGGL((ffn_tiled_kernel<GATEUP, BM, BN, BKT, STAGES, WM, WN>), dim3((unsigned)c.grid_padded),
+                     dim3(64 * WM * WN), 0, s, c, in, out);
 }
 
 int launch_ffn_tiled(const FfnArgs& a) {
@@ -201,11 +225,11 @@ int launch_ffn_tiled(const FfnArgs& a) {
   bf16_t* o = (bf16_t*)a.o_perm;
   const int avg_rows = a.n_rows / std::min(d.n_experts, std::max(1, a.n_rows));
   probe_before(a.stream);
-  if (avg_rows >= 192) launch_cfg<true, 256, 256, 2, 4>(c, a.n_rows, x, h, a.stream);
-  else launch_cfg<true, 128, 256, 2, 4>(c, a.n_rows, x, h, a.stream);
+  if (avg_rows >= 192) launch_cfg<true, 256, 256, 64, 2, 2, 4>(c, a.n_rows, x, h, a.stream);
+  else launch_cfg<true, 128, 256, 64, 3, 2, 4>(c, a.n_rows, x, h, a.stream);
   probe_after(a.stream);
-  if (avg_rows >= 192) launch_cfg<false, 256, 256, 2, 4>(c, a.n_rows, h, o, a.stream);
-  else launch_cfg<false, 128, 256, 2, 4>(c, a.n_rows, h, o, a.stream);
+  if (avg_rows >= 192) launch_cfg<false, 256, 256, 64, 2, 2, 4>(c, a.n_rows, h, o, a.stream);
+  else launch_cfg<false, 128, 256, 64, 3, 2, 4>(c, a.n_rows, h, o, a.stream);
   HMOE_HIP(hipGetLastError());
   return HMOE_OK;
 }
