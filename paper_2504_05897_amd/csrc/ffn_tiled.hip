@@ -23,6 +23,8 @@
 //     its odd fragments the matching up columns: SwiGLU is applied to registers.
 //   * Tiles are numbered expert-major, then n-tile, then m-tile, and block ids are dealt to the
 //     8 XCDs in contiguous ranges so that blocks sharing a weight panel share an L2.
+#include <stdlib.h>
+
 #include <algorithm>
 
 #include "common.h"
@@ -128,15 +130,25 @@ __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, con
     const int grp = group0 + g < n_groups ? group0 + g : 0;
     b_src[i] = w + ((size_t)grp * kt16) * 64 + within;
   }
-  auto issue = [&](int stage, int kstep) {
+  // The LPS copies of one K step are issued in KK pieces, one piece in front of each MFMA group, so
+  // that the vector-memory queue never holds more than a couple of copies per wave.
+  auto issue_piece = [&](int stage, int kstep, int piece) {
     const uint32_t base = lds0 + (uint32_t)stage * (A_CHUNKS + B_CHUNKS) * 16;
 #pragma unroll
-    for (int i = 0; i < A_OPS; ++i)
-      load_to_lds_16(a_src[i] + (size_t)kstep * CPR, base + (uint32_t)((i * NWAVES + wave) * 64) * 16);
+    for (int op = 0; op < LPS; ++op) {
+      if (op < piece * LPS / KK || op >= (piece + 1) * LPS / KK) continue;
+      if (op < A_OPS) {
+        load_to_lds_16(a_src[op] + (size_t)kstep * CPR, base + (uint32_t)((op * NWAVES + wave) * 64) * 16);
+      } else {
+        const int i = op - A_OPS;
+        load_to_lds_16(b_src[i] + (size_t)kstep * (KK * 64),
+                       base + (uint32_t)(A_CHUNKS + (i * NWAVES + wave) * 64) * 16);
+      }
+    }
+  };
+  auto issue = [&](int stage, int kstep) {
 #pragma unroll
-    for (int i = 0; i < B_OPS; ++i)
-      load_to_lds_16(b_src[i] + (size_t)kstep * (KK * 64),
-                     base + (uint32_t)(A_CHUNKS + (i * NWAVES + wave) * 64) * 16);
+    for (int p = 0; p < KK; ++p) issue_piece(stage, kstep, p);
   };
 
   f32x16_t acc[FM][FN];
@@ -146,35 +158,77 @@ __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, con
     for (int j = 0; j < FN; ++j) acc[i][j] = f32x16_t{0};
 
   const int k_steps = K / BKT;
+  static_assert(KK % 2 == 0, "fragment double buffering assumes an even number of k-substeps");
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
     if (s < k_steps) issue(s, s);
 
-  int stage = 0;
-  for (int ks = 0; ks < k_steps; ++ks) {
-    const bool more = ks + STAGES - 1 < k_steps;
-    // loads of step ks have landed once at most the younger STAGES-2 steps' loads are outstanding
-    if (more) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();  // everyone's part of step ks is in LDS; everyone left step ks-1's buffer
-    if (more) issue(stage == 0 ? STAGES - 1 : stage - 1, ks + STAGES - 1);
+  // Fragments are double buffered in registers: the LDS reads of substep kk+1 are issued before the
+  // MFMAs of substep kk, across K steps too (the barrier that opens step ks+1 sits before the last
+  // MFMA group of step ks).
+  // A wave whose rows all lie past the end of the expert (ragged last m-tile) neither reads
+  // fragments nor multiplies; it still takes part in the copies and barriers.
+  const bool live = m_rows - m0 - wm * WTM > 0;
+  u32x4 fa[2][FM], fb[2][FN];
+  auto read_frags = [&](int buf, int stage, int kk) {
     const u32x4* sa = lds + stage * (A_CHUNKS + B_CHUNKS);
     const u32x4* sb = sa + A_CHUNKS;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      u32x4 fa[FM], fb[FN];
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const int r = wm * WTM + i * 32 + col;
-        fa[i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
-      }
-#pragma unroll
-      for (int j = 0; j < FN; ++j) fb[j] = sb[((wn * FN + j) * KK + kk) * 64 + lane];
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[i], fb[j], acc[i][j]);
+    for (int i = 0; i < FM; ++i) {
+      const int r = wm * WTM + i * 32 + col;
+      if (live) fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
     }
-    stage = stage + 1 == STAGES ? 0 : stage + 1;
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+      if (live) fb[buf][j] = sb[((wn * FN + j) * KK + kk) * 64 + lane];
+  };
+  auto mfma_frags = [&](int buf) {
+    if (!live) return;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j]);
+  };
+
+  // open step 0: its loads have landed once only the younger STAGES-2 groups are outstanding
+  if (STAGES - 1 <= k_steps) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+  if (STAGES - 1 < k_steps) issue(STAGES - 1, STAGES - 1);   // the last ring slot is still untouched
+  read_frags(0, 0, 0);
+
+  int stage = 0;
+  bool pending = false;   // a K step's copies are partly issued
+  int pend_stage = 0, pend_step = 0;
+  for (int ks = 0; ks < k_steps; ++ks) {
+#pragma unroll
+    for (int kk = 0; kk < KK - 1; ++kk) {
+      if (STAGES >= 3 && pending) issue_piece(pend_stage, pend_step, kk + 1);
+      read_frags((kk + 1) & 1, stage, kk + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_frags(kk & 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    const int next_stage = stage + 1 == STAGES ? 0 : stage + 1;
+    pending = false;
+    if (ks + 1 < k_steps) {
+      // open step ks+1.  Every wave has finished reading this step's buffer (its last fragments are
+      // in registers), so after the barrier that buffer takes the loads of step ks+STAGES.
+      if (ks + STAGES <= k_steps) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragment reads are in registers
+      __builtin_amdgcn_s_barrier();
+      pending = ks + STAGES < k_steps;
+      pend_stage = stage;
+      pend_step = ks + STAGES;
+      if (pending) {
+        if (STAGES >= 3) issue_piece(pend_stage, pend_step, 0);
+        else issue(pend_stage, pend_step);   // two stages: the data is needed one step from now
+      }
+      read_frags(0, next_stage, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mfma_frags((KK - 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    stage = next_stage;
   }
 
   // ---- epilogue -----------------------------------------------------------------------
@@ -215,6 +269,30 @@ static void launch_cfg(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hi
                      dim3(64 * WM * WN), 0, s, c, in, out);
 }
 
+// Tile shapes built into the library.  hmoe picks one from the average rows per expert; the
+// environment variable HMOE_TILED_VARIANT (an index into this table) overrides the choice for
+// tuning runs.
+typedef void (*tiled_launch_fn)(TiledCtx, int, const bf16_t*, bf16_t*, hipStream_t);
+struct TiledVariant {
+  const char* name;
+  tiled_launch_fn gate_up, down;
+};
+#define HMOE_TILED_VARIANT(BM, BN, BKT, ST, WM, WN) \
+  { #BM "x" #BN "x" #BKT " s" #ST " w" #WM "x" #WN, launch_cfg<true, BM, BN, BKT, ST, WM, WN>, \
+    launch_cfg<false, BM, BN, BKT, ST, WM, WN> }
+static const TiledVariant kVariants[] = {
+    HMOE_TILED_VARIANT(256, 256, 64, 2, 2, 4),  // 0: 8 waves, 128x64 per wave
+    HMOE_TILED_VARIANT(128, 256, 64, 3, 2, 4),  // 1: 8 waves, 64x64 per wave, 3 stages
+    HMOE_TILED_VARIANT(256, 256, 32, 4, 2, 4),  // 2: as 0 with 4 stages of K 32
+    HMOE_TILED_VARIANT(256, 128, 64, 3, 4, 2),  // 3: 8 waves, 64x64 per wave
+    HMOE_TILED_VARIANT(128, 128, 64, 4, 2, 2),  // 4: 4 waves, 64x64 per wave, 4 stages
+    HMOE_TILED_VARIANT(256, 256, 64, 2, 2, 2),  // 5: 4 waves, 128x128 per wave
+    HMOE_TILED_VARIANT(256, 256, 64, 2, 4, 2),  // 6: 8 waves, 64x128 per wave
+    HMOE_TILED_VARIANT(256, 256, 32, 5, 2, 4),  // 7: as 2 with 5 stages (all of LDS)
+    HMOE_TILED_VARIANT(256, 256, 32, 4, 4, 2),  // 8: as 2, 64x128 per wave
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
 int launch_ffn_tiled(const FfnArgs& a) {
   const hmoe_layer_desc& d = *a.desc;
   if (d.dtype != HMOE_BF16) return HMOE_ERR_UNSUPPORTED;
@@ -223,13 +301,22 @@ int launch_ffn_tiled(const FfnArgs& a) {
   const bf16_t* x = (const bf16_t*)a.x_perm;
   bf16_t* h = (bf16_t*)a.h;
   bf16_t* o = (bf16_t*)a.o_perm;
+  // Tile choice (measured on the workload shapes): many rows per expert -> 256x256 tiles, which read
+  // the least LDS per flop; few rows per expert -> 128-row tiles with a 3-deep ring, which keep more
+  // weight bytes in flight.  When 256x256 would give fewer tiles than CUs (one long shared expert,
+  // small N) the 128-row tile doubles the block count.
   const int avg_rows = a.n_rows / std::min(d.n_experts, std::max(1, a.n_rows));
+  int v_gate_up = avg_rows >= 192 ? 2 : 1, v_down = v_gate_up;
+  const long big_tiles_down = ((long)a.n_rows / 256 + 1) * ((d.hidden + 255) / 256);
+  if (v_down != 1 && big_tiles_down < 256) v_down = 1;
+  if (const char* env = getenv("HMOE_TILED_VARIANT")) {
+    const int want = atoi(env);
+    if (want >= 0 && want < kNumVariants) v_gate_up = v_down = want;
+  }
   probe_before(a.stream);
-  if (avg_rows >= 192) launch_cfg<true, 256, 256, 64, 2, 2, 4>(c, a.n_rows, x, h, a.stream);
-  else launch_cfg<true, 128, 256, 64, 3, 2, 4>(c, a.n_rows, x, h, a.stream);
+  kVariants[v_gate_up].gate_up(c, a.n_rows, x, h, a.stream);
   probe_after(a.stream);
-  if (avg_rows >= 192) launch_cfg<false, 256, 256, 64, 2, 2, 4>(c, a.n_rows, h, o, a.stream);
-  else launch_cfg<false, 128, 256, 64, 3, 2, 4>(c, a.n_rows, h, o, a.stream);
+  kVariants[v_down].down(c, a.n_rows, h, o, a.stream);
   HMOE_HIP(hipGetLastError());
   return HMOE_OK;
 }
