@@ -3,13 +3,21 @@
 //
 // With a handful of rows per expert the expert FFN is bound by reading its weights (the paper
 // observes GPU expert time flat in the workload at small batch, Section III / Fig. 3(f)), so the
-// kernel is organised around the weight stream: a block owns one 32-row group of one matrix of
-// one expert (for gate/up: the matching gate and up groups), its NW waves split the K range, and
-// each wave issues U consecutive 1 KiB tile loads (one fully coalesced 16-byte load per lane,
-// already in 32x32x16 bf16 MFMA operand order thanks to the packed slot layout) before it
-// multiplies.  Tokens ride along as the other MFMA operand (up to 32 rows, zero padded), read
-// from the L1/L2-resident activation rows.  Partial sums of the waves meet in LDS; wave 0 applies
-// SwiGLU / rounds and stores.
+// kernel is organised around the weight stream:
+//   * a block owns `gpb` consecutive 32-row groups of one matrix of one expert (for gate/up: the
+//     matching gate and up groups); its NW waves split K, every wave walks its K range of group
+//     after group as one long stream of 1 KiB tiles;
+//   * a tile is one fully coalesced 16-byte non-temporal load per lane and is already in 32x32x16
+//     bf16 MFMA operand order (packed slot layout), so it goes from HBM to the matrix core through
+//     registers only; two register sets of U tiles alternate, so U tiles per matrix are always in
+//     flight per wave, across group boundaries too;
+//   * tokens ride along as the other MFMA operand (up to MR rows, zero padded), read from the
+//     L1/L2-resident activation rows;
+//   * at the end of a group the waves' partial sums meet in LDS (double buffered, one barrier per
+//     group); wave 0 applies SwiGLU / rounds and stores.
+#include <stdio.h>
+#include <stdlib.h>
+
 #include <algorithm>
 
 #include "common.h"
@@ -23,6 +31,7 @@ struct SkinnyCtx {
   size_t slot_bytes;
   ActiveMask active;
   int n_experts, hidden, ffn;
+  int gpb;  // 32-row groups per block
 };
 
 // id of the `want`-th expert (ascending) that is active, resident and has rows; -1 if fewer
@@ -43,13 +52,14 @@ __device__ __forceinline__ int nth_busy_expert(const SkinnyCtx& c, int want, int
 }
 
 // GATEUP: in = x_perm [A, H], out = h [A, F];  else: in = h [A, F], out = o_perm [A, H].
-// NW waves per block, MR = rows kept per pass (8 or 32), U = tiles in flight per wave and matrix.
+// NW waves per block, MR = rows kept per pass (8 or 32), U = tiles per register set and matrix.
 template <bool GATEUP, int NW, int MR, int U>
 __global__ __launch_bounds__(64 * NW) void ffn_skinny_kernel(SkinnyCtx c, const bf16_t* __restrict__ in,
                                                               bf16_t* __restrict__ out) {
   constexpr int NMAT = GATEUP ? 2 : 1;
   constexpr int RR = MR == 8 ? 4 : 16;  // accumulator registers that can hold valid rows
-  __shared__ float red[(NW - 1) * NMAT * RR * 64];
+  constexpr int RED = (NW > 1 ? NW - 1 : 1) * NMAT * RR * 64;
+  __shared__ float red[2][RED];
 
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int e = nth_busy_expert(c, blockIdx.y, lane);
@@ -58,101 +68,153 @@ __global__ __launch_bounds__(64 * NW) void ffn_skinny_kernel(SkinnyCtx c, const 
   const int K = GATEUP ? c.hidden : c.ffn;        // reduction length
   const int n_out = GATEUP ? c.ffn : c.hidden;    // row length of `out`
   const int kt = K / TILE_K;
+  const int g_begin = blockIdx.x * c.gpb, g_end = min(g_begin + c.gpb, n_out / TILE_N);
+  if (g_begin >= g_end) return;
   const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
-  // this block's 32-row group(s)
-  const u32x4* w0;
-  const u32x4* w1 = nullptr;
-  if (GATEUP) {
-    w0 = (const u32x4*)slot + (size_t)(2 * blockIdx.x) * kt * 64;
-    w1 = w0 + (size_t)kt * 64;
-  } else {
-    w0 = (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden) + (size_t)blockIdx.x * kt * 64;
-  }
-  // this wave's share of the K tiles
-  const int per_wave = (kt + NW - 1) / NW;
-  const int kb0 = min(wave * per_wave, kt), kb1 = min(kb0 + per_wave, kt);
+  const u32x4* wbase = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
+  const size_t group_stride = (size_t)kt * 64 * NMAT;  // u32x4 per group (gate/up: the pair)
+  // this wave's share of the K tiles, in batches of U
+  const int per_wave = ((kt + NW - 1) / NW + U - 1) / U * U;
+  const int bpg = per_wave / U;                    // batches per group
+  const int kb_wave = wave * per_wave;
   const int half = lane / 32, col = lane % 32;
+  const int n_batches = (g_end - g_begin) * bpg;
 
   for (int row0 = row_first; row0 < row_end; row0 += MR) {
     const int rows = min(MR, row_end - row0);
     const bool has_row = col < rows;
     const u32x4* xin = (const u32x4*)(in + (size_t)(row0 + (has_row ? col : 0)) * K) + half;
-    f32x16_t acc0 = {0}, acc1 = {0};
-    for (int kb = kb0; kb < kb1; kb += U) {
-      u32x4 wa[U], wb[U], xa[U];
+
+    u32x4 wa[2][U], wb[2][U], xa[2][U];
+    int load_g = g_begin, load_j = 0;  // cursor of the next batch to load
+    auto load_batch = [&](int set, bool live) {
+      const u32x4* w0 = wbase + (size_t)load_g * group_stride;
+      const int kb = kb_wave + load_j * U;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const bool in_range = kb + u < kb1;
+        const bool ok = live && kb + u < kt;
         const size_t t = (size_t)(kb + u) * 64 + lane;
-        wa[u] = in_range ? __builtin_nontemporal_load(w0 + t) : u32x4{0, 0, 0, 0};
-        if (GATEUP) wb[u] = in_range ? __builtin_nontemporal_load(w1 + t) : u32x4{0, 0, 0, 0};
-        xa[u] = (in_range && has_row) ? xin[(size_t)(kb + u) * 2] : u32x4{0, 0, 0, 0};
+        wa[set][u] = ok ? __builtin_nontemporal_load(w0 + t) : u32x4{0, 0, 0, 0};
+        if (GATEUP) wb[set][u] = ok ? __builtin_nontemporal_load(w0 + (size_t)kt * 64 + t) : u32x4{0, 0, 0, 0};
+        xa[set][u] = (ok && has_row) ? xin[(size_t)(kb + u) * 2] : u32x4{0, 0, 0, 0};
       }
+      if (++load_j == bpg) { load_j = 0; ++load_g; }
+    };
+
+    f32x16_t acc0 = {0}, acc1 = {0};
+    int cur_g = g_begin, cur_j = 0;  // cursor of the batch being multiplied
+    auto compute_batch = [&](int set) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        acc0 = mfma_32x32x16_bf16(xa[u], wa[u], acc0);
-        if (GATEUP) acc1 = mfma_32x32x16_bf16(xa[u], wb[u], acc1);
+        acc0 = mfma_32x32x16_bf16(xa[set][u], wa[set][u], acc0);
+        if (GATEUP) acc1 = mfma_32x32x16_bf16(xa[set][u], wb[set][u], acc1);
       }
-    }
-    // accumulator register r of lane (half, col) is row 8*(r/4) + 4*half + r%4, output column col
-    if (wave > 0) {
-      float* dst = red + (size_t)(wave - 1) * NMAT * RR * 64;
+      if (++cur_j < bpg) return;
+      // ---- end of a group: cross-wave reduction, epilogue, store --------------------------
+      // accumulator register r of lane (half, col) is row 8*(r/4) + 4*half + r%4, output column col
+      float* area = red[cur_g & 1];
+      if (NW > 1 && wave > 0) {
+        float* dst = area + (size_t)(wave - 1) * NMAT * RR * 64;
 #pragma unroll
-      for (int r = 0; r < RR; ++r) {
-        if ((r / 4) * 8 < rows) {
-          dst[r * 64 + lane] = acc0[r];
-          if (GATEUP) dst[(RR + r) * 64 + lane] = acc1[r];
-        }
-      }
-    }
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll
-      for (int r = 0; r < RR; ++r) {
-        if ((r / 4) * 8 < rows) {
-          float g = acc0[r], u = GATEUP ? acc1[r] : 0.0f;
-          for (int w = 0; w < NW - 1; ++w) {
-            g += red[((size_t)w * NMAT * RR + r) * 64 + lane];
-            if (GATEUP) u += red[((size_t)w * NMAT * RR + RR + r) * 64 + lane];
-          }
-          const int m = (r / 4) * 8 + half * 4 + (r % 4);
-          if (m < rows) {
-            const float v = GATEUP ? silu_f32(g) * u : g;
-            out[(size_t)(row0 + m) * n_out + blockIdx.x * TILE_N + col] = f32_to_bf16(v);
+        for (int r = 0; r < RR; ++r) {
+          if ((r / 4) * 8 < rows) {
+            dst[r * 64 + lane] = acc0[r];
+            if (GATEUP) dst[(RR + r) * 64 + lane] = acc1[r];
           }
         }
       }
+      if (NW > 1) __syncthreads();
+      if (wave == 0) {
+#pragma unroll
+        for (int r = 0; r < RR; ++r) {
+          if ((r / 4) * 8 < rows) {
+            float g = acc0[r], u = GATEUP ? acc1[r] : 0.0f;
+            for (int w = 0; w < NW - 1; ++w) {
+              g += area[((size_t)w * NMAT * RR + r) * 64 + lane];
+              if (GATEUP) u += area[((size_t)w * NMAT * RR + RR + r) * 64 + lane];
+            }
+            const int m = (r / 4) * 8 + half * 4 + (r % 4);
+            if (m < rows) {
+              const float v = GATEUP ? silu_f32(g) * u : g;
+              out[(size_t)(row0 + m) * n_out + cur_g * TILE_N + col] = f32_to_bf16(v);
+            }
+          }
+        }
+      }
+      acc0 = f32x16_t{0};
+      acc1 = f32x16_t{0};
+      cur_j = 0;
+      ++cur_g;
+    };
+
+    load_batch(0, true);
+    for (int b = 0; b < n_batches; b += 2) {
+      load_batch(1, b + 1 < n_batches);
+      compute_batch(0);
+      load_batch(0, b + 2 < n_batches);
+      if (b + 1 < n_batches) compute_batch(1);
     }
-    __syncthreads();
+    if (NW > 1) __syncthreads();  // the reduction areas are reused by the next row pass
   }
 }
 
-template <bool GATEUP, int NW, int MR>
-static void launch_one(const SkinnyCtx& c, int groups, int busy_max, const bf16_t* in, bf16_t* out, hipStream_t s) {
-  hipLaunchKernelGGL((ffn_skinny_kernel<GATEUP, NW, MR, 4>), dim3((unsigned)groups, (unsigned)busy_max), dim3(64 * NW), 0,
-                     s, c, in, out);
+typedef void (*skinny_launch_fn)(const SkinnyCtx&, dim3, const bf16_t*, bf16_t*, hipStream_t);
+template <bool GATEUP, int NW, int MR, int U>
+static void launch_one(const SkinnyCtx& c, dim3 grid, const bf16_t* in, bf16_t* out, hipStream_t s) {
+  hipLaunchKernelGGL((ffn_skinny_kernel<GATEUP, NW, MR, U>), grid, dim3(64 * NW), 0, s, c, in, out);
 }
 
+// K-split widths and tile batch sizes built into the library
+struct SkinnyShape { int nw, u; };
+static const SkinnyShape kShapes[] = {{1, 4}, {2, 4}, {4, 4}, {8, 4}, {8, 2}, {16, 2}};
+constexpr int kNumShapes = sizeof(kShapes) / sizeof(kShapes[0]);
+template <bool GATEUP, int MR>
+static skinny_launch_fn pick(int shape) {
+  if constexpr (MR == 32) {
+    // up to 32 rows: the reduction area grows with the rows, so at most 4 waves split K
+    switch (kShapes[shape].nw) {
+      case 1: return launch_one<GATEUP, 1, 32, 4>;
+      case 2: return launch_one<GATEUP, 2, 32, 4>;
+      default: return launch_one<GATEUP, 4, 32, 4>;
+    }
+  } else {
+    switch (shape) {
+      case 0: return launch_one<GATEUP, 1, MR, 4>;
+      case 1: return launch_one<GATEUP, 2, MR, 4>;
+      case 2: return launch_one<GATEUP, 4, MR, 4>;
+      case 3: return launch_one<GATEUP, 8, MR, 4>;
+      case 4: return launch_one<GATEUP, 8, MR, 2>;
+      default: return launch_one<GATEUP, 16, MR, 2>;
+    }
+  }
+}
+
+// Work split for one of the two GEMVs: n_groups 32-row groups per expert, at most busy_max experts
+// with rows.  Measured on the decode shapes, 8 waves per block with 2 tiles per register set is at or
+// near the best everywhere; very few (expert, group) tasks get 16 waves, very many get two groups
+// per block.
 template <bool GATEUP>
-static void launch_stage(const SkinnyCtx& c, int groups, int busy_max, int max_rows, int kt, const bf16_t* in,
-                         bf16_t* out, hipStream_t s) {
-  if (max_rows > 8) {
-    launch_one<GATEUP, 4, 32>(c, groups, busy_max, in, out, s);
-    return;
+static void launch_stage(SkinnyCtx c, int n_groups, int busy_max, int max_rows, int kt, const bf16_t* in, bf16_t* out,
+                         hipStream_t s) {
+  const long tasks = (long)n_groups * busy_max;
+  int shape = tasks < 200 ? 5 : 4;
+  int gpb = tasks >= 2048 ? 2 : 1;
+  if (const char* env = getenv("HMOE_SKINNY")) {  // tuning override: "<shape>,<groups per block>"
+    int es = -1, eg = -1;
+    if (sscanf(env, "%d,%d", &es, &eg) >= 1 && es >= 0 && es < kNumShapes) shape = es;
+    if (eg > 0) gpb = eg;
   }
-  // enough waves to keep HBM busy (about 16 per CU), but at least 4 K tiles per wave
-  int nw = 4;
-  while (nw < 16 && (long)groups * busy_max * nw < 4096 && kt / (nw * 2) >= 4) nw *= 2;
-  if (nw == 4) launch_one<GATEUP, 4, 8>(c, groups, busy_max, in, out, s);
-  else if (nw == 8) launch_one<GATEUP, 8, 8>(c, groups, busy_max, in, out, s);
-  else launch_one<GATEUP, 16, 8>(c, groups, busy_max, in, out, s);
+  (void)kt;
+  c.gpb = std::min(gpb, n_groups);
+  const dim3 grid((unsigned)((n_groups + c.gpb - 1) / c.gpb), (unsigned)busy_max);
+  (max_rows > 8 ? pick<GATEUP, 32>(shape) : pick<GATEUP, 8>(shape))(c, grid, in, out, s);
 }
 
 int launch_ffn_skinny(const FfnArgs& a) {
   const hmoe_layer_desc& d = *a.desc;
   if (d.dtype != HMOE_BF16) return HMOE_ERR_UNSUPPORTED;
   if (a.n_rows == 0) return HMOE_OK;
-  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn};
+  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1};
   const int busy_max = std::min(d.n_experts, a.n_rows);     // every busy expert has at least one row
   const int max_rows = std::max(1, a.n_rows / d.top_k);     // a token names an expert at most once
   probe_before(a.stream);

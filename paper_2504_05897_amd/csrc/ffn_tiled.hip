@@ -54,6 +54,13 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
+// Workgroup barrier that the compiler may not move LDS accesses across.  (No fence instruction:
+// the waits that make the data visible are issued explicitly by the caller.)
+__device__ __forceinline__ void block_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
 
 template <bool GATEUP, int BM, int BN, int BKT, int STAGES, int WM, int WN>
 __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, const bf16_t* __restrict__ in,
@@ -192,7 +199,7 @@ __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, con
 
   // open step 0: its loads have landed once only the younger STAGES-2 groups are outstanding
   if (STAGES - 1 <= k_steps) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
-  __builtin_amdgcn_s_barrier();
+  block_barrier();
   if (STAGES - 1 < k_steps) issue(STAGES - 1, STAGES - 1);   // the last ring slot is still untouched
   read_frags(0, 0, 0);
 
@@ -215,7 +222,7 @@ __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, con
       // in registers), so after the barrier that buffer takes the loads of step ks+STAGES.
       if (ks + STAGES <= k_steps) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
       __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragment reads are in registers
-      __builtin_amdgcn_s_barrier();
+      block_barrier();
       pending = ks + STAGES < k_steps;
       pend_stage = stage;
       pend_step = ks + STAGES;

@@ -1,0 +1,129 @@
+"""Parity at the full sizes of the five workloads, in the launch configuration the benchmark
+times (AUTO kernel choice, real cache sizes with staging from pinned host memory).
+
+Integer results (top-k ids, offsets, permutation, slot map) are compared in full and bit for bit.
+The layer output is compared on every token for small batches and on a seeded sample of tokens
+for prefill batches (tokens are independent in Eq. (1), so the oracle evaluates the sampled ones
+one by one); the measure is max|y - y_ref| / max|y_ref| over the compared tokens, 2e-2 for bf16
+and 1e-4 for fp32."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import moe_oracle as orc
+from hmoe_testlib import TOL, build_layer, max_rel_err, oracle_layer, to_device, to_host_f32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hm():
+    import paper_2504_05897_amd as hm
+    return hm
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def run_and_check(hm, layer, base, shape, seed, T, n_sample, model=None):
+    """One forward of `layer` on fresh seeded activations; returns the error on the sample."""
+    lay = wl.make_layer(shape, seed, T, with_weights=False)
+    lay.experts, lay.shared, lay.w_router = base.experts, base.shared, base.w_router
+    x = to_device(lay.x)
+    if lay.logits is None:
+        hm.hmoe_router_logits(layer.desc, x, layer.w_router, T, layer.logits)
+        logits = layer.logits[:T].cpu().numpy()
+        ref_lg = orc.router_logits(wl.as_f64(lay.x), wl.as_f64(lay.w_router))
+        assert np.abs(logits - ref_lg).max() <= 1e-5 * np.abs(ref_lg).max()
+        y = layer.forward(x, layer.logits[:T])
+    else:
+        logits = lay.logits
+        y = layer.forward(x, to_device(logits))
+    torch.cuda.synchronize()
+    K, E = shape.top_k, shape.n_experts
+    ridx, rw = orc.route(logits, K)
+    ro, rp, ri = orc.permute(ridx, E)
+    assert np.array_equal(layer.topk_idx[:T].cpu().numpy(), ridx)
+    np.testing.assert_allclose(layer.topk_w[:T].cpu().numpy(), rw, rtol=2e-6, atol=1e-7)
+    assert np.array_equal(layer.offsets.cpu().numpy(), ro)
+    assert np.array_equal(layer.perm[:T * K].cpu().numpy(), rp)
+    assert np.array_equal(layer.inv_perm[:T * K].cpu().numpy(), ri)
+    if model is not None:
+        plan = model.serve(np.unique(ridx).tolist())
+        assert layer.slot_map() == model.slot_of
+        assert np.array_equal(layer.slot_of.cpu().numpy(), np.array(model.slot_of, np.int32))
+        wave = layer.last_plan[0]
+        for (e, s, w, v) in plan:
+            assert wave[e] == w
+    if n_sample >= T:
+        sub = np.arange(T)
+    else:
+        sub = np.sort(np.random.default_rng(seed).choice(T, n_sample, replace=False))
+    y_ref = oracle_layer(lay, logits, token_subset=sub)
+    return max_rel_err(to_host_f32(y)[sub], y_ref)
+
+
+def test_workload1_toy_fp32(hm):
+    say("workload 1: toy fp32, seed 0")
+    base = wl.make_layer(wl.TOY, 0, 16)
+    layer = build_layer(hm, base)
+    err = run_and_check(hm, layer, base, wl.TOY, 0, 16, 16)
+    say("  err", err)
+    layer.close()
+    assert err < TOL[wl.F32]
+
+
+def test_workload2_mixtral(hm):
+    say("workload 2: mixtral, 4 of 8 experts cached")
+    shape = wl.MIXTRAL
+    base = wl.make_layer(shape, 1, 1, threads=16)
+    layer = build_layer(hm, base, max_tokens=512)
+    model = orc.ExpertCacheModel(shape.n_experts, shape.n_slots)
+    for i, (T, n_sample) in enumerate([(1, 1), (1, 1), (8, 8), (1, 1), (512, 24), (8, 8)]):
+        err = run_and_check(hm, layer, base, shape, 200 + i, T, n_sample, model)
+        say("  T", T, "waves", layer.last_plan[3], "err", err)
+        assert err < TOL[wl.BF16]
+    layer.close()
+
+
+def test_workload3_dsv2lite(hm):
+    say("workload 3: deepseek-v2-lite style, Zipf logits, 32 of 64 experts cached")
+    shape = wl.DSV2LITE
+    base = wl.make_layer(shape, 2, 1, threads=16)
+    layer = build_layer(hm, base, max_tokens=1024)
+    model = orc.ExpertCacheModel(shape.n_experts, shape.n_slots)
+    for i, (T, n_sample) in enumerate([(1, 1), (1, 1), (1024, 96), (1, 1)]):
+        err = run_and_check(hm, layer, base, shape, 300 + i, T, n_sample, model)
+        say("  T", T, "waves", layer.last_plan[3], "err", err)
+        assert err < TOL[wl.BF16]
+    layer.close()
+
+
+def test_workload4_qwen2moe(hm):
+    say("workload 4: qwen2-moe style, hot expert 0, 48 of 64 experts cached")
+    shape = wl.QWEN2MOE
+    base = wl.make_layer(shape, 3, 1, threads=16)
+    layer = build_layer(hm, base, max_tokens=2048)
+    model = orc.ExpertCacheModel(shape.n_experts, shape.n_slots)
+    for i, (T, n_sample) in enumerate([(4, 4), (2048, 64), (4, 4)]):
+        err = run_and_check(hm, layer, base, shape, 400 + i, T, n_sample, model)
+        say("  T", T, "waves", layer.last_plan[3], "err", err)
+        assert err < TOL[wl.BF16]
+    layer.close()
+
+
+def test_workload5_stress_layers(hm):
+    say("workload 5: 16384 tokens, all experts resident, two of the stacked layers")
+    shape = wl.STRESS
+    for li in (0, 26):
+        base = wl.make_layer(shape, 5000 + li, 1, threads=16)
+        layer = build_layer(hm, base, max_tokens=16384)
+        err = run_and_check(hm, layer, base, shape, 5000 + li, 16384, 64)
+        say("  layer", li, "err", err)
+        layer.close()
+        assert err < TOL[wl.BF16]
