@@ -47,6 +47,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a captured HIP graph")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (a kernel of known traffic, to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported"
@@ -73,6 +76,14 @@ def main() -> int:
         if a.dtype == np.uint16:
             return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
         return torch.from_numpy(a).to(dev)
+
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- layers: all experts resident for the kernel-only figure ------------------------------
     t0 = time.time()
@@ -181,6 +192,10 @@ def main() -> int:
     else:
         roofline = {"bound": "hbm", "achieved": main["gate_up_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": main["gate_up_hbm_frac"], "traffic": None}
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):   # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs (see profiles/)
+        with open(traffic_file) as fh:
+            roofline["traffic"] = json.load(fh).get("%s/%s" % (args.workload, main_name))
     roofline["kernel"] = "ffn gate/up (routed experts), phase " + main_name
     roofline["kernel_ms"] = main["gate_up_kernel_ms"]
 
@@ -222,7 +237,7 @@ def main() -> int:
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as orc
         lay0 = host_layers[0]
-        sample = min(main_T, {"toy": 16, "mixtral": 64, "dsv2lite": 256, "qwen2moe": 64, "stress": 256}[args.workload])
+        sample = min(main_T, {"toy": 16, "mixtral": 512, "dsv2lite": 1024, "qwen2moe": 256, "stress": 512}[args.workload])
         sub = np.arange(sample) * (main_T // sample)
         if lay0.logits is None:
             logits = orc.router_logits(wl.as_f64(lay0.x[:main_T]), wl.as_f64(lay0.w_router))
