@@ -276,6 +276,211 @@ static void launch_cfg(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hi
                      dim3(64 * WM * WN), 0, s, c, in, out);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Second kernel family: the weights bypass LDS.
+//
+// All NWV waves of a block span the whole BM rows; a wave owns 64 packed weight rows (one gate/up
+// pair, or 64 output columns of the down projection).  Activation tiles still go through the LDS ring
+// (every wave needs all of them); weight tiles are 1 KiB each in MFMA operand order, so each wave
+// streams its own straight from global memory into a ring of DB register slots, DB k-substeps ahead.
+// Compared with the kernel above this removes the LDS fill and the LDS reads of the weight operand
+// (about 40 % of the LDS traffic of a 256x256 tile) and keeps DB KiB per matrix in flight per wave,
+// which is what the weight-streaming shapes need.
+//
+// Every vector-memory operation is issued by hand in a fixed order per k-substep
+//   [FN weight-tile loads for substep s+DB] [this substep's share of the LDS copies for step t+SA-1]
+// so the number of younger operations at each wait is a compile-time constant: N_B for a weight tile,
+// N_A for an activation stage.  In the last steps the same operations are still issued, with the
+// step clamped (their results are never used), which keeps the counts valid.
+__device__ __forceinline__ u32x4 load_stream_16(const void* gptr) {
+  u32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(gptr) : "memory");
+  return v;
+}
+// wait until at most N younger vector-memory operations are outstanding; the operands tie the wait
+// to the registers whose loads it covers, so their uses cannot be scheduled above it
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_regs(u32x4& a, u32x4& b) {
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+
+template <bool GATEUP, int BM, int NWV, int SA>
+__global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const bf16_t* __restrict__ in,
+                                                               bf16_t* __restrict__ out) {
+  constexpr int FN = 2, BN = NWV * 64, FM = BM / 32, BKT = 64, KK = 4, DB = 8;
+  constexpr int CPR = BKT / 8, RP = 256 / (BKT * 2);
+  constexpr int A_CHUNKS = BM * CPR;
+  constexpr int A_OPS = A_CHUNKS / (64 * NWV);
+  static_assert(A_OPS >= 1 && A_OPS * 64 * NWV == A_CHUNKS, "activation tile must split evenly over the waves");
+  static_assert(SA >= 3, "the activation ring needs three stages");
+  constexpr int OPS3 = A_OPS - A_OPS * 3 / KK;  // copies issued in the last substep of a step
+  constexpr int N_B = (DB - 1) * FN + (DB / KK) * A_OPS;
+  constexpr int N_A = (SA - 3) * (KK * FN + A_OPS) + 3 * FN + A_OPS - OPS3;
+  static_assert(N_B <= 63 && N_A <= 63, "vmcnt range");
+  __shared__ u32x4 lds[SA * A_CHUNKS];
+
+  const int per_xcd = c.grid_padded / 8;
+  const int tile_id = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  int e = -1, row_first = 0, m_rows = 0, mt = 0, nt = 0;
+  {
+    int cum = 0;
+    for (int i = 0; i < c.n_experts; ++i) {
+      const int r0 = c.offsets[i], r1 = c.offsets[i + 1];
+      if (r1 <= r0 || !c.active.test(i) || c.slot_of[i] < 0) continue;
+      const int mts = (r1 - r0 + BM - 1) / BM;
+      const int tiles = mts * c.n_tiles_n;
+      if (tile_id < cum + tiles) {
+        const int within = tile_id - cum;
+        e = i; row_first = r0; m_rows = r1 - r0;
+        nt = within / mts; mt = within % mts;
+        break;
+      }
+      cum += tiles;
+    }
+  }
+  if (e < 0) return;  // uniform over the block
+
+  const int K = GATEUP ? c.hidden : c.ffn;
+  const int n_out = GATEUP ? c.ffn : c.hidden;
+  const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;
+  const int kt16 = K / TILE_K;
+  const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
+  const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
+  const int m0 = mt * BM;
+  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+  const int half = lane / 32, col = lane % 32;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
+
+  const u32x4* a_src[A_OPS];
+#pragma unroll
+  for (int i = 0; i < A_OPS; ++i) {
+    const int ci = (i * NWV + wave) * 64 + lane;
+    const int r = ci / CPR, sl = ci % CPR;
+    const int chunk = sl ^ ((r / RP) % CPR);
+    const int row = m0 + r < m_rows ? m0 + r : m_rows - 1;
+    a_src[i] = (const u32x4*)(in + (size_t)(row_first + row) * K) + chunk;
+  }
+  const u32x4* b_src[FN];
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int g = nt * (BN / TILE_N) + wave * FN + j;
+    b_src[j] = w + ((size_t)(g < n_groups ? g : 0) * kt16) * 64 + lane;
+  }
+  const int k_steps = K / BKT, n_sub = k_steps * KK;
+  auto issue_a_piece = [&](int stage, int kstep, int piece) {
+    const uint32_t base = lds0 + (uint32_t)stage * A_CHUNKS * 16;
+    const size_t koff = (size_t)(kstep < k_steps ? kstep : k_steps - 1) * CPR;
+#pragma unroll
+    for (int op = 0; op < A_OPS; ++op)
+      if (op >= A_OPS * piece / KK && op < A_OPS * (piece + 1) / KK)
+        load_to_lds_16(a_src[op] + koff, base + (uint32_t)((op * NWV + wave) * 64) * 16);
+  };
+
+  f32x16_t acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) acc[i][j] = f32x16_t{0};
+  u32x4 ring[DB][FN];
+  u32x4 fa[2][FM];
+  auto read_a = [&](int buf, int stage, int kk) {
+    const u32x4* sa = lds + stage * A_CHUNKS;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int r = i * 32 + col;
+      fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
+    }
+  };
+
+  // ---- prologue: fill the weight ring and SA-1 activation stages, then wait for all of it ----
+#pragma unroll
+  for (int s = 0; s < DB; ++s)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) ring[s][j] = load_stream_16(b_src[j] + (size_t)(s < n_sub ? s : n_sub - 1) * 64);
+#pragma unroll
+  for (int st = 0; st < SA - 1; ++st)
+#pragma unroll
+    for (int p = 0; p < KK; ++p) issue_a_piece(st, st, p);
+  wait_vmcnt<0>();
+  block_barrier();
+  read_a(0, 0, 0);
+
+  int stage = 0;  // ring stage of step tt
+  for (int t = 0; t < k_steps; t += DB / KK) {
+#pragma unroll
+    for (int h = 0; h < DB / KK; ++h) {
+      const int tt = t + h;
+      if (tt < k_steps) {
+        const int next_stage = stage + 1 == SA ? 0 : stage + 1;
+        const int fill_stage = stage == 0 ? SA - 1 : stage - 1;  // held step tt-1, free since this step opened
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          constexpr int dummy = 0;
+          (void)dummy;
+          if (kk == KK - 1) {
+            // open step tt+1: its activation tile has landed once at most N_A younger operations are out
+            wait_vmcnt<N_A>();
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragments are in registers
+            block_barrier();
+            read_a((kk + 1) & 1, next_stage, 0);
+          } else {
+            read_a((kk + 1) & 1, stage, kk + 1);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          const int sl = h * KK + kk;  // ring slot of substep 4*tt + kk
+          wait_vmcnt_regs<N_B>(ring[sl][0], ring[sl][1]);
+#pragma unroll
+          for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
+          __builtin_amdgcn_sched_barrier(0);
+          const int s_next = tt * KK + kk + DB;
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+            ring[sl][j] = load_stream_16(b_src[j] + (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64);
+          issue_a_piece(fill_stage, tt + SA - 1, kk);
+        }
+        stage = next_stage;
+      }
+    }
+  }
+  wait_vmcnt<0>();  // the clamped tail copies must not outlive the block's LDS
+
+  // ---- epilogue: accumulator register r of lane (half, col) is row 8*(r/4) + 4*half + r%4 ----
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps the accumulator reads from piling up
+      const int m = m0 + i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
+      if (m >= m_rows) continue;
+      bf16_t* orow = out + (size_t)(row_first + m) * n_out;
+      if (GATEUP) {
+        const int f = nt * (BN / 2) + wave * 32 + col;
+        if (f < n_out) orow[f] = f32_to_bf16(silu_f32(acc[i][0][r]) * acc[i][1][r]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const int n = nt * BN + (wave * FN + j) * 32 + col;
+          if (n < n_out) orow[n] = f32_to_bf16(acc[i][j][r]);
+        }
+      }
+    }
+  }
+}
+
+template <bool GATEUP, int BM, int NWV, int SA>
+static void launch_stream(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
+  constexpr int BN = NWV * 64;
+  const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
+  c.n_tiles_n = (n_total + BN - 1) / BN;
+  const int busy_max = std::min(c.n_experts, n_rows);
+  const long tiles = ((long)n_rows / BM + busy_max) * c.n_tiles_n;
+  c.grid_padded = (int)((tiles + 7) / 8 * 8);
+  hipLaunchKernelGGL((ffn_stream_kernel<GATEUP, BM, NWV, SA>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in,
+                     out);
+}
+
 // Tile shapes built into the library.  hmoe picks one from the average rows per expert; the
 // environment variable HMOE_TILED_VARIANT (an index into this table) overrides the choice for
 // tuning runs.
@@ -297,6 +502,8 @@ static const TiledVariant kVariants[] = {
     HMOE_TILED_VARIANT(256, 256, 64, 2, 4, 2),  // 6: 8 waves, 64x128 per wave
     HMOE_TILED_VARIANT(256, 256, 32, 5, 2, 4),  // 7: as 2 with 5 stages (all of LDS)
     HMOE_TILED_VARIANT(256, 256, 32, 4, 4, 2),  // 8: as 2, 64x128 per wave
+    {"stream 128x256 s4", launch_stream<true, 128, 4, 4>, launch_stream<false, 128, 4, 4>},   // 9: weights bypass LDS, 4 waves
+    {"stream 128x512 s4", launch_stream<true, 128, 8, 4>, launch_stream<false, 128, 8, 4>},   // 10: weights bypass LDS, 8 waves
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -308,14 +515,12 @@ int launch_ffn_tiled(const FfnArgs& a) {
   const bf16_t* x = (const bf16_t*)a.x_perm;
   bf16_t* h = (bf16_t*)a.h;
   bf16_t* o = (bf16_t*)a.o_perm;
-  // Tile choice (measured on the workload shapes): many rows per expert -> 256x256 tiles, which read
-  // the least LDS per flop; few rows per expert -> 128-row tiles with a 3-deep ring, which keep more
-  // weight bytes in flight.  When 256x256 would give fewer tiles than CUs (one long shared expert,
-  // small N) the 128-row tile doubles the block count.
-  const int avg_rows = a.n_rows / std::min(d.n_experts, std::max(1, a.n_rows));
-  int v_gate_up = avg_rows >= 192 ? 2 : 1, v_down = v_gate_up;
-  const long big_tiles_down = ((long)a.n_rows / 256 + 1) * ((d.hidden + 255) / 256);
-  if (v_down != 1 && big_tiles_down < 256) v_down = 1;
+  // Kernel choice (measured on the workload shapes): the weight-streaming family wins everywhere, with
+  // 8 waves and a 128x512 tile; when that tile would leave most CUs without a block (down projection
+  // of few, large experts: small N) the 128x256 tile with 4 waves doubles the block count.
+  int v_gate_up = 10, v_down = 10;
+  const long tiles_down = ((long)a.n_rows / 128 + std::min(d.n_experts, a.n_rows)) * ((d.hidden + 511) / 512);
+  if (tiles_down < 256) v_down = 9;
   if (const char* env = getenv("HMOE_TILED_VARIANT")) {
     const int want = atoi(env);
     if (want >= 0 && want < kNumVariants) v_gate_up = v_down = want;
