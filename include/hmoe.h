@@ -128,6 +128,15 @@ int32_t hmoe_permute(const hmoe_layer_desc* desc, const int32_t* topk_idx, int32
                      void* x_perm, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
                      int32_t* h_counts_pinned, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * hmoe_route followed by hmoe_permute (without the row gather; see hmoe_expert_ffn_grouped_gather)
+ * as one call.  For small batches (T*K <= 1024: every decode shape) both run in a single one-block
+ * launch; larger batches run the two calls above.  Arguments and results as in those calls.
+ */
+int32_t hmoe_route_permute(const hmoe_layer_desc* desc, const float* logits, int32_t T, int32_t* topk_idx,
+                           float* topk_w, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
+                           int32_t* h_counts_pinned, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------
  * Expert weights.  An expert is three bias-free matrices (SwiGLU; the paper gives only
  * the sizes, Table II): W_gate [F, H], W_up [F, H], W_down [H, F], row-major.
@@ -209,6 +218,16 @@ int32_t hmoe_expert_ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, 
                                 const int32_t* expert_offsets, int32_t A, const int32_t* h_active,
                                 int32_t n_active, void* o_perm, void* workspace, size_t workspace_bytes,
                                 int32_t path, void* stream);
+
+/*
+ * Same FFN with the row gather of hmoe_permute fused into its first GEMM: sorted row p of the
+ * input is x[perm[p] / K] (x [T, H] un-permuted, perm [A] as written by hmoe_permute), so x_perm
+ * need not be materialised.  Everything else as hmoe_expert_ffn_grouped.
+ */
+int32_t hmoe_expert_ffn_grouped_gather(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x,
+                                       const int32_t* perm, const int32_t* expert_offsets, int32_t A,
+                                       const int32_t* h_active, int32_t n_active, void* o_perm,
+                                       void* workspace, size_t workspace_bytes, int32_t path, void* stream);
 
 /* ------------------------------------------------------------------------------------
  * The sum of Eq. (1) in gather form:

@@ -38,7 +38,8 @@ EXPORTS = [
     "hmoe_permute_workspace_bytes", "hmoe_permute", "hmoe_slot_bytes", "hmoe_pack_expert",
     "hmoe_cache_create", "hmoe_cache_destroy", "hmoe_cache_lookup", "hmoe_cache_occupant",
     "hmoe_cache_evict", "hmoe_cache_pin_slot", "hmoe_cache_stage", "hmoe_cache_plan",
-    "hmoe_ffn_workspace_bytes", "hmoe_expert_ffn_grouped", "hmoe_combine",
+    "hmoe_ffn_workspace_bytes", "hmoe_expert_ffn_grouped", "hmoe_expert_ffn_grouped_gather", "hmoe_route_permute",
+    "hmoe_combine",
     "hmoe_probe_arm", "hmoe_probe_read",
 ]
 
@@ -90,6 +91,8 @@ def _load() -> ctypes.CDLL:
     lib.hmoe_ffn_workspace_bytes.restype = sz
     lib.hmoe_ffn_workspace_bytes.argtypes = [dp, i32]
     lib.hmoe_expert_ffn_grouped.argtypes = [dp, vp, vp, vp, i32, vp, i32, vp, vp, sz, i32, vp]
+    lib.hmoe_expert_ffn_grouped_gather.argtypes = [dp, vp, vp, vp, vp, i32, vp, i32, vp, vp, sz, i32, vp]
+    lib.hmoe_route_permute.argtypes = [dp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.hmoe_combine.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp]
     lib.hmoe_probe_arm.argtypes = [i32]
     lib.hmoe_probe_read.argtypes = [vp, i32, ctypes.POINTER(i32)]
@@ -229,6 +232,22 @@ def hmoe_expert_ffn_grouped(desc, cache, x_perm, expert_offsets, A, h_active, o_
                                         workspace_bytes, path, _stream(stream)), "hmoe_expert_ffn_grouped")
 
 
+def hmoe_expert_ffn_grouped_gather(desc, cache, x, perm, expert_offsets, A, h_active, o_perm, workspace,
+                                   workspace_bytes, path=HMOE_FFN_AUTO, stream=None):
+    act = None if h_active is None else np.ascontiguousarray(h_active, dtype=np.int32)
+    _check(_lib.hmoe_expert_ffn_grouped_gather(ctypes.byref(desc), cache, _ptr(x), _ptr(perm), _ptr(expert_offsets), A,
+                                               _ptr(act), 0 if act is None else int(act.shape[0]), _ptr(o_perm),
+                                               _ptr(workspace), workspace_bytes, path, _stream(stream)),
+           "hmoe_expert_ffn_grouped_gather")
+
+
+def hmoe_route_permute(desc, logits, T, topk_idx, topk_w, expert_offsets, perm, inv_perm, h_counts_pinned, workspace,
+                       workspace_bytes, stream=None):
+    _check(_lib.hmoe_route_permute(ctypes.byref(desc), _ptr(logits), T, _ptr(topk_idx), _ptr(topk_w),
+                                   _ptr(expert_offsets), _ptr(perm), _ptr(inv_perm), _ptr(h_counts_pinned),
+                                   _ptr(workspace), workspace_bytes, _stream(stream)), "hmoe_route_permute")
+
+
 def hmoe_combine(desc, o_perm, inv_perm, topk_w, o_shared, T, y, stream=None):
     _check(_lib.hmoe_combine(ctypes.byref(desc), _ptr(o_perm), _ptr(inv_perm), _ptr(topk_w), _ptr(o_shared), T,
                              _ptr(y), _stream(stream)), "hmoe_combine")
@@ -265,8 +284,10 @@ class MoELayer:
     """
 
     def __init__(self, desc: LayerDesc, experts: Sequence, shared: Sequence = (), w_router=None,
-                 max_tokens: int = 1, device: str = "cuda:0", resident: Optional[Sequence[int]] = None):
+                 max_tokens: int = 1, device: str = "cuda:0", resident: Optional[Sequence[int]] = None,
+                 fused: bool = True):
         self.desc = desc
+        self.fused = fused          # route+permute in one call, gather fused into the FFN, shared expert on a side stream
         self.dev = torch.device(device)
         self.dt = torch_dtype(desc)
         E, S, K, H, F = desc.n_experts, desc.n_slots, desc.top_k, desc.hidden, desc.ffn
@@ -282,6 +303,9 @@ class MoELayer:
         self.slot_of = torch.empty(E, dtype=torch.int32, device=self.dev)
         self.cache = hmoe_cache_create(desc, self.slots, self.slot_of)
         self.copy_stream = torch.cuda.Stream(device=self.dev)
+        self.side_stream = torch.cuda.Stream(device=self.dev)
+        self.ev_fork = torch.cuda.Event()
+        self.ev_join = torch.cuda.Event()
         self.w_router = None if w_router is None else _storage_tensor(w_router).to(self.dev)
         # shared experts: one always-resident expert
         self.shared_desc = None
@@ -356,21 +380,49 @@ class MoELayer:
         assert T <= self.max_tokens and x.dtype == self.dt and x.is_contiguous()
         K, E = d.top_k, d.n_experts
         A = T * K
+        if all_resident is None:
+            all_resident = d.n_slots == d.n_experts
+        counts = None if all_resident else self.h_counts
+        cur = torch.cuda.current_stream()
+        o_shared = None
+        if self.shared_desc is not None:
+            # shared experts (Section II-A) see every token and do not depend on the routing: with
+            # `fused` they run on a side stream next to the routed path
+            if self._shared_T != T:
+                self.shared_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
+                self._shared_T = T
+            o_shared = self.o_shared
+            if self.fused:
+                self.ev_fork.record(cur)
+                self.side_stream.wait_event(self.ev_fork)
+                with torch.cuda.stream(self.side_stream):
+                    hmoe_expert_ffn_grouped(self.shared_desc, self.shared_cache, x, self.shared_offsets, T, None,
+                                            self.o_shared, self.shared_ws, self.shared_ws_bytes, path)
+                    self.ev_join.record(self.side_stream)
         if logits is None:
             hmoe_router_logits(d, x, self.w_router, T, self.logits)
             logits = self.logits
-        hmoe_route(d, logits, T, self.topk_idx, self.topk_w)
-        if all_resident is None:
-            all_resident = d.n_slots == d.n_experts
-        hmoe_permute(d, self.topk_idx, T, x, self.x_perm, self.offsets, self.perm, self.inv_perm,
-                     None if all_resident else self.h_counts, self.perm_ws, self.perm_ws_bytes)
-        if all_resident:
-            hmoe_expert_ffn_grouped(d, self.cache, self.x_perm, self.offsets, A, None, self.o_perm, self.ffn_ws,
-                                    self.ffn_ws_bytes, path)
+        if self.fused:
+            hmoe_route_permute(d, logits, T, self.topk_idx, self.topk_w, self.offsets, self.perm, self.inv_perm, counts,
+                               self.perm_ws, self.perm_ws_bytes)
         else:
-            torch.cuda.current_stream().synchronize()          # the host needs the per-expert loads
-            counts = self.h_counts.numpy()
-            wave, slot, victim, n_waves = hmoe_cache_plan(self.cache, counts)
+            hmoe_route(d, logits, T, self.topk_idx, self.topk_w)
+            hmoe_permute(d, self.topk_idx, T, x, self.x_perm, self.offsets, self.perm, self.inv_perm, counts,
+                         self.perm_ws, self.perm_ws_bytes)
+
+        def routed_ffn(active):
+            if self.fused:
+                hmoe_expert_ffn_grouped_gather(d, self.cache, x, self.perm, self.offsets, A, active, self.o_perm,
+                                               self.ffn_ws, self.ffn_ws_bytes, path)
+            else:
+                hmoe_expert_ffn_grouped(d, self.cache, self.x_perm, self.offsets, A, active, self.o_perm, self.ffn_ws,
+                                        self.ffn_ws_bytes, path)
+
+        if all_resident:
+            routed_ffn(None)
+        else:
+            cur.synchronize()          # the host needs the per-expert loads
+            wave, slot, victim, n_waves = hmoe_cache_plan(self.cache, self.h_counts.numpy())
             self.last_plan = (wave.copy(), slot.copy(), victim.copy(), n_waves)
             for w in range(n_waves):
                 members = np.nonzero(wave == w)[0].astype(np.int32)
@@ -380,16 +432,13 @@ class MoELayer:
                                          self.copy_stream)
                         self.staged_bytes += self.slot_bytes
                 if members.size:
-                    hmoe_expert_ffn_grouped(d, self.cache, self.x_perm, self.offsets, A, members, self.o_perm,
-                                            self.ffn_ws, self.ffn_ws_bytes, path)
-        o_shared = None
+                    routed_ffn(members)
         if self.shared_desc is not None:
-            if self._shared_T != T:
-                self.shared_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
-                self._shared_T = T
-            hmoe_expert_ffn_grouped(self.shared_desc, self.shared_cache, x, self.shared_offsets, T, None,
-                                    self.o_shared, self.shared_ws, self.shared_ws_bytes, path)
-            o_shared = self.o_shared
+            if self.fused:
+                cur.wait_event(self.ev_join)
+            else:
+                hmoe_expert_ffn_grouped(self.shared_desc, self.shared_cache, x, self.shared_offsets, T, None,
+                                        self.o_shared, self.shared_ws, self.shared_ws_bytes, path)
         hmoe_combine(d, self.o_perm, self.inv_perm, self.topk_w, o_shared, T, self.y)
         return self.y[:T]
 

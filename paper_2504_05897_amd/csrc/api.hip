@@ -319,10 +319,9 @@ extern "C" size_t hmoe_ffn_workspace_bytes(const hmoe_layer_desc* desc, int32_t 
   return (((size_t)A * desc->ffn * elem) + 255) & ~(size_t)255;
 }
 
-extern "C" int32_t hmoe_expert_ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x_perm,
-                                           const int32_t* expert_offsets, int32_t A, const int32_t* h_active,
-                                           int32_t n_active, void* o_perm, void* workspace, size_t workspace_bytes,
-                                           int32_t path, void* stream) {
+static int32_t ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x_perm, const int32_t* row_map,
+                           const int32_t* expert_offsets, int32_t A, const int32_t* h_active, int32_t n_active,
+                           void* o_perm, void* workspace, size_t workspace_bytes, int32_t path, void* stream) {
   int rc = check_ffn_shape(desc);
   if (rc != HMOE_OK) return rc;
   if (!cache || A < 0 || !expert_offsets) return HMOE_ERR_INVALID_ARG;
@@ -337,6 +336,8 @@ extern "C" int32_t hmoe_expert_ffn_grouped(const hmoe_layer_desc* desc, hmoe_cac
   FfnArgs a;
   a.desc = desc;
   a.x_perm = x_perm;
+  a.row_map = row_map;
+  a.map_div = desc->top_k;
   a.offsets = expert_offsets;
   a.n_rows = A;
   a.slot_of = cache->d_slot_of;
@@ -374,4 +375,21 @@ extern "C" int32_t hmoe_expert_ffn_grouped(const hmoe_layer_desc* desc, hmoe_cac
       if (a.active.test(e) && cache->slot_of[e] >= 0) cache->slot_last_read[cache->slot_of[e]] = seq;
   }
   return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_expert_ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x_perm,
+                                           const int32_t* expert_offsets, int32_t A, const int32_t* h_active,
+                                           int32_t n_active, void* o_perm, void* workspace, size_t workspace_bytes,
+                                           int32_t path, void* stream) {
+  return ffn_grouped(desc, cache, x_perm, nullptr, expert_offsets, A, h_active, n_active, o_perm, workspace,
+                     workspace_bytes, path, stream);
+}
+
+extern "C" int32_t hmoe_expert_ffn_grouped_gather(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x,
+                                                  const int32_t* perm, const int32_t* expert_offsets, int32_t A,
+                                                  const int32_t* h_active, int32_t n_active, void* o_perm,
+                                                  void* workspace, size_t workspace_bytes, int32_t path, void* stream) {
+  if (A > 0 && !perm) return HMOE_ERR_INVALID_ARG;
+  return ffn_grouped(desc, cache, x, perm, expert_offsets, A, h_active, n_active, o_perm, workspace, workspace_bytes,
+                     path, stream);
 }

@@ -31,6 +31,11 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return (bf16_t)(u >> 16);
 }
 
+// source row of sorted row p (gather fused into the FFN's first GEMM when a row map is given)
+__device__ __forceinline__ int mapped_row(const int32_t* __restrict__ row_map, int map_div, int p) {
+  return row_map ? row_map[p] / map_div : p;
+}
+
 __device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + __expf(-g)); }
 
 // Experts taking part in one FFN call, one bit per expert id.
@@ -74,7 +79,9 @@ void probe_after(hipStream_t s);
 // kernel launchers, one per source file ---------------------------------------------------
 struct FfnArgs {
   const hmoe_layer_desc* desc;
-  const void* x_perm;
+  const void* x_perm;       // rows of the gate/up input; with row_map: the un-permuted x [T, H]
+  const int32_t* row_map;   // device [A] or NULL: input row of sorted row p is row_map[p] / map_div
+  int32_t map_div;
   const int32_t* offsets;   // device [E+1]
   int32_t n_rows;           // A
   const int32_t* slot_of;   // device [E]

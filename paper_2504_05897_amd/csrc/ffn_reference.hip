@@ -28,6 +28,8 @@ struct RefCtx {
   size_t slot_bytes;
   ActiveMask active;
   int n_experts, hidden, ffn, n_rows;
+  const int32_t* row_map;
+  int map_div;
 };
 
 // returns slot base or nullptr if row p is not to be computed
@@ -47,7 +49,7 @@ __global__ __launch_bounds__(256) void ref_gateup_f32(RefCtx c, const float* __r
   if (!slot) return;
   const float* wg = (const float*)slot + (size_t)f * c.hidden;
   const float* wu = wg + (size_t)c.ffn * c.hidden;
-  const float* xr = x + (size_t)p * c.hidden;
+  const float* xr = x + (size_t)mapped_row(c.row_map, c.map_div, p) * c.hidden;
   float g = 0.0f, u = 0.0f;
   for (int k = lane; k < c.hidden; k += 64) {
     const float xv = xr[k];
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(256) void ref_gateup_bf16(RefCtx c, const bf16_t* _
   const bf16_t* wgu = (const bf16_t*)slot;
   const int kt = c.hidden / TILE_K;
   const int n_gate = 2 * TILE_N * (f / TILE_N) + f % TILE_N, n_up = n_gate + TILE_N;
-  const bf16_t* xr = x + (size_t)p * c.hidden;
+  const bf16_t* xr = x + (size_t)mapped_row(c.row_map, c.map_div, p) * c.hidden;
   float g = 0.0f, u = 0.0f;
   for (int k = lane; k < c.hidden; k += 64) {
     const float xv = bf16_to_f32(xr[k]);
@@ -113,7 +115,7 @@ int launch_ffn_reference(const FfnArgs& a) {
   const hmoe_layer_desc& d = *a.desc;
   if (a.n_rows == 0) return HMOE_OK;
   if ((d.ffn + 3) / 4 > 65535 || (d.hidden + 3) / 4 > 65535) return HMOE_ERR_UNSUPPORTED;
-  RefCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, a.n_rows};
+  RefCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, a.n_rows, a.row_map, a.map_div};
   const dim3 g1((unsigned)a.n_rows, (unsigned)((d.ffn + 3) / 4)), g2((unsigned)a.n_rows, (unsigned)((d.hidden + 3) / 4));
   probe_before(a.stream);
   if (d.dtype == HMOE_F32)

@@ -32,6 +32,8 @@ struct SkinnyCtx {
   ActiveMask active;
   int n_experts, hidden, ffn;
   int gpb;  // 32-row groups per block
+  const int32_t* row_map;  // gate/up only: input row of sorted row p is row_map[p] / map_div
+  int map_div;
 };
 
 // id of the `want`-th expert (ascending) that is active, resident and has rows; -1 if fewer
@@ -83,7 +85,8 @@ __global__ __launch_bounds__(64 * NW) void ffn_skinny_kernel(SkinnyCtx c, const 
   for (int row0 = row_first; row0 < row_end; row0 += MR) {
     const int rows = min(MR, row_end - row0);
     const bool has_row = col < rows;
-    const u32x4* xin = (const u32x4*)(in + (size_t)(row0 + (has_row ? col : 0)) * K) + half;
+    const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row0 + (has_row ? col : 0)) : row0 + (has_row ? col : 0);
+    const u32x4* xin = (const u32x4*)(in + (size_t)in_row * K) + half;
 
     u32x4 wa[2][U], wb[2][U], xa[2][U];
     int load_g = g_begin, load_j = 0;  // cursor of the next batch to load
@@ -214,7 +217,7 @@ int launch_ffn_skinny(const FfnArgs& a) {
   const hmoe_layer_desc& d = *a.desc;
   if (d.dtype != HMOE_BF16) return HMOE_ERR_UNSUPPORTED;
   if (a.n_rows == 0) return HMOE_OK;
-  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1};
+  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div};
   const int busy_max = std::min(d.n_experts, a.n_rows);     // every busy expert has at least one row
   const int max_rows = std::max(1, a.n_rows / d.top_k);     // a token names an expert at most once
   probe_before(a.stream);

@@ -40,6 +40,8 @@ struct TiledCtx {
   int n_experts, hidden, ffn;
   int n_tiles_n;  // n-tiles per expert
   int grid_padded;
+  const int32_t* row_map;  // gate/up only: input row of sorted row p is row_map[p] / map_div
+  int map_div;
 };
 
 // One 16-byte global -> LDS copy per lane; the wave's 64 chunks land at lds_base .. +1024 in lane
@@ -127,7 +129,8 @@ __global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, con
     const int r = ci / CPR, s = ci % CPR;
     const int chunk = s ^ ((r / RP) % CPR);
     const int row = m0 + r < m_rows ? m0 + r : m_rows - 1;  // clamp: never stored
-    a_src[i] = (const u32x4*)(in + (size_t)(row_first + row) * K) + chunk;
+    const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row_first + row) : row_first + row;
+    a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk;
   }
   const u32x4* b_src[B_OPS];
 #pragma unroll
@@ -304,7 +307,7 @@ __device__ __forceinline__ void wait_vmcnt_regs(u32x4& a, u32x4& b) {
   asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
 
-template <bool GATEUP, int BM, int NWV, int SA>
+template <bool GATEUP, int BM, int NWV, int SA, bool SKIP>
 __global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const bf16_t* __restrict__ in,
                                                                bf16_t* __restrict__ out) {
   constexpr int FN = 2, BN = NWV * 64, FM = BM / 32, BKT = 64, KK = 4, DB = 8;
@@ -358,7 +361,8 @@ __global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const 
     const int r = ci / CPR, sl = ci % CPR;
     const int chunk = sl ^ ((r / RP) % CPR);
     const int row = m0 + r < m_rows ? m0 + r : m_rows - 1;
-    a_src[i] = (const u32x4*)(in + (size_t)(row_first + row) * K) + chunk;
+    const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row_first + row) : row_first + row;
+    a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk;
   }
   const u32x4* b_src[FN];
 #pragma unroll
@@ -383,12 +387,15 @@ __global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const 
     for (int j = 0; j < FN; ++j) acc[i][j] = f32x16_t{0};
   u32x4 ring[DB][FN];
   u32x4 fa[2][FM];
+  // SKIP: 32-row fragments past the end of the expert (ragged last m-tile) are neither read nor
+  // multiplied; the count is the same for every wave of the block.
+  const int fm_live = SKIP ? min(FM, (m_rows - m0 + 31) / 32) : FM;
   auto read_a = [&](int buf, int stage, int kk) {
     const u32x4* sa = lds + stage * A_CHUNKS;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
       const int r = i * 32 + col;
-      fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
+      if (!SKIP || i < fm_live) fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
     }
   };
 
@@ -430,9 +437,12 @@ __global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const 
           const int sl = h * KK + kk;  // ring slot of substep 4*tt + kk
           wait_vmcnt_regs<N_B>(ring[sl][0], ring[sl][1]);
 #pragma unroll
-          for (int i = 0; i < FM; ++i)
+          for (int i = 0; i < FM; ++i) {
+            if (!SKIP || i < fm_live) {
 #pragma unroll
-            for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
+              for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
+            }
+          }
           __builtin_amdgcn_sched_barrier(0);
           const int s_next = tt * KK + kk + DB;
 #pragma unroll
@@ -469,7 +479,7 @@ __global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const 
   }
 }
 
-template <bool GATEUP, int BM, int NWV, int SA>
+template <bool GATEUP, int BM, int NWV, int SA, bool SKIP>
 static void launch_stream(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
   constexpr int BN = NWV * 64;
   const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
@@ -477,7 +487,7 @@ static void launch_stream(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out,
   const int busy_max = std::min(c.n_experts, n_rows);
   const long tiles = ((long)n_rows / BM + busy_max) * c.n_tiles_n;
   c.grid_padded = (int)((tiles + 7) / 8 * 8);
-  hipLaunchKernelGGL((ffn_stream_kernel<GATEUP, BM, NWV, SA>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in,
+  hipLaunchKernelGGL((ffn_stream_kernel<GATEUP, BM, NWV, SA, SKIP>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in,
                      out);
 }
 
@@ -502,8 +512,10 @@ static const TiledVariant kVariants[] = {
     HMOE_TILED_VARIANT(256, 256, 64, 2, 4, 2),  // 6: 8 waves, 64x128 per wave
     HMOE_TILED_VARIANT(256, 256, 32, 5, 2, 4),  // 7: as 2 with 5 stages (all of LDS)
     HMOE_TILED_VARIANT(256, 256, 32, 4, 4, 2),  // 8: as 2, 64x128 per wave
-    {"stream 128x256 s4", launch_stream<true, 128, 4, 4>, launch_stream<false, 128, 4, 4>},   // 9: weights bypass LDS, 4 waves
-    {"stream 128x512 s4", launch_stream<true, 128, 8, 4>, launch_stream<false, 128, 8, 4>},   // 10: weights bypass LDS, 8 waves
+    {"stream 128x256 s4", launch_stream<true, 128, 4, 4, false>, launch_stream<false, 128, 4, 4, false>},  // 9: weights bypass LDS, 4 waves
+    {"stream 128x512 s4", launch_stream<true, 128, 8, 4, false>, launch_stream<false, 128, 8, 4, false>},  // 10: weights bypass LDS, 8 waves
+    {"stream 128x256 s4 skip", launch_stream<true, 128, 4, 4, true>, launch_stream<false, 128, 4, 4, true>},  // 11: 9 + skip padded fragments
+    {"stream 128x512 s4 skip", launch_stream<true, 128, 8, 4, true>, launch_stream<false, 128, 8, 4, true>},  // 12: 10 + skip padded fragments
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -511,7 +523,7 @@ int launch_ffn_tiled(const FfnArgs& a) {
   const hmoe_layer_desc& d = *a.desc;
   if (d.dtype != HMOE_BF16) return HMOE_ERR_UNSUPPORTED;
   if (a.n_rows == 0) return HMOE_OK;
-  TiledCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 0, 0};
+  TiledCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 0, 0, a.row_map, a.map_div};
   const bf16_t* x = (const bf16_t*)a.x_perm;
   bf16_t* h = (bf16_t*)a.h;
   bf16_t* o = (bf16_t*)a.o_perm;

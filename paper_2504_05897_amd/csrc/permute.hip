@@ -10,7 +10,7 @@
 //                  ballots (same-key mask), waves and steps are ordered by per-wave LDS bases
 // For A <= 1024 (every decode shape) one block does all three in one launch.
 //   4. gather      x_perm[p] = x[perm[p] / K], 16 bytes per lane
-#include "common.h"
+#include "route_body.h"
 
 namespace hmoe {
 
@@ -81,13 +81,11 @@ __global__ __launch_bounds__(PB_THREADS) void permute_scan_kernel(int32_t* __res
 
 // Ranks one chunk.  SINGLE: the chunk is the whole input and this block also builds the offsets.
 template <bool SINGLE>
-__global__ __launch_bounds__(PB_THREADS) void permute_rank_kernel(const int32_t* __restrict__ topk_idx, int n_assign,
-                                                                  int n_experts, int key_bits,
-                                                                  const int32_t* __restrict__ block_bases,
-                                                                  int32_t* __restrict__ expert_offsets,
-                                                                  int32_t* __restrict__ counts_out,
-                                                                  int32_t* __restrict__ perm,
-                                                                  int32_t* __restrict__ inv_perm) {
+__device__ __forceinline__ void permute_rank_body(const int32_t* topk_idx, int n_assign, int n_experts, int key_bits,
+                                                  const int32_t* __restrict__ block_bases,
+                                                  int32_t* __restrict__ expert_offsets,
+                                                  int32_t* __restrict__ counts_out, int32_t* __restrict__ perm,
+                                                  int32_t* __restrict__ inv_perm) {
   __shared__ int wave_base[PB_WAVES][HMOE_MAX_EXPERTS];  // first counts, then running bases
   __shared__ int scan_tmp[HMOE_MAX_EXPERTS];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
@@ -157,6 +155,40 @@ __global__ __launch_bounds__(PB_THREADS) void permute_rank_kernel(const int32_t*
   }
 }
 
+template <bool SINGLE>
+__global__ __launch_bounds__(PB_THREADS) void permute_rank_kernel(const int32_t* __restrict__ topk_idx, int n_assign,
+                                                                  int n_experts, int key_bits,
+                                                                  const int32_t* __restrict__ block_bases,
+                                                                  int32_t* __restrict__ expert_offsets,
+                                                                  int32_t* __restrict__ counts_out,
+                                                                  int32_t* __restrict__ perm,
+                                                                  int32_t* __restrict__ inv_perm) {
+  permute_rank_body<SINGLE>(topk_idx, n_assign, n_experts, key_bits, block_bases, expert_offsets, counts_out, perm,
+                            inv_perm);
+}
+
+// Small batches (A <= 1024, every decode shape): routing and permutation in ONE block and one launch.
+// The block first routes all tokens (lane groups as in hmoe_route), then ranks the assignments it has
+// just written.
+template <int G, int VPL>
+__global__ __launch_bounds__(PB_THREADS) void route_permute_small_kernel(const float* __restrict__ logits, int n_tokens,
+                                                                         int n_experts, int top_k, int key_bits,
+                                                                         int32_t* topk_idx, float* __restrict__ topk_w,
+                                                                         int32_t* __restrict__ expert_offsets,
+                                                                         int32_t* __restrict__ counts_out,
+                                                                         int32_t* __restrict__ perm,
+                                                                         int32_t* __restrict__ inv_perm) {
+  constexpr int TOKENS_PER_PASS = PB_THREADS / G;
+  for (int t0 = 0; t0 < n_tokens; t0 += TOKENS_PER_PASS) {
+    const long token = t0 + threadIdx.x / G;
+    route_token<G, VPL>(logits, n_experts, top_k, token, token < n_tokens, threadIdx.x % G, topk_idx, topk_w);
+  }
+  __threadfence_block();
+  __syncthreads();  // the ids written above are read back below by other lanes of this block
+  permute_rank_body<true>(topk_idx, n_tokens * top_k, n_experts, key_bits, nullptr, expert_offsets, counts_out, perm,
+                          inv_perm);
+}
+
 // x_perm[p, :] = x[perm[p] / K, :], rows of row_bytes (multiple of 16)
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ perm,
                                                           int top_k, int row_vec, int n_assign,
@@ -221,5 +253,43 @@ extern "C" int32_t hmoe_permute(const hmoe_layer_desc* desc, const int32_t* topk
                        (int)(row_bytes / 16), (int)A, (uint4*)x_perm);
     HMOE_HIP(hipGetLastError());
   }
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_route_permute(const hmoe_layer_desc* desc, const float* logits, int32_t T, int32_t* topk_idx,
+                                      float* topk_w, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
+                                      int32_t* h_counts_pinned, void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace hmoe;
+  int rc = check_desc(desc);
+  if (rc != HMOE_OK) return rc;
+  if (T < 0 || !expert_offsets) return HMOE_ERR_INVALID_ARG;
+  const long A = (long)T * desc->top_k;
+  if (A > PB_CHUNK || T == 0) {  // large batches: the two separate calls
+    rc = hmoe_route(desc, logits, T, topk_idx, topk_w, stream);
+    if (rc != HMOE_OK) return rc;
+    return hmoe_permute(desc, topk_idx, T, nullptr, nullptr, expert_offsets, perm, inv_perm, h_counts_pinned, workspace,
+                        workspace_bytes, stream);
+  }
+  if (!logits || !topk_idx || !topk_w || !perm || !inv_perm) return HMOE_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < hmoe_permute_workspace_bytes(desc, T)) return HMOE_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 3u) return HMOE_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  const int E = desc->n_experts, K = desc->top_k;
+  int key_bits = 0;
+  while ((1 << key_bits) < E) ++key_bits;
+  int32_t* counts_dev = (int32_t*)workspace + (size_t)n_chunks(A) * E;
+#define HMOE_LAUNCH_SMALL(G, VPL)                                                                                   \
+  hipLaunchKernelGGL((route_permute_small_kernel<G, VPL>), dim3(1), dim3(PB_THREADS), 0, s, logits, (int)T, E, K, key_bits, \
+                     topk_idx, topk_w, expert_offsets, counts_dev, perm, inv_perm)
+  if (E <= 8) HMOE_LAUNCH_SMALL(8, 1);
+  else if (E <= 16) HMOE_LAUNCH_SMALL(16, 1);
+  else if (E <= 32) HMOE_LAUNCH_SMALL(32, 1);
+  else if (E <= 64) HMOE_LAUNCH_SMALL(64, 1);
+  else if (E <= 128) HMOE_LAUNCH_SMALL(64, 2);
+  else HMOE_LAUNCH_SMALL(64, 4);
+#undef HMOE_LAUNCH_SMALL
+  HMOE_HIP(hipGetLastError());
+  if (h_counts_pinned)
+    HMOE_HIP(hipMemcpyAsync(h_counts_pinned, counts_dev, (size_t)E * sizeof(int32_t), hipMemcpyDeviceToHost, s));
   return HMOE_OK;
 }

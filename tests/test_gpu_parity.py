@@ -329,3 +329,51 @@ def test_cache_stage_errors_and_pinning(hm):
     sb = layer.slot_bytes
     assert torch.equal(got[:sb], layer.h_packed[2]) and torch.equal(got[sb:2 * sb], layer.h_packed[3])
     layer.close()
+
+
+# ----------------------------------------------------------------------------------------- fused entry points
+@pytest.mark.parametrize("T,E,K", [(1, 8, 2), (1, 64, 6), (4, 64, 8), (32, 64, 8), (128, 8, 8), (300, 64, 6), (0, 8, 2)])
+def test_route_permute_fused_equals_the_two_calls(hm, T, E, K):
+    """hmoe_route_permute (one launch for T*K <= 1024) against the oracle, bit for bit."""
+    say("route_permute", T, E, K)
+    rng = np.random.default_rng(T + E + K)
+    lg = rng.standard_normal((max(T, 1), E)).astype(np.float32)[:T]
+    lg[::2] = np.round(lg[::2] * 2) / 2
+    d = hm.make_desc(64, 64, E, K, E, hm.HMOE_BF16)
+    A = T * K
+    idx = torch.full((max(T, 1), K), -5, dtype=torch.int32, device=DEV)
+    w = torch.zeros(max(T, 1), K, dtype=torch.float32, device=DEV)
+    offs = torch.full((E + 1,), -7, dtype=torch.int32, device=DEV)
+    perm = torch.full((max(A, 1),), -7, dtype=torch.int32, device=DEV)
+    inv = torch.full((max(A, 1),), -7, dtype=torch.int32, device=DEV)
+    counts = torch.zeros(E, dtype=torch.int32, pin_memory=True)
+    ws_bytes = hm.hmoe_permute_workspace_bytes(d, T)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    hm.hmoe_route_permute(d, to_device(lg) if T else None, T, idx, w, offs, perm, inv, counts, ws, ws_bytes)
+    torch.cuda.synchronize()
+    ridx, rw = orc.route(lg, K) if T else (np.zeros((0, K), np.int32), np.zeros((0, K), np.float32))
+    ro, rp, ri = orc.permute(ridx, E)
+    assert np.array_equal(idx.cpu().numpy()[:T], ridx)
+    np.testing.assert_allclose(w.cpu().numpy()[:T], rw, rtol=2e-6, atol=1e-7)
+    assert np.array_equal(offs.cpu().numpy(), ro)
+    assert np.array_equal(perm.cpu().numpy()[:A], rp) and np.array_equal(inv.cpu().numpy()[:A], ri)
+    assert np.array_equal(counts.numpy(), np.diff(ro))
+
+
+@pytest.mark.parametrize("T", [3, 70])
+def test_fused_and_unfused_layers_agree(hm, T):
+    """The fused call sequence (route+permute in one call, gather inside the FFN, shared expert on a side
+    stream) and the plain five-call sequence give the same integers and outputs."""
+    say("fused vs unfused", T)
+    shape = wl.small_shape(dtype=wl.BF16, hidden=128, ffn=192, n_experts=8, top_k=2, shared_ffn=(64,), x_mode="rmsnorm")
+    lay = wl.make_layer(shape, 31, T)
+    d = desc_of(hm, shape)
+    outs = []
+    for fused in (True, False):
+        layer = hm.MoELayer(d, lay.experts, lay.shared, lay.w_router, max_tokens=T, fused=fused)
+        y = layer.forward(to_device(lay.x))
+        torch.cuda.synchronize()
+        outs.append((to_host_f32(y).copy(), layer.perm[:T * 2].cpu().numpy().copy(), layer.offsets.cpu().numpy().copy()))
+        layer.close()
+    assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
+    assert np.array_equal(outs[0][0], outs[1][0])      # same kernels on the same rows: bit-identical outputs
