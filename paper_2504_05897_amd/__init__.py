@@ -287,18 +287,24 @@ class MoELayer:
                  max_tokens: int = 1, device: str = "cuda:0", resident: Optional[Sequence[int]] = None,
                  fused: bool = True):
         self.desc = desc
-        self.fused = fused          # route+permute in one call, gather fused into the FFN, shared expert on a side stream
+        self.fused = fused          # route+permute in one call, gather fused into the FFN
+        self.overlap_shared = fused  # shared-expert FFN on a side stream, next to the routed path
         self.dev = torch.device(device)
         self.dt = torch_dtype(desc)
         E, S, K, H, F = desc.n_experts, desc.n_slots, desc.top_k, desc.hidden, desc.ffn
         self.slot_bytes = hmoe_slot_bytes(desc)
         # pinned host copies of the packed experts
-        self.h_packed: List[torch.Tensor] = []
-        for (wg, wu, wd) in experts:
-            buf = torch.empty(self.slot_bytes, dtype=torch.uint8, pin_memory=True)
+        self.h_packed: List[torch.Tensor] = [torch.empty(self.slot_bytes, dtype=torch.uint8, pin_memory=True)
+                                             for _ in experts]
+
+        def pack_one(i):
+            wg, wu, wd = experts[i]
             hmoe_pack_expert(desc, np.ascontiguousarray(wg), np.ascontiguousarray(wu), np.ascontiguousarray(wd),
-                             buf)
-            self.h_packed.append(buf)
+                             self.h_packed[i])
+
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, max(1, len(experts)))) as pool:   # packing is host-side memcpy work
+            list(pool.map(pack_one, range(len(experts))))
         self.slots = torch.empty(S * self.slot_bytes, dtype=torch.uint8, device=self.dev)
         self.slot_of = torch.empty(E, dtype=torch.int32, device=self.dev)
         self.cache = hmoe_cache_create(desc, self.slots, self.slot_of)
@@ -392,7 +398,7 @@ class MoELayer:
                 self.shared_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
                 self._shared_T = T
             o_shared = self.o_shared
-            if self.fused:
+            if self.overlap_shared:
                 self.ev_fork.record(cur)
                 self.side_stream.wait_event(self.ev_fork)
                 with torch.cuda.stream(self.side_stream):
@@ -434,7 +440,7 @@ class MoELayer:
                 if members.size:
                     routed_ffn(members)
         if self.shared_desc is not None:
-            if self.fused:
+            if self.overlap_shared:
                 cur.wait_event(self.ev_join)
             else:
                 hmoe_expert_ffn_grouped(self.shared_desc, self.shared_cache, x, self.shared_offsets, T, None,
