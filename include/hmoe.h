@@ -198,6 +198,34 @@ int32_t hmoe_cache_stage(hmoe_cache* cache, int32_t expert_id, int32_t slot,
 int32_t hmoe_cache_plan(hmoe_cache* cache, const int32_t* h_counts, int32_t* h_wave, int32_t* h_slot,
                         int32_t* h_victim, int32_t* n_waves);
 
+/*
+ * Score-aware replacement (Section IV-D, Eq. (3)): the Minus Recent Score policy keeps a priority
+ * estimate S per expert, S <- alpha * TopP(s) + (1 - alpha) * S, where s are the routing scores of the
+ * current iteration and only the p largest are accumulated (the paper uses p = 2K); the victim is the
+ * candidate with the lowest S.  Where the paper is silent: S starts at 0; s is the batch mean of the
+ * full softmax over all E experts (hmoe_route_scores); TopP keeps the p largest entries (ties: lower
+ * id) and zeroes the rest; candidates are ordered as for LRU (experts this call does not need first,
+ * then by wave), S replacing the use tick inside a class, ties -> lowest slot.
+ *   hmoe_cache_set_policy    HMOE_POLICY_LRU (default) or HMOE_POLICY_MRS with 0 < alpha <= 1
+ *   hmoe_cache_update_scores one update of Eq. (3) from HOST scores h_scores [E]; call once per
+ *                            iteration, after the layer call
+ *   hmoe_cache_get_scores    copies S [E] (double) to the host
+ */
+enum { HMOE_POLICY_LRU = 0, HMOE_POLICY_MRS = 1 };
+int32_t hmoe_cache_set_policy(hmoe_cache* cache, int32_t policy, float alpha);
+int32_t hmoe_cache_update_scores(hmoe_cache* cache, const float* h_scores, int32_t top_p);
+int32_t hmoe_cache_get_scores(const hmoe_cache* cache, double* h_out);
+
+/*
+ * Routing scores of one iteration for Eq. (3): scores[e] = mean over the T tokens of
+ * softmax(logits[t, :])[e] (full softmax over all E experts), fp32, summed in a fixed order.
+ *   scores [E] device fp32 out; h_scores_pinned [E] HOST pinned or NULL (async copy on `stream`)
+ *   workspace: hmoe_route_scores_workspace_bytes(desc, T) bytes of device scratch.
+ */
+size_t hmoe_route_scores_workspace_bytes(const hmoe_layer_desc* desc, int32_t T);
+int32_t hmoe_route_scores(const hmoe_layer_desc* desc, const float* logits, int32_t T, float* scores,
+                          float* h_scores_pinned, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------
  * Grouped SwiGLU expert FFN over resident experts: for every expert e that is active,
  * has rows and sits in a slot,

@@ -275,3 +275,62 @@ class ExpertCacheModel:
         if s >= 0:
             self.slot_of[expert] = -1
             self.expert_in[s] = -1
+
+
+# ---------------------------------------------------------------------------
+# score-aware replacement (Section IV-D, Eq. (3))
+# ---------------------------------------------------------------------------
+def route_scores(logits: np.ndarray) -> np.ndarray:
+    """Routing scores s of one iteration: the batch mean of the full softmax over all experts."""
+    lg = np.asarray(logits, f64)
+    z = np.exp(lg - lg.max(axis=1, keepdims=True))
+    return (z / z.sum(axis=1, keepdims=True)).mean(axis=0)
+
+
+def mrs_update(score: Sequence[float], s: Sequence[float], alpha: float, top_p: int) -> List[float]:
+    """One step of Eq. (3), S <- alpha * TopP(s) + (1 - alpha) * S: only the top_p largest routing
+    scores are accumulated (ties: lower id), the others count as zero."""
+    n = len(s)
+    keep = set(sorted(range(n), key=lambda e: (-float(s[e]), e))[:top_p])
+    return [alpha * (float(s[e]) if e in keep else 0.0) + (1.0 - alpha) * float(score[e]) for e in range(n)]
+
+
+class MRSCacheModel(ExpertCacheModel):
+    """ExpertCacheModel with the Minus Recent Score victim choice: candidates are ordered by class
+    (occupants this call does not need first, then by the wave in which they are computed), inside a
+    class the lowest priority estimate S loses, ties -> lowest slot.  S starts at 0 and is updated once
+    per iteration with `update` (the paper sets p to twice the number of activated experts)."""
+
+    def __init__(self, n_experts: int, n_slots: int, alpha: float):
+        super().__init__(n_experts, n_slots)
+        self.alpha = alpha
+        self.score = [0.0] * n_experts
+
+    def update(self, s: Sequence[float], top_p: int) -> None:
+        self.score = mrs_update(self.score, s, self.alpha, top_p)
+
+    def serve(self, needed: Sequence[int]) -> List[Tuple[int, int, int, int]]:
+        need = sorted(set(int(e) for e in needed))
+        wave = {}
+        plan = []
+        for e in need:
+            if self.slot_of[e] >= 0:
+                wave[e] = 0
+                plan.append((e, self.slot_of[e], 0, -1))
+        for e in [x for x in need if x not in wave]:
+            free = [s for s in range(self.n_slots) if self.expert_in[s] < 0]
+            if free:
+                s, victim, w = free[0], -1, 1
+            else:
+                def key(q):
+                    occ = self.expert_in[q]
+                    return (1 + wave[occ] if occ in wave else 0, self.score[occ], q)
+                s = min(range(self.n_slots), key=key)
+                victim = self.expert_in[s]
+                w = wave[victim] + 1 if victim in wave else 1
+                self.slot_of[victim] = -1
+            self.expert_in[s] = e
+            self.slot_of[e] = s
+            wave[e] = w
+            plan.append((e, s, w, victim))
+        return plan

@@ -40,8 +40,11 @@ EXPORTS = [
     "hmoe_cache_evict", "hmoe_cache_pin_slot", "hmoe_cache_stage", "hmoe_cache_plan",
     "hmoe_ffn_workspace_bytes", "hmoe_expert_ffn_grouped", "hmoe_expert_ffn_grouped_gather", "hmoe_route_permute",
     "hmoe_combine",
+    "hmoe_cache_set_policy", "hmoe_cache_update_scores", "hmoe_cache_get_scores",
+    "hmoe_route_scores_workspace_bytes", "hmoe_route_scores",
     "hmoe_probe_arm", "hmoe_probe_read",
 ]
+HMOE_POLICY_LRU, HMOE_POLICY_MRS = 0, 1
 
 
 class HmoeError(RuntimeError):
@@ -94,6 +97,12 @@ def _load() -> ctypes.CDLL:
     lib.hmoe_expert_ffn_grouped_gather.argtypes = [dp, vp, vp, vp, vp, i32, vp, i32, vp, vp, sz, i32, vp]
     lib.hmoe_route_permute.argtypes = [dp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.hmoe_combine.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp]
+    lib.hmoe_cache_set_policy.argtypes = [vp, i32, ctypes.c_float]
+    lib.hmoe_cache_update_scores.argtypes = [vp, vp, i32]
+    lib.hmoe_cache_get_scores.argtypes = [vp, vp]
+    lib.hmoe_route_scores_workspace_bytes.restype = sz
+    lib.hmoe_route_scores_workspace_bytes.argtypes = [dp, i32]
+    lib.hmoe_route_scores.argtypes = [dp, vp, i32, vp, vp, vp, sz, vp]
     lib.hmoe_probe_arm.argtypes = [i32]
     lib.hmoe_probe_read.argtypes = [vp, i32, ctypes.POINTER(i32)]
     for name in EXPORTS:
@@ -251,6 +260,30 @@ def hmoe_route_permute(desc, logits, T, topk_idx, topk_w, expert_offsets, perm, 
 def hmoe_combine(desc, o_perm, inv_perm, topk_w, o_shared, T, y, stream=None):
     _check(_lib.hmoe_combine(ctypes.byref(desc), _ptr(o_perm), _ptr(inv_perm), _ptr(topk_w), _ptr(o_shared), T,
                              _ptr(y), _stream(stream)), "hmoe_combine")
+
+
+def hmoe_cache_set_policy(cache, policy: int, alpha: float = 0.5):
+    _check(_lib.hmoe_cache_set_policy(cache, policy, alpha), "hmoe_cache_set_policy")
+
+
+def hmoe_cache_update_scores(cache, h_scores, top_p: int):
+    s = h_scores.numpy() if isinstance(h_scores, torch.Tensor) else np.ascontiguousarray(h_scores, dtype=np.float32)
+    _check(_lib.hmoe_cache_update_scores(cache, _ptr(s), top_p), "hmoe_cache_update_scores")
+
+
+def hmoe_cache_get_scores(cache, n_experts: int) -> np.ndarray:
+    out = np.zeros(n_experts, np.float64)
+    _check(_lib.hmoe_cache_get_scores(cache, _ptr(out)), "hmoe_cache_get_scores")
+    return out
+
+
+def hmoe_route_scores_workspace_bytes(desc, T) -> int:
+    return int(_lib.hmoe_route_scores_workspace_bytes(ctypes.byref(desc), T))
+
+
+def hmoe_route_scores(desc, logits, T, scores, h_scores_pinned, workspace, workspace_bytes, stream=None):
+    _check(_lib.hmoe_route_scores(ctypes.byref(desc), _ptr(logits), T, _ptr(scores), _ptr(h_scores_pinned),
+                                  _ptr(workspace), workspace_bytes, _stream(stream)), "hmoe_route_scores")
 
 
 def hmoe_probe_arm(max_pairs: int):
@@ -447,6 +480,25 @@ class MoELayer:
                                         self.o_shared, self.shared_ws, self.shared_ws_bytes, path)
         hmoe_combine(d, self.o_perm, self.inv_perm, self.topk_w, o_shared, T, self.y)
         return self.y[:T]
+
+    # -- score-aware replacement (Section IV-D) -------------------------------------------
+    def set_policy(self, policy: int, alpha: float = 0.5):
+        hmoe_cache_set_policy(self.cache, policy, alpha)
+
+    def update_scores(self, logits: torch.Tensor, top_p: Optional[int] = None) -> np.ndarray:
+        """One Eq. (3) update from this iteration's logits [T, E]; returns the routing scores used."""
+        d = self.desc
+        T = int(logits.shape[0])
+        if not hasattr(self, "_scores_dev"):
+            self._scores_dev = torch.empty(d.n_experts, dtype=torch.float32, device=self.dev)
+            self._scores_host = torch.zeros(d.n_experts, dtype=torch.float32, pin_memory=True)
+        ws_bytes = hmoe_route_scores_workspace_bytes(d, T)
+        if getattr(self, "_scores_ws", None) is None or self._scores_ws.numel() < ws_bytes:
+            self._scores_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=self.dev)
+        hmoe_route_scores(d, logits, T, self._scores_dev, self._scores_host, self._scores_ws, ws_bytes)
+        torch.cuda.current_stream().synchronize()
+        hmoe_cache_update_scores(self.cache, self._scores_host, 2 * d.top_k if top_p is None else top_p)
+        return self._scores_host.numpy().copy()
 
     def slot_map(self) -> List[int]:
         return [hmoe_cache_lookup(self.cache, e) for e in range(self.desc.n_experts)]

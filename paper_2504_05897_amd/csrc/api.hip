@@ -164,6 +164,9 @@ extern "C" int32_t hmoe_cache_create(const hmoe_layer_desc* desc, void* slot_sto
   c->expert_in.assign(desc->n_slots, -1);
   c->tick.assign(desc->n_experts, 0);
   c->clock = 1;
+  c->policy = HMOE_POLICY_LRU;
+  c->alpha = 0.5;
+  c->score.assign(desc->n_experts, 0.0);
   c->pinned.assign(desc->n_slots, 0);
   c->use_seq = 0;
   c->track_reads = desc->n_slots < desc->n_experts;
@@ -294,7 +297,17 @@ extern "C" int32_t hmoe_cache_plan(hmoe_cache* c, const int32_t* h_counts, int32
     if (target < 0) {
       for (int s = 0; s < S; ++s) {
         if (c->pinned[s]) continue;
-        if (target < 0 || c->tick[occ[s]] < c->tick[occ[target]]) target = s;
+        if (target < 0) { target = s; continue; }
+        const int a = occ[s], b = occ[target];
+        bool better;
+        if (c->policy == HMOE_POLICY_MRS) {
+          // class: not needed by this call first, then by the wave in which it is computed; lowest S inside a class
+          const int ca = h_wave[a] >= 0 ? 1 + h_wave[a] : 0, cb = h_wave[b] >= 0 ? 1 + h_wave[b] : 0;
+          better = ca < cb || (ca == cb && c->score[a] < c->score[b]);
+        } else {
+          better = c->tick[a] < c->tick[b];
+        }
+        if (better) target = s;
       }
       if (target < 0) return HMOE_ERR_SLOT_BUSY;
       const int victim = occ[target];
@@ -309,6 +322,34 @@ extern "C" int32_t hmoe_cache_plan(hmoe_cache* c, const int32_t* h_counts, int32
   }
   c->clock = base + last_wave + 1;
   *n_waves = last_wave + 1;
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_cache_set_policy(hmoe_cache* c, int32_t policy, float alpha) {
+  if (!c || (policy != HMOE_POLICY_LRU && policy != HMOE_POLICY_MRS)) return HMOE_ERR_INVALID_ARG;
+  if (policy == HMOE_POLICY_MRS && !(alpha > 0.0f && alpha <= 1.0f)) return HMOE_ERR_INVALID_ARG;
+  c->policy = policy;
+  if (policy == HMOE_POLICY_MRS) c->alpha = alpha;
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_cache_update_scores(hmoe_cache* c, const float* h_scores, int32_t top_p) {
+  if (!c || !h_scores || top_p < 1) return HMOE_ERR_INVALID_ARG;
+  const int E = c->desc.n_experts;
+  // TopP: the top_p largest scores (ties: lower id) are accumulated, the others count as 0
+  std::vector<int> order(E);
+  for (int e = 0; e < E; ++e) order[e] = e;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return h_scores[a] > h_scores[b]; });
+  std::vector<uint8_t> keep(E, 0);
+  for (int i = 0; i < E && i < top_p; ++i) keep[order[i]] = 1;
+  for (int e = 0; e < E; ++e)
+    c->score[e] = c->alpha * (keep[e] ? (double)h_scores[e] : 0.0) + (1.0 - c->alpha) * c->score[e];
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_cache_get_scores(const hmoe_cache* c, double* h_out) {
+  if (!c || !h_out) return HMOE_ERR_INVALID_ARG;
+  for (int e = 0; e < c->desc.n_experts; ++e) h_out[e] = c->score[e];
   return HMOE_OK;
 }
 

@@ -108,6 +108,9 @@ struct hmoe_cache {
   std::vector<int32_t> slot_of;    // [E] host mirror
   std::vector<int32_t> expert_in;  // [S]
   std::vector<int64_t> tick;       // [E] LRU use ticks
+  int policy;                      // HMOE_POLICY_*
+  double alpha;                    // MRS averaging coefficient
+  std::vector<double> score;       // [E] MRS priority estimate S
   int64_t clock;
   std::vector<uint8_t> pinned;     // [S]
   // read tracking: FFN calls record one event each; a slot remembers the sequence number of

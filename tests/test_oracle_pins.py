@@ -287,3 +287,48 @@ def test_workload_recipes():
     lay_a = wl.make_layer(wl.small_shape(), 9, 4)
     lay_b = wl.make_layer(wl.small_shape(), 9, 4)
     assert np.array_equal(lay_a.experts[3][2], lay_b.experts[3][2])
+
+
+# ----------------------------------------------------------------------------- score-aware replacement, Eq. (3)
+def test_mrs_update_hand_values_and_closed_form():
+    # alpha = 0.5, p = 2: only the two largest scores are accumulated
+    s1 = [0.1, 0.5, 0.3, 0.1]
+    S = orc.mrs_update([0.0] * 4, s1, 0.5, 2)
+    assert S == [0.0, 0.25, 0.15, 0.0]
+    S = orc.mrs_update(S, [0.6, 0.1, 0.2, 0.1], 0.5, 2)
+    np.testing.assert_allclose(S, [0.3, 0.125, 0.175, 0.0], rtol=1e-15)
+    # ties at the p-th place: lower id is kept
+    assert orc.mrs_update([0.0] * 3, [0.2, 0.2, 0.2], 1.0, 2) == [0.2, 0.2, 0.0]
+    # constant scores: S_n = s * (1 - (1 - alpha)^n)
+    S = [0.0, 0.0]
+    for n in range(1, 8):
+        S = orc.mrs_update(S, [0.7, 0.3], 0.3, 2)
+        np.testing.assert_allclose(S, [0.7 * (1 - 0.7 ** n), 0.3 * (1 - 0.7 ** n)], rtol=1e-12)
+
+
+def test_route_scores_is_mean_softmax():
+    lg = np.log(np.array([[1.0, 1.0, 2.0], [3.0, 1.0, 0.0 + 1e-300]]))
+    lg[1, 2] = -745.0          # exp underflows to 0
+    np.testing.assert_allclose(orc.route_scores(lg), [(0.25 + 0.75) / 2, (0.25 + 0.25) / 2, 0.25], rtol=1e-12)
+
+
+def test_mrs_cache_evicts_lowest_score_and_keeps_wave_order():
+    c = orc.MRSCacheModel(n_experts=6, n_slots=3, alpha=1.0)
+    c.update([0.05, 0.4, 0.3, 0.1, 0.1, 0.05], top_p=6)       # S = s
+    assert c.serve([3]) == [(3, 0, 1, 0)]                      # resident 0,1,2: expert 0 has the lowest S
+    assert c.serve([4]) == [(4, 0, 1, 3)]                      # now 3 (0.1) < 2 (0.3) < 1 (0.4)
+    # all residents needed: they form wave 0 and are evicted in order of S; misses run one wave later
+    c = orc.MRSCacheModel(n_experts=6, n_slots=2, alpha=1.0)
+    c.update([0.3, 0.1, 0.2, 0.2, 0.1, 0.1], top_p=6)
+    assert c.serve([0, 1, 2, 3]) == [(0, 0, 0, -1), (1, 1, 0, -1), (2, 1, 1, 1), (3, 0, 1, 0)]
+    # invariants under random use
+    rng = np.random.default_rng(0)
+    c = orc.MRSCacheModel(10, 4, 0.4)
+    for _ in range(200):
+        need = rng.choice(10, size=int(rng.integers(1, 8)), replace=False).tolist()
+        plan = c.serve(need)
+        assert sorted(p[0] for p in plan) == sorted(need)
+        c.update(rng.random(10), 4)
+        for ex in range(10):
+            if c.slot_of[ex] >= 0:
+                assert c.expert_in[c.slot_of[ex]] == ex
