@@ -44,6 +44,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="mixtral", choices=sorted(PHASES))
     ap.add_argument("--layers", type=int, default=0, help="stress: stacked layers (default 27); others: weight sets rotated")
+    ap.add_argument("--phase", default="", help="run only this phase of the workload (e.g. decode1), for profiling")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a captured HIP graph")
@@ -68,7 +69,8 @@ def main() -> int:
     E, K, H, F = shape.n_experts, shape.top_k, shape.hidden, shape.ffn
     Fs = sum(shape.shared_ffn)
     n_layers = args.layers or (27 if args.workload == "stress" else 1)
-    phases = PHASES[args.workload]
+    phases = [p for p in PHASES[args.workload] if not args.phase or p[0] == args.phase]
+    assert phases, "workload %s has no phase %r" % (args.workload, args.phase)
     max_T = max(t for _, t in phases)
     threads = min(16, len(os.sched_getaffinity(0)))
 
