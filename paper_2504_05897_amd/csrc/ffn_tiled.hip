@@ -334,9 +334,17 @@ static void launch_cfg(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hi
 // so the number of younger operations at each wait is a compile-time constant: N_B for a weight tile,
 // N_A for an activation stage.  In the last steps the same operations are still issued, with the
 // step clamped (their results are never used), which keeps the counts valid.
+//
+// NT: weight loads carry the non-temporal hint.  It pays when an expert has one or two m-tiles (each
+// weight byte is used about once); with many m-tiles per expert the blocks of an XCD share the panel
+// through L2 and plain loads are faster.
+template <bool NT>
 __device__ __forceinline__ u32x4 load_stream_16(const void* gptr) {
   u32x4 v;
-  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(gptr) : "memory");
+  if (NT)
+    asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(gptr) : "memory");
+  else
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(gptr) : "memory");
   return v;
 }
 // wait until at most N younger vector-memory operations are outstanding; the operands tie the wait
@@ -346,7 +354,7 @@ __device__ __forceinline__ void wait_vmcnt_regs(u32x4& a, u32x4& b) {
   asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
 
-template <bool GATEUP, int BM, int NWV, int SA, bool SKIP>
+template <bool GATEUP, int BM, int NWV, int SA, bool SKIP, bool NT>
 __global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const bf16_t* __restrict__ in,
                                                                bf16_t* __restrict__ out) {
   constexpr int FN = 2, BN = NWV * 64, FM = BM / 32, BKT = 64, KK = 4, DB = 8;
@@ -425,7 +433,7 @@ __global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const 
 #pragma unroll
   for (int s = 0; s < DB; ++s)
 #pragma unroll
-    for (int j = 0; j < FN; ++j) ring[s][j] = load_stream_16(b_src[j] + (size_t)(s < n_sub ? s : n_sub - 1) * 64);
+    for (int j = 0; j < FN; ++j) ring[s][j] = load_stream_16<NT>(b_src[j] + (size_t)(s < n_sub ? s : n_sub - 1) * 64);
 #pragma unroll
   for (int st = 0; st < SA - 1; ++st)
 #pragma unroll
@@ -469,7 +477,7 @@ __global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const 
           const int s_next = tt * KK + kk + DB;
 #pragma unroll
           for (int j = 0; j < FN; ++j)
-            ring[sl][j] = load_stream_16(b_src[j] + (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64);
+            ring[sl][j] = load_stream_16<NT>(b_src[j] + (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64);
           issue_a_piece(fill_stage, tt + SA - 1, kk);
         }
         stage = next_stage;
@@ -501,7 +509,7 @@ __global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const 
   }
 }
 
-template <bool GATEUP, int BM, int NWV, int SA, bool SKIP>
+template <bool GATEUP, int BM, int NWV, int SA, bool SKIP, bool NT>
 static void launch_stream(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
   constexpr int BN = NWV * 64;
   const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
@@ -509,7 +517,7 @@ static void launch_stream(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out,
   const int busy_max = std::min(c.n_experts, n_rows);
   const long tiles = ((long)n_rows / BM + busy_max) * c.n_tiles_n;
   c.grid_padded = (int)((tiles + 7) / 8 * 8);
-  hipLaunchKernelGGL((ffn_stream_kernel<GATEUP, BM, NWV, SA, SKIP>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in,
+  hipLaunchKernelGGL((ffn_stream_kernel<GATEUP, BM, NWV, SA, SKIP, NT>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in,
                      out);
 }
 
@@ -534,10 +542,12 @@ static const TiledVariant kVariants[] = {
     HMOE_TILED_VARIANT(256, 256, 64, 2, 4, 2),  // 6: 8 waves, 64x128 per wave
     HMOE_TILED_VARIANT(256, 256, 32, 5, 2, 4),  // 7: as 2 with 5 stages (all of LDS)
     HMOE_TILED_VARIANT(256, 256, 32, 4, 4, 2),  // 8: as 2, 64x128 per wave
-    {"stream 128x256 s4", launch_stream<true, 128, 4, 4, false>, launch_stream<false, 128, 4, 4, false>},  // 9: weights bypass LDS, 4 waves
-    {"stream 128x512 s4", launch_stream<true, 128, 8, 4, false>, launch_stream<false, 128, 8, 4, false>},  // 10: weights bypass LDS, 8 waves
-    {"stream 128x256 s4 skip", launch_stream<true, 128, 4, 4, true>, launch_stream<false, 128, 4, 4, true>},  // 11: 9 + skip padded fragments
-    {"stream 128x512 s4 skip", launch_stream<true, 128, 8, 4, true>, launch_stream<false, 128, 8, 4, true>},  // 12: 10 + skip padded fragments
+    {"stream 128x256 s4", launch_stream<true, 128, 4, 4, false, true>, launch_stream<false, 128, 4, 4, false, true>},  // 9: weights bypass LDS, 4 waves
+    {"stream 128x512 s4", launch_stream<true, 128, 8, 4, false, true>, launch_stream<false, 128, 8, 4, false, true>},  // 10: weights bypass LDS, 8 waves
+    {"stream 128x256 s4 skip", launch_stream<true, 128, 4, 4, true, true>, launch_stream<false, 128, 4, 4, true, true>},  // 11: 9 + skip padded fragments
+    {"stream 128x512 s4 skip", launch_stream<true, 128, 8, 4, true, true>, launch_stream<false, 128, 8, 4, true, true>},  // 12: 10 + skip padded fragments
+    {"stream 128x256 s4 plain", launch_stream<true, 128, 4, 4, false, false>, launch_stream<false, 128, 4, 4, false, false>},  // 13: 9 with plain weight loads
+    {"stream 128x512 s4 plain", launch_stream<true, 128, 8, 4, false, false>, launch_stream<false, 128, 8, 4, false, false>},  // 14: 10 with plain weight loads
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -549,12 +559,18 @@ int launch_ffn_tiled(const FfnArgs& a) {
   const bf16_t* x = (const bf16_t*)a.x_perm;
   bf16_t* h = (bf16_t*)a.h;
   bf16_t* o = (bf16_t*)a.o_perm;
-  // Kernel choice (measured on the workload shapes): the weight-streaming family wins everywhere, with
-  // 8 waves and a 128x512 tile; when that tile would leave most CUs without a block (down projection
-  // of few, large experts: small N) the 128x256 tile with 4 waves doubles the block count.
-  int v_gate_up = 10, v_down = 10;
-  const long tiles_down = ((long)a.n_rows / 128 + std::min(d.n_experts, a.n_rows)) * ((d.hidden + 511) / 512);
-  if (tiles_down < 256) v_down = 9;
+  // Kernel choice (measured on the workload shapes; the tile counts are the launch's upper bounds).  The
+  // weight-streaming family with 8 waves and a 128x512 tile wins whenever it yields several rounds of
+  // blocks per CU.  With fewer tiles the round-up to whole rounds costs more than the kernel gains:
+  // gate/up then takes the 128x256 LDS-ring tile (twice the blocks), and the down projection of few,
+  // large experts (small N) the 128x256 streaming tile with 4 waves.
+  const long m_tiles = (long)a.n_rows / 128 + std::min(d.n_experts, a.n_rows);
+  const long tiles_gate_up = m_tiles * ((2 * d.ffn + 511) / 512);
+  const long tiles_down = m_tiles * ((d.hidden + 511) / 512);
+  // Many m-tiles per expert (512 rows or more on average): the panel is shared through L2, plain loads.
+  const bool shared_panels = a.n_rows / d.n_experts >= 512;
+  int v_gate_up = tiles_gate_up < 1024 ? 1 : (shared_panels ? 14 : 10);
+  int v_down = tiles_down < 256 ? (shared_panels ? 13 : 9) : (shared_panels ? 14 : 10);
   if (const char* env = getenv("HMOE_TILED_VARIANT")) {
     const int want = atoi(env);
     if (want >= 0 && want < kNumVariants) v_gate_up = v_down = want;

@@ -183,6 +183,30 @@ def test_ffn_bf16_paths(hm, path, hidden, ffn, counts):
     assert np.abs(ref).max() > 1e-2
 
 
+@pytest.mark.parametrize("variant", range(15))
+def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
+    """The library's tuning override selects each built-in prefill kernel (LDS-ring tiles 0-8, weight-streaming
+    tiles 9-14) in turn; ragged groups spanning several m-tiles, partial n-tiles for every tile width."""
+    say("ffn prefill variant", variant)
+    monkeypatch.setenv("HMOE_TILED_VARIANT", str(variant))
+    shape = wl.small_shape(dtype=wl.BF16, hidden=256, ffn=320, n_experts=8, top_k=2)
+    got, ref = _ffn_case(hm, shape, [33, 1, 0, 0, 300, 5, 64, 129], 3, seed=variant)
+    assert max_rel_err(got, ref) < TOL[wl.BF16]
+
+
+@pytest.mark.parametrize("shape_id", range(6))
+@pytest.mark.parametrize("gpb", [1, 2, 3])
+def test_ffn_every_decode_block_shape(hm, shape_id, gpb, monkeypatch):
+    """Every (waves, unroll) block shape of the decode kernel and 1-3 row groups per block, on groups of
+    at most 8 rows and of more than 8 rows."""
+    say("ffn decode shape", shape_id, gpb)
+    monkeypatch.setenv("HMOE_SKINNY", "%d,%d" % (shape_id, gpb))
+    shape = wl.small_shape(dtype=wl.BF16, hidden=256, ffn=192, n_experts=6, top_k=2)
+    for counts in ([2, 0, 8, 1, 0, 3], [9, 0, 32, 1, 17, 0]):
+        got, ref = _ffn_case(hm, shape, counts, 2, seed=shape_id * 4 + gpb)
+        assert max_rel_err(got, ref) < TOL[wl.BF16]
+
+
 def test_ffn_inactive_and_non_resident_rows_untouched(hm):
     say("ffn active list")
     shape = wl.small_shape(dtype=wl.BF16, hidden=64, ffn=64, n_experts=4, top_k=2, n_slots=2)
