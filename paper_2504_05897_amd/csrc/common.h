@@ -78,19 +78,19 @@ void probe_after(hipStream_t s);
 
 // kernel launchers, one per source file ---------------------------------------------------
 struct FfnArgs {
-  const hmoe_layer_desc* desc;
-  const void* x_perm;       // rows of the gate/up input; with row_map: the un-permuted x [T, H]
-  const int32_t* row_map;   // device [A] or NULL: input row of sorted row p is row_map[p] / map_div
-  int32_t map_div;
-  const int32_t* offsets;   // device [E+1]
-  int32_t n_rows;           // A
-  const int32_t* slot_of;   // device [E]
-  const char* slots;        // device slot storage
-  size_t slot_bytes;
-  ActiveMask active;
-  void* o_perm;
-  void* h;                  // workspace [A, F]
-  hipStream_t stream;
+  const hmoe_layer_desc* desc = nullptr;
+  const void* x_perm = nullptr;       // rows of the gate/up input; with row_map: the un-permuted x [T, H]
+  const int32_t* row_map = nullptr;   // device [A] or NULL: input row of sorted row p is row_map[p] / map_div
+  int32_t map_div = 1;
+  const int32_t* offsets = nullptr;   // device [E+1]
+  int32_t n_rows = 0;                 // A
+  const int32_t* slot_of = nullptr;   // device [E]
+  const char* slots = nullptr;        // device slot storage
+  size_t slot_bytes = 0;
+  ActiveMask active = {};
+  void* o_perm = nullptr;
+  void* h = nullptr;                  // workspace [A, F]
+  hipStream_t stream = nullptr;
 };
 int launch_ffn_reference(const FfnArgs& a);
 int launch_ffn_skinny(const FfnArgs& a);
