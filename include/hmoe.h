@@ -137,6 +137,17 @@ int32_t hmoe_route_permute(const hmoe_layer_desc* desc, const float* logits, int
                            float* topk_w, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
                            int32_t* h_counts_pinned, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * hmoe_router_logits followed by hmoe_route_permute as one call: the whole front end of Eq. (1)
+ * (x . W_g, Softmax(TopK(.)), permutation).  For decode batches (bf16, T <= 8) it is a single
+ * one-block launch; anything else runs the two calls above.  `logits` [T, E] is an output (the same
+ * bits hmoe_router_logits writes); the other arguments and results as in those calls.
+ */
+int32_t hmoe_router_route_permute(const hmoe_layer_desc* desc, const void* x, const void* w_g, int32_t T,
+                                  float* logits, int32_t* topk_idx, float* topk_w, int32_t* expert_offsets,
+                                  int32_t* perm, int32_t* inv_perm, int32_t* h_counts_pinned, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------
  * Expert weights.  An expert is three bias-free matrices (SwiGLU; the paper gives only
  * the sizes, Table II): W_gate [F, H], W_up [F, H], W_down [H, F], row-major.

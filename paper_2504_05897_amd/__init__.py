@@ -39,6 +39,7 @@ EXPORTS = [
     "hmoe_cache_create", "hmoe_cache_destroy", "hmoe_cache_lookup", "hmoe_cache_occupant",
     "hmoe_cache_evict", "hmoe_cache_pin_slot", "hmoe_cache_stage", "hmoe_cache_plan",
     "hmoe_ffn_workspace_bytes", "hmoe_expert_ffn_grouped", "hmoe_expert_ffn_grouped_gather", "hmoe_route_permute",
+    "hmoe_router_route_permute",
     "hmoe_combine",
     "hmoe_cache_set_policy", "hmoe_cache_update_scores", "hmoe_cache_get_scores",
     "hmoe_route_scores_workspace_bytes", "hmoe_route_scores",
@@ -66,7 +67,7 @@ class LayerDesc(ctypes.Structure):
 
 def _load() -> ctypes.CDLL:
     if not os.path.exists(_LIB_PATH):
-        raise ImportError("libhmoe.so is not built: run `python -m paper_2504_05897_amd.build` "
+        raise ImportError("libhmoe.so is not built: run `python paper_2504_05897_amd/build.py` "
                           "(needs hipcc; there is no fallback path)")
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
@@ -96,6 +97,7 @@ def _load() -> ctypes.CDLL:
     lib.hmoe_expert_ffn_grouped.argtypes = [dp, vp, vp, vp, i32, vp, i32, vp, vp, sz, i32, vp]
     lib.hmoe_expert_ffn_grouped_gather.argtypes = [dp, vp, vp, vp, vp, i32, vp, i32, vp, vp, sz, i32, vp]
     lib.hmoe_route_permute.argtypes = [dp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.hmoe_router_route_permute.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.hmoe_combine.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp]
     lib.hmoe_cache_set_policy.argtypes = [vp, i32, ctypes.c_float]
     lib.hmoe_cache_update_scores.argtypes = [vp, vp, i32]
@@ -255,6 +257,14 @@ def hmoe_route_permute(desc, logits, T, topk_idx, topk_w, expert_offsets, perm, 
     _check(_lib.hmoe_route_permute(ctypes.byref(desc), _ptr(logits), T, _ptr(topk_idx), _ptr(topk_w),
                                    _ptr(expert_offsets), _ptr(perm), _ptr(inv_perm), _ptr(h_counts_pinned),
                                    _ptr(workspace), workspace_bytes, _stream(stream)), "hmoe_route_permute")
+
+
+def hmoe_router_route_permute(desc, x, w_g, T, logits, topk_idx, topk_w, expert_offsets, perm, inv_perm, h_counts_pinned,
+                              workspace, workspace_bytes, stream=None):
+    _check(_lib.hmoe_router_route_permute(ctypes.byref(desc), _ptr(x), _ptr(w_g), T, _ptr(logits), _ptr(topk_idx),
+                                          _ptr(topk_w), _ptr(expert_offsets), _ptr(perm), _ptr(inv_perm),
+                                          _ptr(h_counts_pinned), _ptr(workspace), workspace_bytes, _stream(stream)),
+           "hmoe_router_route_permute")
 
 
 def hmoe_combine(desc, o_perm, inv_perm, topk_w, o_shared, T, y, stream=None):
@@ -438,10 +448,17 @@ class MoELayer:
                     hmoe_expert_ffn_grouped(self.shared_desc, self.shared_cache, x, self.shared_offsets, T, None,
                                             self.o_shared, self.shared_ws, self.shared_ws_bytes, path)
                     self.ev_join.record(self.side_stream)
-        if logits is None:
+        if logits is None and self.fused:
+            hmoe_router_route_permute(d, x, self.w_router, T, self.logits, self.topk_idx, self.topk_w, self.offsets,
+                                      self.perm, self.inv_perm, counts, self.perm_ws, self.perm_ws_bytes)
+            logits = self.logits
+        elif logits is None:
             hmoe_router_logits(d, x, self.w_router, T, self.logits)
             logits = self.logits
-        if self.fused:
+            hmoe_route(d, logits, T, self.topk_idx, self.topk_w)
+            hmoe_permute(d, self.topk_idx, T, x, self.x_perm, self.offsets, self.perm, self.inv_perm, counts,
+                         self.perm_ws, self.perm_ws_bytes)
+        elif self.fused:
             hmoe_route_permute(d, logits, T, self.topk_idx, self.topk_w, self.offsets, self.perm, self.inv_perm, counts,
                                self.perm_ws, self.perm_ws_bytes)
         else:

@@ -1,6 +1,6 @@
 """Builds libhmoe.so (HIP, gfx950 only) in-tree, next to this file.
 
-    python -m paper_2504_05897_amd.build
+    python paper_2504_05897_amd/build.py
 
 Every source is compiled each time this runs; the library is what the Python binding, the
 tests and the benchmark load.

@@ -3,7 +3,7 @@
 // j ascending then the shared term, fp32 accumulation, one rounding.  No atomics: every output
 // element is produced by one lane, so results do not depend on scheduling.
 // Also: hmoe_router_logits (x . W_g), the small GEMM in front of the router.
-#include "common.h"
+#include "router_body.h"
 
 namespace hmoe {
 
@@ -145,6 +145,14 @@ __global__ __launch_bounds__(256) void router_logits_bf16_kernel(const bf16_t* _
   }
 }
 
+// decode batches (T <= 8): one block, loads kept in flight (router_body.h)
+template <int NF>
+__global__ __launch_bounds__(256) void router_logits_small_kernel(const bf16_t* __restrict__ x,
+                                                                  const bf16_t* __restrict__ w_g, int n_tokens,
+                                                                  int n_experts, int hidden, float* __restrict__ logits) {
+  router_logits_small<NF>(x, w_g, n_tokens, n_experts, hidden, logits, nullptr);
+}
+
 }  // namespace hmoe
 
 extern "C" int32_t hmoe_combine(const hmoe_layer_desc* desc, const void* o_perm, const int32_t* inv_perm,
@@ -185,7 +193,12 @@ extern "C" int32_t hmoe_router_logits(const hmoe_layer_desc* desc, const void* x
     const dim3 grid((unsigned)((T + 31) / 32)), block(256);
     const bf16_t* xb = (const bf16_t*)x;
     const bf16_t* wb = (const bf16_t*)w_g;
-    if (E <= 32) hipLaunchKernelGGL((router_logits_bf16_kernel<1>), grid, block, 0, s, xb, wb, T, E, H, logits);
+    if (T <= ROUTER_SMALL_T) {
+      if (E <= 32) hipLaunchKernelGGL((router_logits_small_kernel<1>), dim3(1), block, 0, s, xb, wb, T, E, H, logits);
+      else if (E <= 64) hipLaunchKernelGGL((router_logits_small_kernel<2>), dim3(1), block, 0, s, xb, wb, T, E, H, logits);
+      else if (E <= 128) hipLaunchKernelGGL((router_logits_small_kernel<4>), dim3(1), block, 0, s, xb, wb, T, E, H, logits);
+      else hipLaunchKernelGGL((router_logits_small_kernel<8>), dim3(1), block, 0, s, xb, wb, T, E, H, logits);
+    } else if (E <= 32) hipLaunchKernelGGL((router_logits_bf16_kernel<1>), grid, block, 0, s, xb, wb, T, E, H, logits);
     else if (E <= 64) hipLaunchKernelGGL((router_logits_bf16_kernel<2>), grid, block, 0, s, xb, wb, T, E, H, logits);
     else if (E <= 128) hipLaunchKernelGGL((router_logits_bf16_kernel<4>), grid, block, 0, s, xb, wb, T, E, H, logits);
     else hipLaunchKernelGGL((router_logits_bf16_kernel<8>), grid, block, 0, s, xb, wb, T, E, H, logits);

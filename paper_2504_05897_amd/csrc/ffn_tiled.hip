@@ -123,200 +123,195 @@ __device__ __forceinline__ bool locate_tile(const TiledCtx& c, TileLoc& t) {
   return false;
 }
 
-template <bool GATEUP, int BM, int BN, int BKT, int STAGES, int WM, int WN>
-__global__ __launch_bounds__(64 * WM * WN) void ffn_tiled_kernel(TiledCtx c, const bf16_t* __restrict__ in,
-                                                                  bf16_t* __restrict__ out) {
-  constexpr int NWAVES = WM * WN;
-  constexpr int WTM = BM / WM, WTN = BN / WN;
-  constexpr int FM = WTM / 32, FN = WTN / 32;
-  constexpr int CPR = BKT / 8;              // 16-byte chunks per activation row per step
-  constexpr int RP = 256 / (BKT * 2);       // rows per 256 bytes of LDS
-  constexpr int KK = BKT / TILE_K;          // MFMA k-substeps per step
-  constexpr int A_CHUNKS = BM * CPR;        // per stage
-  constexpr int B_CHUNKS = BN * CPR;
-  constexpr int A_OPS = A_CHUNKS / (64 * NWAVES);  // wave-wide copies per wave per step
-  constexpr int B_OPS = B_CHUNKS / (64 * NWAVES);
-  constexpr int LPS = A_OPS + B_OPS;        // loads per lane per step
+template <bool GATEUP_, int BM_, int BN_, int BKT_, int STAGES, int WM, int WN>
+struct LdsRingTile {
+  static constexpr bool GATEUP = GATEUP_;
+  static constexpr int BM = BM_, BN = BN_, BKT = BKT_;
+  static constexpr int NWAVES = WM * WN;
+  static constexpr int WTM = BM / WM, WTN = BN / WN;
+  static constexpr int FM = WTM / 32, FN = WTN / 32;
+  static constexpr int CPR = BKT / 8;              // 16-byte chunks per activation row per step
+  static constexpr int RP = 256 / (BKT * 2);       // rows per 256 bytes of LDS
+  static constexpr int KK = BKT / TILE_K;          // MFMA k-substeps per step
+  static constexpr int A_CHUNKS = BM * CPR;        // per stage
+  static constexpr int B_CHUNKS = BN * CPR;
+  static constexpr int A_OPS = A_CHUNKS / (64 * NWAVES);  // wave-wide copies per wave per step
+  static constexpr int B_OPS = B_CHUNKS / (64 * NWAVES);
+  static constexpr int LPS = A_OPS + B_OPS;        // loads per lane per step
   static_assert(A_OPS >= 1 && B_OPS >= 1 && A_OPS * 64 * NWAVES == A_CHUNKS && B_OPS * 64 * NWAVES == B_CHUNKS, "");
   static_assert(FM >= 1 && FN >= 1 && (!GATEUP || FN % 2 == 0), "a wave needs gate/up fragment pairs");
   static_assert(STAGES >= 2 && (STAGES - 2) * LPS <= 63, "vmcnt range");
-  __shared__ u32x4 lds[STAGES * (A_CHUNKS + B_CHUNKS)];
+  static constexpr int THREADS = 64 * NWAVES;
+  static constexpr int LDS_VEC = STAGES * (A_CHUNKS + B_CHUNKS);  // 16-byte units
+  typedef f32x16_t Acc[FM][FN];
 
-  TileLoc loc;
-  if (!locate_tile<BM>(c, loc)) return;  // uniform over the block
-  const int e = loc.e, row_first = loc.row_first, m_rows = loc.m_rows, mt = loc.mt, nt = loc.nt;
+  // acc += A[rows of the tile, k range] * W[columns of the tile, k range]^T for the k_steps steps of BKT
+  // that start at step k_begin.  On return every copy into LDS has landed.
+  static __device__ __forceinline__ void mainloop(const TiledCtx& c, const bf16_t* __restrict__ in, const TileLoc& loc,
+                                                  int k_begin, int k_steps, u32x4* lds, Acc& acc) {
+    const int e = loc.e, row_first = loc.row_first, m_rows = loc.m_rows, mt = loc.mt, nt = loc.nt;
+    const int K = GATEUP ? c.hidden : c.ffn;
+    const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;  // packed 32-row groups of W
+    const int kt16 = K / TILE_K;
+    const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
+    const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
+    const int group0 = nt * (BN / TILE_N);
+    const int m0 = mt * BM;  // first row of the tile within the expert
 
-  const int K = GATEUP ? c.hidden : c.ffn;
-  const int n_out = GATEUP ? c.ffn : c.hidden;                    // row length of out
-  const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;  // packed 32-row groups of W
-  const int kt16 = K / TILE_K;
-  const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
-  const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
-  const int group0 = nt * (BN / TILE_N);
-  const int m0 = mt * BM;  // first row of the tile within the expert
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int wm = wave / WN, wn = wave % WN;
+    const int half = lane / 32, col = lane % 32;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;  // LDS byte address of the ring
 
-  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
-  const int wm = wave / WN, wn = wave % WN;
-  const int half = lane / 32, col = lane % 32;
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;  // LDS byte address of the ring
-
-  // ---- per-lane source addresses of the copies this wave issues every step ------------------
-  const u32x4* a_src[A_OPS];
+    // ---- per-lane source addresses of the copies this wave issues every step ------------------
+    const u32x4* a_src[A_OPS];
 #pragma unroll
-  for (int i = 0; i < A_OPS; ++i) {
-    const int ci = (i * NWAVES + wave) * 64 + lane;      // LDS chunk this lane fills
-    const int r = ci / CPR, s = ci % CPR;
-    const int chunk = s ^ ((r / RP) % CPR);
-    const int row = m0 + r < m_rows ? m0 + r : m_rows - 1;  // clamp: never stored
-    const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row_first + row) : row_first + row;
-    a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk;
-  }
-  const u32x4* b_src[B_OPS];
-#pragma unroll
-  for (int i = 0; i < B_OPS; ++i) {
-    const int ci = (i * NWAVES + wave) * 64 + lane;
-    const int g = ci / (KK * 64), within = ci % (KK * 64);  // KK tiles of one group per step
-    const int grp = group0 + g < n_groups ? group0 + g : 0;
-    b_src[i] = w + ((size_t)grp * kt16) * 64 + within;
-  }
-  // The LPS copies of one K step are issued in KK pieces, one piece in front of each MFMA group, so
-  // that the vector-memory queue never holds more than a couple of copies per wave.
-  auto issue_piece = [&](int stage, int kstep, int piece) {
-    const uint32_t base = lds0 + (uint32_t)stage * (A_CHUNKS + B_CHUNKS) * 16;
-#pragma unroll
-    for (int op = 0; op < LPS; ++op) {
-      if (op < piece * LPS / KK || op >= (piece + 1) * LPS / KK) continue;
-      if (op < A_OPS) {
-        load_to_lds_16(a_src[op] + (size_t)kstep * CPR, base + (uint32_t)((op * NWAVES + wave) * 64) * 16);
-      } else {
-        const int i = op - A_OPS;
-        load_to_lds_16(b_src[i] + (size_t)kstep * (KK * 64),
-                       base + (uint32_t)(A_CHUNKS + (i * NWAVES + wave) * 64) * 16);
-      }
+    for (int i = 0; i < A_OPS; ++i) {
+      const int ci = (i * NWAVES + wave) * 64 + lane;      // LDS chunk this lane fills
+      const int r = ci / CPR, s = ci % CPR;
+      const int chunk = s ^ ((r / RP) % CPR);
+      const int row = m0 + r < m_rows ? m0 + r : m_rows - 1;  // clamp: never stored
+      const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row_first + row) : row_first + row;
+      a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk + (size_t)k_begin * CPR;
     }
-  };
-  auto issue = [&](int stage, int kstep) {
+    const u32x4* b_src[B_OPS];
 #pragma unroll
-    for (int p = 0; p < KK; ++p) issue_piece(stage, kstep, p);
-  };
+    for (int i = 0; i < B_OPS; ++i) {
+      const int ci = (i * NWAVES + wave) * 64 + lane;
+      const int g = ci / (KK * 64), within = ci % (KK * 64);  // KK tiles of one group per step
+      const int grp = group0 + g < n_groups ? group0 + g : 0;
+      b_src[i] = w + ((size_t)grp * kt16) * 64 + within + (size_t)k_begin * (KK * 64);
+    }
+    // The LPS copies of one K step are issued in KK pieces, one piece in front of each MFMA group, so
+    // that the vector-memory queue never holds more than a couple of copies per wave.
+    auto issue_piece = [&](int stage, int kstep, int piece) {
+      const uint32_t base = lds0 + (uint32_t)stage * (A_CHUNKS + B_CHUNKS) * 16;
+#pragma unroll
+      for (int op = 0; op < LPS; ++op) {
+        if (op < piece * LPS / KK || op >= (piece + 1) * LPS / KK) continue;
+        if (op < A_OPS) {
+          load_to_lds_16(a_src[op] + (size_t)kstep * CPR, base + (uint32_t)((op * NWAVES + wave) * 64) * 16);
+        } else {
+          const int i = op - A_OPS;
+          load_to_lds_16(b_src[i] + (size_t)kstep * (KK * 64),
+                         base + (uint32_t)(A_CHUNKS + (i * NWAVES + wave) * 64) * 16);
+        }
+      }
+    };
+    auto issue = [&](int stage, int kstep) {
+#pragma unroll
+      for (int p = 0; p < KK; ++p) issue_piece(stage, kstep, p);
+    };
 
-  f32x16_t acc[FM][FN];
+    static_assert(KK % 2 == 0, "fragment double buffering assumes an even number of k-substeps");
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j) acc[i][j] = f32x16_t{0};
+    for (int s = 0; s < STAGES - 1; ++s)
+      if (s < k_steps) issue(s, s);
 
-  const int k_steps = K / BKT;
-  static_assert(KK % 2 == 0, "fragment double buffering assumes an even number of k-substeps");
+    // Fragments are double buffered in registers: the LDS reads of substep kk+1 are issued before the
+    // MFMAs of substep kk, across K steps too (the barrier that opens step ks+1 sits before the last
+    // MFMA group of step ks).
+    // A wave whose rows all lie past the end of the expert (ragged last m-tile) neither reads
+    // fragments nor multiplies; it still takes part in the copies and barriers.
+    const bool live = m_rows - m0 - wm * WTM > 0;
+    u32x4 fa[2][FM], fb[2][FN];
+    auto read_frags = [&](int buf, int stage, int kk) {
+      const u32x4* sa = lds + stage * (A_CHUNKS + B_CHUNKS);
+      const u32x4* sb = sa + A_CHUNKS;
 #pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s)
-    if (s < k_steps) issue(s, s);
+      for (int i = 0; i < FM; ++i) {
+        const int r = wm * WTM + i * 32 + col;
+        if (live) fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
+      }
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+        if (live) fb[buf][j] = sb[((wn * FN + j) * KK + kk) * 64 + lane];
+    };
+    auto mfma_frags = [&](int buf) {
+      if (!live) return;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j]);
+    };
 
-  // Fragments are double buffered in registers: the LDS reads of substep kk+1 are issued before the
-  // MFMAs of substep kk, across K steps too (the barrier that opens step ks+1 sits before the last
-  // MFMA group of step ks).
-  // A wave whose rows all lie past the end of the expert (ragged last m-tile) neither reads
-  // fragments nor multiplies; it still takes part in the copies and barriers.
-  const bool live = m_rows - m0 - wm * WTM > 0;
-  u32x4 fa[2][FM], fb[2][FN];
-  auto read_frags = [&](int buf, int stage, int kk) {
-    const u32x4* sa = lds + stage * (A_CHUNKS + B_CHUNKS);
-    const u32x4* sb = sa + A_CHUNKS;
+    // open step 0: its loads have landed once only the younger STAGES-2 groups are outstanding
+    if (STAGES - 1 <= k_steps) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
+    block_barrier();
+    if (STAGES - 1 < k_steps) issue(STAGES - 1, STAGES - 1);   // the last ring slot is still untouched
+    read_frags(0, 0, 0);
+
+    int stage = 0;
+    bool pending = false;   // a K step's copies are partly issued
+    int pend_stage = 0, pend_step = 0;
+    for (int ks = 0; ks < k_steps; ++ks) {
+#pragma unroll
+      for (int kk = 0; kk < KK - 1; ++kk) {
+        if (STAGES >= 3 && pending) issue_piece(pend_stage, pend_step, kk + 1);
+        read_frags((kk + 1) & 1, stage, kk + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(kk & 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      const int next_stage = stage + 1 == STAGES ? 0 : stage + 1;
+      pending = false;
+      if (ks + 1 < k_steps) {
+        // open step ks+1.  Every wave has finished reading this step's buffer (its last fragments are
+        // in registers), so after the barrier that buffer takes the loads of step ks+STAGES.
+        if (ks + STAGES <= k_steps) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragment reads are in registers
+        block_barrier();
+        pending = ks + STAGES < k_steps;
+        pend_stage = stage;
+        pend_step = ks + STAGES;
+        if (pending) {
+          if (STAGES >= 3) issue_piece(pend_stage, pend_step, 0);
+          else issue(pend_stage, pend_step);   // two stages: the data is needed one step from now
+        }
+        read_frags(0, next_stage, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      mfma_frags((KK - 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      stage = next_stage;
+    }
+
+  }
+
+  static __device__ __forceinline__ void epilogue(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
+                                                  const Acc& acc) {
+    const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
+    const int n_out = GATEUP ? c.ffn : c.hidden;
+    const int m0 = loc.mt * BM;
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int wm = wave / WN, wn = wave % WN;
+    const int half = lane / 32, col = lane % 32;
+    // ---- epilogue -----------------------------------------------------------------------
+    // accumulator register r of lane (half, col): row 8*(r/4) + 4*half + r%4, column col
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-      const int r = wm * WTM + i * 32 + col;
-      if (live) fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
-    }
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
-      if (live) fb[buf][j] = sb[((wn * FN + j) * KK + kk) * 64 + lane];
-  };
-  auto mfma_frags = [&](int buf) {
-    if (!live) return;
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * WTM + i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
+        if (m >= m_rows) continue;
+        bf16_t* orow = out + (size_t)(row_first + m) * n_out;
+        if (GATEUP) {
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+          for (int j = 0; j < FN; j += 2) {
+            const int f = nt * (BN / 2) + ((wn * FN + j) / 2) * 32 + col;
+            if (f < n_out) orow[f] = f32_to_bf16(silu_f32(acc[i][j][r]) * acc[i][j + 1][r]);
+          }
+        } else {
 #pragma unroll
-      for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j]);
-  };
-
-  // open step 0: its loads have landed once only the younger STAGES-2 groups are outstanding
-  if (STAGES - 1 <= k_steps) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
-  block_barrier();
-  if (STAGES - 1 < k_steps) issue(STAGES - 1, STAGES - 1);   // the last ring slot is still untouched
-  read_frags(0, 0, 0);
-
-  int stage = 0;
-  bool pending = false;   // a K step's copies are partly issued
-  int pend_stage = 0, pend_step = 0;
-  for (int ks = 0; ks < k_steps; ++ks) {
-#pragma unroll
-    for (int kk = 0; kk < KK - 1; ++kk) {
-      if (STAGES >= 3 && pending) issue_piece(pend_stage, pend_step, kk + 1);
-      read_frags((kk + 1) & 1, stage, kk + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_frags(kk & 1);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    const int next_stage = stage + 1 == STAGES ? 0 : stage + 1;
-    pending = false;
-    if (ks + 1 < k_steps) {
-      // open step ks+1.  Every wave has finished reading this step's buffer (its last fragments are
-      // in registers), so after the barrier that buffer takes the loads of step ks+STAGES.
-      if (ks + STAGES <= k_steps) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
-      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragment reads are in registers
-      block_barrier();
-      pending = ks + STAGES < k_steps;
-      pend_stage = stage;
-      pend_step = ks + STAGES;
-      if (pending) {
-        if (STAGES >= 3) issue_piece(pend_stage, pend_step, 0);
-        else issue(pend_stage, pend_step);   // two stages: the data is needed one step from now
-      }
-      read_frags(0, next_stage, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    mfma_frags((KK - 1) & 1);
-    __builtin_amdgcn_sched_barrier(0);
-    stage = next_stage;
-  }
-
-  // ---- epilogue -----------------------------------------------------------------------
-  // accumulator register r of lane (half, col): row 8*(r/4) + 4*half + r%4, column col
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + wm * WTM + i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
-      if (m >= m_rows) continue;
-      bf16_t* orow = out + (size_t)(row_first + m) * n_out;
-      if (GATEUP) {
-#pragma unroll
-        for (int j = 0; j < FN; j += 2) {
-          const int f = nt * (BN / 2) + ((wn * FN + j) / 2) * 32 + col;
-          if (f < n_out) orow[f] = f32_to_bf16(silu_f32(acc[i][j][r]) * acc[i][j + 1][r]);
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-          const int n = nt * BN + (wn * FN + j) * 32 + col;
-          if (n < n_out) orow[n] = f32_to_bf16(acc[i][j][r]);
+          for (int j = 0; j < FN; ++j) {
+            const int n = nt * BN + (wn * FN + j) * 32 + col;
+            if (n < n_out) orow[n] = f32_to_bf16(acc[i][j][r]);
+          }
         }
       }
     }
   }
-}
-
-template <bool GATEUP, int BM, int BN, int BKT, int STAGES, int WM, int WN>
-static void launch_cfg(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
-  const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
-  c.n_tiles_n = (n_total + BN - 1) / BN;
-  const int busy_max = std::min(c.n_experts, n_rows);
-  const long m_tiles_max = n_rows / BM + busy_max;  // sum over experts of ceil(rows/BM) is at most this
-  const long tiles = m_tiles_max * c.n_tiles_n;
-  c.grid_padded = (int)((tiles + 7) / 8 * 8);
-  hipLaunchKernelGGL((ffn_tiled_kernel<GATEUP, BM, BN, BKT, STAGES, WM, WN>), dim3((unsigned)c.grid_padded),
-                     dim3(64 * WM * WN), 0, s, c, in, out);
-}
+};
 
 // ---------------------------------------------------------------------------------------------
 // Second kernel family: the weights bypass LDS.
@@ -354,171 +349,205 @@ __device__ __forceinline__ void wait_vmcnt_regs(u32x4& a, u32x4& b) {
   asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
 
-template <bool GATEUP, int BM, int NWV, int SA, bool SKIP, bool NT>
-__global__ __launch_bounds__(64 * NWV) void ffn_stream_kernel(TiledCtx c, const bf16_t* __restrict__ in,
-                                                               bf16_t* __restrict__ out) {
-  constexpr int FN = 2, BN = NWV * 64, FM = BM / 32, BKT = 64, KK = 4, DB = 8;
-  constexpr int CPR = BKT / 8, RP = 256 / (BKT * 2);
-  constexpr int A_CHUNKS = BM * CPR;
-  constexpr int A_OPS = A_CHUNKS / (64 * NWV);
+template <bool GATEUP_, int BM_, int NWV, int SA, bool SKIP, bool NT>
+struct StreamTile {
+  static constexpr bool GATEUP = GATEUP_;
+  static constexpr int BM = BM_;
+  static constexpr int FN = 2, BN = NWV * 64, FM = BM / 32, BKT = 64, KK = 4, DB = 8;
+  static constexpr int CPR = BKT / 8, RP = 256 / (BKT * 2);
+  static constexpr int A_CHUNKS = BM * CPR;
+  static constexpr int A_OPS = A_CHUNKS / (64 * NWV);
   static_assert(A_OPS >= 1 && A_OPS * 64 * NWV == A_CHUNKS, "activation tile must split evenly over the waves");
   static_assert(SA >= 3, "the activation ring needs three stages");
-  constexpr int OPS3 = A_OPS - A_OPS * 3 / KK;  // copies issued in the last substep of a step
-  constexpr int N_B = (DB - 1) * FN + (DB / KK) * A_OPS;
-  constexpr int N_A = (SA - 3) * (KK * FN + A_OPS) + 3 * FN + A_OPS - OPS3;
+  static constexpr int OPS3 = A_OPS - A_OPS * 3 / KK;  // copies issued in the last substep of a step
+  static constexpr int N_B = (DB - 1) * FN + (DB / KK) * A_OPS;
+  static constexpr int N_A = (SA - 3) * (KK * FN + A_OPS) + 3 * FN + A_OPS - OPS3;
   static_assert(N_B <= 63 && N_A <= 63, "vmcnt range");
-  __shared__ u32x4 lds[SA * A_CHUNKS];
+  static constexpr int THREADS = 64 * NWV;
+  static constexpr int LDS_VEC = SA * A_CHUNKS;  // 16-byte units
+  typedef f32x16_t Acc[FM][FN];
 
-  TileLoc loc;
-  if (!locate_tile<BM>(c, loc)) return;  // uniform over the block
-  const int e = loc.e, row_first = loc.row_first, m_rows = loc.m_rows, mt = loc.mt, nt = loc.nt;
+  // acc += A[rows of the tile, k range] * W[columns of the tile, k range]^T for the k_steps steps of BKT
+  // that start at step k_begin.  On return every copy into LDS has landed.
+  static __device__ __forceinline__ void mainloop(const TiledCtx& c, const bf16_t* __restrict__ in, const TileLoc& loc,
+                                                  int k_begin, int k_steps, u32x4* lds, Acc& acc) {
+    const int e = loc.e, row_first = loc.row_first, m_rows = loc.m_rows, mt = loc.mt, nt = loc.nt;
+    const int K = GATEUP ? c.hidden : c.ffn;
+    const int n_out = GATEUP ? c.ffn : c.hidden;
+    const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;
+    const int kt16 = K / TILE_K;
+    const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
+    const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
+    const int m0 = mt * BM;
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int half = lane / 32, col = lane % 32;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
 
-  const int K = GATEUP ? c.hidden : c.ffn;
-  const int n_out = GATEUP ? c.ffn : c.hidden;
-  const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;
-  const int kt16 = K / TILE_K;
-  const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
-  const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
-  const int m0 = mt * BM;
-  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
-  const int half = lane / 32, col = lane % 32;
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
-
-  const u32x4* a_src[A_OPS];
+    const u32x4* a_src[A_OPS];
 #pragma unroll
-  for (int i = 0; i < A_OPS; ++i) {
-    const int ci = (i * NWV + wave) * 64 + lane;
-    const int r = ci / CPR, sl = ci % CPR;
-    const int chunk = sl ^ ((r / RP) % CPR);
-    const int row = m0 + r < m_rows ? m0 + r : m_rows - 1;
-    const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row_first + row) : row_first + row;
-    a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk;
+    for (int i = 0; i < A_OPS; ++i) {
+      const int ci = (i * NWV + wave) * 64 + lane;
+      const int r = ci / CPR, sl = ci % CPR;
+      const int chunk = sl ^ ((r / RP) % CPR);
+      const int row = m0 + r < m_rows ? m0 + r : m_rows - 1;
+      const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row_first + row) : row_first + row;
+      a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk + (size_t)k_begin * CPR;
+    }
+    const u32x4* b_src[FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int g = nt * (BN / TILE_N) + wave * FN + j;
+      b_src[j] = w + ((size_t)(g < n_groups ? g : 0) * kt16 + (size_t)k_begin * KK) * 64 + lane;
+    }
+    const int n_sub = k_steps * KK;
+    auto issue_a_piece = [&](int stage, int kstep, int piece) {
+      const uint32_t base = lds0 + (uint32_t)stage * A_CHUNKS * 16;
+      const size_t koff = (size_t)(kstep < k_steps ? kstep : k_steps - 1) * CPR;
+#pragma unroll
+      for (int op = 0; op < A_OPS; ++op)
+        if (op >= A_OPS * piece / KK && op < A_OPS * (piece + 1) / KK)
+          load_to_lds_16(a_src[op] + koff, base + (uint32_t)((op * NWV + wave) * 64) * 16);
+    };
+
+    u32x4 ring[DB][FN];
+    u32x4 fa[2][FM];
+    // SKIP: 32-row fragments past the end of the expert (ragged last m-tile) are neither read nor
+    // multiplied; the count is the same for every wave of the block.
+    const int fm_live = SKIP ? min(FM, (m_rows - m0 + 31) / 32) : FM;
+    auto read_a = [&](int buf, int stage, int kk) {
+      const u32x4* sa = lds + stage * A_CHUNKS;
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        const int r = i * 32 + col;
+        if (!SKIP || i < fm_live) fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
+      }
+    };
+
+    // ---- prologue: fill the weight ring and SA-1 activation stages, then wait for all of it ----
+#pragma unroll
+    for (int s = 0; s < DB; ++s)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) ring[s][j] = load_stream_16<NT>(b_src[j] + (size_t)(s < n_sub ? s : n_sub - 1) * 64);
+#pragma unroll
+    for (int st = 0; st < SA - 1; ++st)
+#pragma unroll
+      for (int p = 0; p < KK; ++p) issue_a_piece(st, st, p);
+    wait_vmcnt<0>();
+    block_barrier();
+    read_a(0, 0, 0);
+
+    int stage = 0;  // ring stage of step tt
+    for (int t = 0; t < k_steps; t += DB / KK) {
+#pragma unroll
+      for (int h = 0; h < DB / KK; ++h) {
+        const int tt = t + h;
+        if (tt < k_steps) {
+          const int next_stage = stage + 1 == SA ? 0 : stage + 1;
+          const int fill_stage = stage == 0 ? SA - 1 : stage - 1;  // held step tt-1, free since this step opened
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk) {
+            constexpr int dummy = 0;
+            (void)dummy;
+            if (kk == KK - 1) {
+              // open step tt+1: its activation tile has landed once at most N_A younger operations are out
+              wait_vmcnt<N_A>();
+              __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragments are in registers
+              block_barrier();
+              read_a((kk + 1) & 1, next_stage, 0);
+            } else {
+              read_a((kk + 1) & 1, stage, kk + 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const int sl = h * KK + kk;  // ring slot of substep 4*tt + kk
+            wait_vmcnt_regs<N_B>(ring[sl][0], ring[sl][1]);
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+              if (!SKIP || i < fm_live) {
+#pragma unroll
+                for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const int s_next = tt * KK + kk + DB;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+              ring[sl][j] = load_stream_16<NT>(b_src[j] + (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64);
+            issue_a_piece(fill_stage, tt + SA - 1, kk);
+          }
+          stage = next_stage;
+        }
+      }
+    }
+    wait_vmcnt<0>();  // the clamped tail copies must not outlive the block's LDS
+
   }
-  const u32x4* b_src[FN];
-#pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int g = nt * (BN / TILE_N) + wave * FN + j;
-    b_src[j] = w + ((size_t)(g < n_groups ? g : 0) * kt16) * 64 + lane;
-  }
-  const int k_steps = K / BKT, n_sub = k_steps * KK;
-  auto issue_a_piece = [&](int stage, int kstep, int piece) {
-    const uint32_t base = lds0 + (uint32_t)stage * A_CHUNKS * 16;
-    const size_t koff = (size_t)(kstep < k_steps ? kstep : k_steps - 1) * CPR;
-#pragma unroll
-    for (int op = 0; op < A_OPS; ++op)
-      if (op >= A_OPS * piece / KK && op < A_OPS * (piece + 1) / KK)
-        load_to_lds_16(a_src[op] + koff, base + (uint32_t)((op * NWV + wave) * 64) * 16);
-  };
 
-  f32x16_t acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j) acc[i][j] = f32x16_t{0};
-  u32x4 ring[DB][FN];
-  u32x4 fa[2][FM];
-  // SKIP: 32-row fragments past the end of the expert (ragged last m-tile) are neither read nor
-  // multiplied; the count is the same for every wave of the block.
-  const int fm_live = SKIP ? min(FM, (m_rows - m0 + 31) / 32) : FM;
-  auto read_a = [&](int buf, int stage, int kk) {
-    const u32x4* sa = lds + stage * A_CHUNKS;
+  static __device__ __forceinline__ void epilogue(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
+                                                  const Acc& acc) {
+    const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
+    const int n_out = GATEUP ? c.ffn : c.hidden;
+    const int m0 = loc.mt * BM;
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int half = lane / 32, col = lane % 32;
+    // ---- epilogue: accumulator register r of lane (half, col) is row 8*(r/4) + 4*half + r%4 ----
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-      const int r = i * 32 + col;
-      if (!SKIP || i < fm_live) fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
-    }
-  };
-
-  // ---- prologue: fill the weight ring and SA-1 activation stages, then wait for all of it ----
 #pragma unroll
-  for (int s = 0; s < DB; ++s)
+      for (int r = 0; r < 16; ++r) {
+        __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps the accumulator reads from piling up
+        const int m = m0 + i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
+        if (m >= m_rows) continue;
+        bf16_t* orow = out + (size_t)(row_first + m) * n_out;
+        if (GATEUP) {
+          const int f = nt * (BN / 2) + wave * 32 + col;
+          if (f < n_out) orow[f] = f32_to_bf16(silu_f32(acc[i][0][r]) * acc[i][1][r]);
+        } else {
 #pragma unroll
-    for (int j = 0; j < FN; ++j) ring[s][j] = load_stream_16<NT>(b_src[j] + (size_t)(s < n_sub ? s : n_sub - 1) * 64);
-#pragma unroll
-  for (int st = 0; st < SA - 1; ++st)
-#pragma unroll
-    for (int p = 0; p < KK; ++p) issue_a_piece(st, st, p);
-  wait_vmcnt<0>();
-  block_barrier();
-  read_a(0, 0, 0);
-
-  int stage = 0;  // ring stage of step tt
-  for (int t = 0; t < k_steps; t += DB / KK) {
-#pragma unroll
-    for (int h = 0; h < DB / KK; ++h) {
-      const int tt = t + h;
-      if (tt < k_steps) {
-        const int next_stage = stage + 1 == SA ? 0 : stage + 1;
-        const int fill_stage = stage == 0 ? SA - 1 : stage - 1;  // held step tt-1, free since this step opened
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          constexpr int dummy = 0;
-          (void)dummy;
-          if (kk == KK - 1) {
-            // open step tt+1: its activation tile has landed once at most N_A younger operations are out
-            wait_vmcnt<N_A>();
-            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragments are in registers
-            block_barrier();
-            read_a((kk + 1) & 1, next_stage, 0);
-          } else {
-            read_a((kk + 1) & 1, stage, kk + 1);
+          for (int j = 0; j < FN; ++j) {
+            const int n = nt * BN + (wave * FN + j) * 32 + col;
+            if (n < n_out) orow[n] = f32_to_bf16(acc[i][j][r]);
           }
-          __builtin_amdgcn_sched_barrier(0);
-          const int sl = h * KK + kk;  // ring slot of substep 4*tt + kk
-          wait_vmcnt_regs<N_B>(ring[sl][0], ring[sl][1]);
-#pragma unroll
-          for (int i = 0; i < FM; ++i) {
-            if (!SKIP || i < fm_live) {
-#pragma unroll
-              for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);
-          const int s_next = tt * KK + kk + DB;
-#pragma unroll
-          for (int j = 0; j < FN; ++j)
-            ring[sl][j] = load_stream_16<NT>(b_src[j] + (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64);
-          issue_a_piece(fill_stage, tt + SA - 1, kk);
-        }
-        stage = next_stage;
-      }
-    }
-  }
-  wait_vmcnt<0>();  // the clamped tail copies must not outlive the block's LDS
-
-  // ---- epilogue: accumulator register r of lane (half, col) is row 8*(r/4) + 4*half + r%4 ----
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps the accumulator reads from piling up
-      const int m = m0 + i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
-      if (m >= m_rows) continue;
-      bf16_t* orow = out + (size_t)(row_first + m) * n_out;
-      if (GATEUP) {
-        const int f = nt * (BN / 2) + wave * 32 + col;
-        if (f < n_out) orow[f] = f32_to_bf16(silu_f32(acc[i][0][r]) * acc[i][1][r]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-          const int n = nt * BN + (wave * FN + j) * 32 + col;
-          if (n < n_out) orow[n] = f32_to_bf16(acc[i][j][r]);
         }
       }
     }
   }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Kernels over a tile type (LdsRingTile or StreamTile).
+
+template <class TILE>
+__device__ __forceinline__ void zero_acc(typename TILE::Acc& acc) {
+#pragma unroll
+  for (int i = 0; i < TILE::FM; ++i)
+#pragma unroll
+    for (int j = 0; j < TILE::FN; ++j) acc[i][j] = f32x16_t{0};
 }
 
-template <bool GATEUP, int BM, int NWV, int SA, bool SKIP, bool NT>
-static void launch_stream(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
-  constexpr int BN = NWV * 64;
-  const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
-  c.n_tiles_n = (n_total + BN - 1) / BN;
-  const int busy_max = std::min(c.n_experts, n_rows);
-  const long tiles = ((long)n_rows / BM + busy_max) * c.n_tiles_n;
-  c.grid_padded = (int)((tiles + 7) / 8 * 8);
-  hipLaunchKernelGGL((ffn_stream_kernel<GATEUP, BM, NWV, SA, SKIP, NT>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in,
-                     out);
+// One block per tile, the whole K range.
+template <class TILE>
+__global__ __launch_bounds__(TILE::THREADS) void ffn_tile_kernel(TiledCtx c, const bf16_t* __restrict__ in,
+                                                                  bf16_t* __restrict__ out) {
+  __shared__ u32x4 lds[TILE::LDS_VEC];
+  TileLoc loc;
+  if (!locate_tile<TILE::BM>(c, loc)) return;  // uniform over the block
+  typename TILE::Acc acc;
+  zero_acc<TILE>(acc);
+  TILE::mainloop(c, in, loc, 0, (TILE::GATEUP ? c.hidden : c.ffn) / TILE::BKT, lds, acc);
+  TILE::epilogue(c, out, loc, acc);
+}
+
+// upper bound of the tile count of a launch (sum over experts of ceil(rows / BM) is at most this)
+static long tiles_upper_bound(const TiledCtx& c, int n_rows, int bm) {
+  return ((long)n_rows / bm + std::min(c.n_experts, n_rows)) * c.n_tiles_n;
+}
+
+template <class TILE>
+static void launch_tiles(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
+  const int n_total = TILE::GATEUP ? 2 * c.ffn : c.hidden;
+  c.n_tiles_n = (n_total + TILE::BN - 1) / TILE::BN;
+  c.grid_padded = (int)((tiles_upper_bound(c, n_rows, TILE::BM) + 7) / 8 * 8);
+  hipLaunchKernelGGL((ffn_tile_kernel<TILE>), dim3((unsigned)c.grid_padded), dim3(TILE::THREADS), 0, s, c, in, out);
 }
 
 // Tile shapes built into the library.  hmoe picks one from the average rows per expert; the
@@ -529,25 +558,27 @@ struct TiledVariant {
   const char* name;
   tiled_launch_fn gate_up, down;
 };
-#define HMOE_TILED_VARIANT(BM, BN, BKT, ST, WM, WN) \
-  { #BM "x" #BN "x" #BKT " s" #ST " w" #WM "x" #WN, launch_cfg<true, BM, BN, BKT, ST, WM, WN>, \
-    launch_cfg<false, BM, BN, BKT, ST, WM, WN> }
+#define HMOE_LDS_RING(BM, BN, BKT, ST, WM, WN) \
+  { #BM "x" #BN "x" #BKT " s" #ST " w" #WM "x" #WN, launch_tiles<LdsRingTile<true, BM, BN, BKT, ST, WM, WN>>, \
+    launch_tiles<LdsRingTile<false, BM, BN, BKT, ST, WM, WN>> }
+#define HMOE_STREAM(NAME, NWV, SKIP, NT) \
+  { NAME, launch_tiles<StreamTile<true, 128, NWV, 4, SKIP, NT>>, launch_tiles<StreamTile<false, 128, NWV, 4, SKIP, NT>> }
 static const TiledVariant kVariants[] = {
-    HMOE_TILED_VARIANT(256, 256, 64, 2, 2, 4),  // 0: 8 waves, 128x64 per wave
-    HMOE_TILED_VARIANT(128, 256, 64, 3, 2, 4),  // 1: 8 waves, 64x64 per wave, 3 stages
-    HMOE_TILED_VARIANT(256, 256, 32, 4, 2, 4),  // 2: as 0 with 4 stages of K 32
-    HMOE_TILED_VARIANT(256, 128, 64, 3, 4, 2),  // 3: 8 waves, 64x64 per wave
-    HMOE_TILED_VARIANT(128, 128, 64, 4, 2, 2),  // 4: 4 waves, 64x64 per wave, 4 stages
-    HMOE_TILED_VARIANT(256, 256, 64, 2, 2, 2),  // 5: 4 waves, 128x128 per wave
-    HMOE_TILED_VARIANT(256, 256, 64, 2, 4, 2),  // 6: 8 waves, 64x128 per wave
-    HMOE_TILED_VARIANT(256, 256, 32, 5, 2, 4),  // 7: as 2 with 5 stages (all of LDS)
-    HMOE_TILED_VARIANT(256, 256, 32, 4, 4, 2),  // 8: as 2, 64x128 per wave
-    {"stream 128x256 s4", launch_stream<true, 128, 4, 4, false, true>, launch_stream<false, 128, 4, 4, false, true>},  // 9: weights bypass LDS, 4 waves
-    {"stream 128x512 s4", launch_stream<true, 128, 8, 4, false, true>, launch_stream<false, 128, 8, 4, false, true>},  // 10: weights bypass LDS, 8 waves
-    {"stream 128x256 s4 skip", launch_stream<true, 128, 4, 4, true, true>, launch_stream<false, 128, 4, 4, true, true>},  // 11: 9 + skip padded fragments
-    {"stream 128x512 s4 skip", launch_stream<true, 128, 8, 4, true, true>, launch_stream<false, 128, 8, 4, true, true>},  // 12: 10 + skip padded fragments
-    {"stream 128x256 s4 plain", launch_stream<true, 128, 4, 4, false, false>, launch_stream<false, 128, 4, 4, false, false>},  // 13: 9 with plain weight loads
-    {"stream 128x512 s4 plain", launch_stream<true, 128, 8, 4, false, false>, launch_stream<false, 128, 8, 4, false, false>},  // 14: 10 with plain weight loads
+    HMOE_LDS_RING(256, 256, 64, 2, 2, 4),  // 0: 8 waves, 128x64 per wave
+    HMOE_LDS_RING(128, 256, 64, 3, 2, 4),  // 1: 8 waves, 64x64 per wave, 3 stages
+    HMOE_LDS_RING(256, 256, 32, 4, 2, 4),  // 2: as 0 with 4 stages of K 32
+    HMOE_LDS_RING(256, 128, 64, 3, 4, 2),  // 3: 8 waves, 64x64 per wave
+    HMOE_LDS_RING(128, 128, 64, 4, 2, 2),  // 4: 4 waves, 64x64 per wave, 4 stages
+    HMOE_LDS_RING(256, 256, 64, 2, 2, 2),  // 5: 4 waves, 128x128 per wave
+    HMOE_LDS_RING(256, 256, 64, 2, 4, 2),  // 6: 8 waves, 64x128 per wave
+    HMOE_LDS_RING(256, 256, 32, 5, 2, 4),  // 7: as 2 with 5 stages (all of LDS)
+    HMOE_LDS_RING(256, 256, 32, 4, 4, 2),  // 8: as 2, 64x128 per wave
+    HMOE_STREAM("stream 128x256 s4", 4, false, true),         // 9: weights bypass LDS, 4 waves
+    HMOE_STREAM("stream 128x512 s4", 8, false, true),         // 10: weights bypass LDS, 8 waves
+    HMOE_STREAM("stream 128x256 s4 skip", 4, true, true),     // 11: 9 + skip padded fragments
+    HMOE_STREAM("stream 128x512 s4 skip", 8, true, true),     // 12: 10 + skip padded fragments
+    HMOE_STREAM("stream 128x256 s4 plain", 4, false, false),  // 13: 9 with plain weight loads
+    HMOE_STREAM("stream 128x512 s4 plain", 8, false, false),  // 14: 10 with plain weight loads
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 

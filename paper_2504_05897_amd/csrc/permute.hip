@@ -11,6 +11,7 @@
 // For A <= 1024 (every decode shape) one block does all three in one launch.
 //   4. gather      x_perm[p] = x[perm[p] / K], 16 bytes per lane
 #include "route_body.h"
+#include "router_body.h"
 
 namespace hmoe {
 
@@ -189,6 +190,31 @@ __global__ __launch_bounds__(PB_THREADS) void route_permute_small_kernel(const f
                           inv_perm);
 }
 
+// Decode batches (T <= 8, bf16): router logits, routing and permutation in ONE block and one launch.
+// The logits go to global memory (they are an output) and to LDS, from where the lane groups route.
+template <int G, int VPL, int NF>
+__global__ __launch_bounds__(PB_THREADS) void front_small_kernel(const bf16_t* __restrict__ x,
+                                                                 const bf16_t* __restrict__ w_g, int hidden,
+                                                                 float* __restrict__ logits, int n_tokens, int n_experts,
+                                                                 int top_k, int key_bits, int32_t* topk_idx,
+                                                                 float* __restrict__ topk_w,
+                                                                 int32_t* __restrict__ expert_offsets,
+                                                                 int32_t* __restrict__ counts_out,
+                                                                 int32_t* __restrict__ perm,
+                                                                 int32_t* __restrict__ inv_perm) {
+  __shared__ float lds_logits[ROUTER_SMALL_T * HMOE_MAX_EXPERTS];
+  router_logits_small<NF>(x, w_g, n_tokens, n_experts, hidden, logits, lds_logits);  // ends with a barrier
+  constexpr int TOKENS_PER_PASS = PB_THREADS / G;
+  for (int t0 = 0; t0 < n_tokens; t0 += TOKENS_PER_PASS) {
+    const long token = t0 + threadIdx.x / G;
+    route_token<G, VPL>(lds_logits, n_experts, top_k, token, token < n_tokens, threadIdx.x % G, topk_idx, topk_w);
+  }
+  __threadfence_block();
+  __syncthreads();
+  permute_rank_body<true>(topk_idx, n_tokens * top_k, n_experts, key_bits, nullptr, expert_offsets, counts_out, perm,
+                          inv_perm);
+}
+
 // x_perm[p, :] = x[perm[p] / K, :], rows of row_bytes (multiple of 16)
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ perm,
                                                           int top_k, int row_vec, int n_assign,
@@ -288,6 +314,48 @@ extern "C" int32_t hmoe_route_permute(const hmoe_layer_desc* desc, const float* 
   else if (E <= 128) HMOE_LAUNCH_SMALL(64, 2);
   else HMOE_LAUNCH_SMALL(64, 4);
 #undef HMOE_LAUNCH_SMALL
+  HMOE_HIP(hipGetLastError());
+  if (h_counts_pinned)
+    HMOE_HIP(hipMemcpyAsync(h_counts_pinned, counts_dev, (size_t)E * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_router_route_permute(const hmoe_layer_desc* desc, const void* x, const void* w_g, int32_t T,
+                                             float* logits, int32_t* topk_idx, float* topk_w, int32_t* expert_offsets,
+                                             int32_t* perm, int32_t* inv_perm, int32_t* h_counts_pinned, void* workspace,
+                                             size_t workspace_bytes, void* stream) {
+  using namespace hmoe;
+  int rc = check_desc(desc);
+  if (rc != HMOE_OK) return rc;
+  if (T < 0 || !expert_offsets) return HMOE_ERR_INVALID_ARG;
+  const long A = (long)T * desc->top_k;
+  if (T == 0 || T > ROUTER_SMALL_T || A > PB_CHUNK || desc->dtype != HMOE_BF16) {  // the separate calls
+    rc = hmoe_router_logits(desc, x, w_g, T, logits, stream);
+    if (rc != HMOE_OK) return rc;
+    return hmoe_route_permute(desc, logits, T, topk_idx, topk_w, expert_offsets, perm, inv_perm, h_counts_pinned,
+                              workspace, workspace_bytes, stream);
+  }
+  if (!x || !w_g || !logits || !topk_idx || !topk_w || !perm || !inv_perm) return HMOE_ERR_INVALID_ARG;
+  if (desc->hidden % 16 != 0) return HMOE_ERR_UNSUPPORTED;
+  if (!aligned16(x) || !aligned16(w_g)) return HMOE_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < hmoe_permute_workspace_bytes(desc, T)) return HMOE_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 3u) return HMOE_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  const int E = desc->n_experts, K = desc->top_k;
+  int key_bits = 0;
+  while ((1 << key_bits) < E) ++key_bits;
+  int32_t* counts_dev = (int32_t*)workspace + (size_t)n_chunks(A) * E;
+#define HMOE_LAUNCH_FRONT(G, VPL, NF)                                                                              \
+  hipLaunchKernelGGL((front_small_kernel<G, VPL, NF>), dim3(1), dim3(PB_THREADS), 0, s, (const bf16_t*)x,          \
+                     (const bf16_t*)w_g, desc->hidden, logits, (int)T, E, K, key_bits, topk_idx, topk_w, expert_offsets, \
+                     counts_dev, perm, inv_perm)
+  if (E <= 8) HMOE_LAUNCH_FRONT(8, 1, 1);
+  else if (E <= 16) HMOE_LAUNCH_FRONT(16, 1, 1);
+  else if (E <= 32) HMOE_LAUNCH_FRONT(32, 1, 1);
+  else if (E <= 64) HMOE_LAUNCH_FRONT(64, 1, 2);
+  else if (E <= 128) HMOE_LAUNCH_FRONT(64, 2, 4);
+  else HMOE_LAUNCH_FRONT(64, 4, 8);
+#undef HMOE_LAUNCH_FRONT
   HMOE_HIP(hipGetLastError());
   if (h_counts_pinned)
     HMOE_HIP(hipMemcpyAsync(h_counts_pinned, counts_dev, (size_t)E * sizeof(int32_t), hipMemcpyDeviceToHost, s));

@@ -135,6 +135,26 @@ def test_router_logits(hm, name, T):
     assert np.abs(lg.cpu().numpy() - ref).max() <= 1e-5 * np.abs(ref).max()
 
 
+@pytest.mark.parametrize("E,H", [(8, 4096), (60, 128), (64, 2048), (100, 3584), (256, 64)])
+def test_router_logits_decode_batches(hm, E, H):
+    """T <= 8 takes the one-block kernel: against the oracle, and the same bits as the many-token kernel
+    gives for the same rows."""
+    say("router_logits small", E, H)
+    rng = np.random.default_rng(E + H)
+    x = wl.store(rng.standard_normal((40, H)).astype(np.float32), wl.BF16)
+    wg = wl.store(rng.standard_normal((E, H)).astype(np.float32) * 0.05, wl.BF16)
+    d = hm.make_desc(H, 64, E, 1, E, hm.HMOE_BF16)
+    xd, wd = to_device(x), to_device(wg)
+    big = torch.empty(40, E, dtype=torch.float32, device=DEV)
+    hm.hmoe_router_logits(d, xd, wd, 40, big)
+    ref = orc.router_logits(wl.as_f64(x), wl.as_f64(wg))
+    assert np.abs(big.cpu().numpy() - ref).max() <= 1e-5 * np.abs(ref).max()
+    for T in (1, 3, 8):
+        small = torch.full((T, E), 99.0, dtype=torch.float32, device=DEV)
+        hm.hmoe_router_logits(d, xd, wd, T, small)
+        assert np.array_equal(small.cpu().numpy(), big.cpu().numpy()[:T])
+
+
 # ----------------------------------------------------------------------------------------- FFN paths
 def _ffn_case(hm, shape, counts, path, seed=0):
     """Grouped FFN over hand-made ragged row groups, every kernel path, against the oracle."""
@@ -382,6 +402,50 @@ def test_route_permute_fused_equals_the_two_calls(hm, T, E, K):
     assert np.array_equal(offs.cpu().numpy(), ro)
     assert np.array_equal(perm.cpu().numpy()[:A], rp) and np.array_equal(inv.cpu().numpy()[:A], ri)
     assert np.array_equal(counts.numpy(), np.diff(ro))
+
+
+@pytest.mark.parametrize("T,E,K,H", [(1, 8, 2, 4096), (8, 8, 2, 256), (1, 64, 6, 2048), (4, 64, 8, 3584), (7, 60, 4, 128),
+                                     (8, 128, 8, 64), (2, 200, 9, 192), (8, 256, 32, 64), (9, 64, 6, 128), (40, 8, 2, 64),
+                                     (0, 8, 2, 64)])
+def test_front_end_fused_equals_the_separate_calls(hm, T, E, K, H):
+    """hmoe_router_route_permute (one launch for bf16, T <= 8; the separate calls otherwise) writes the same
+    bits as hmoe_router_logits + hmoe_route + hmoe_permute, and the integers the oracle derives from them."""
+    say("router_route_permute", T, E, K, H)
+    rng = np.random.default_rng(T + E + K + H)
+    x = wl.store(rng.standard_normal((max(T, 1), H)).astype(np.float32), wl.BF16)
+    wg = wl.store(rng.standard_normal((E, H)).astype(np.float32) * 0.05, wl.BF16)
+    d = hm.make_desc(H, 64, E, K, E, hm.HMOE_BF16)
+    A = T * K
+    xd, wd = to_device(x), to_device(wg)
+    ws_bytes = hm.hmoe_permute_workspace_bytes(d, T)
+    ws = torch.empty(max(ws_bytes, 4), dtype=torch.uint8, device=DEV)
+
+    def buffers():
+        return dict(lg=torch.full((max(T, 1), E), 3.0, dtype=torch.float32, device=DEV),
+                    idx=torch.full((max(T, 1), K), -5, dtype=torch.int32, device=DEV),
+                    w=torch.zeros(max(T, 1), K, dtype=torch.float32, device=DEV),
+                    offs=torch.full((E + 1,), -7, dtype=torch.int32, device=DEV),
+                    perm=torch.full((max(A, 1),), -7, dtype=torch.int32, device=DEV),
+                    inv=torch.full((max(A, 1),), -7, dtype=torch.int32, device=DEV),
+                    counts=torch.zeros(E, dtype=torch.int32, pin_memory=True))
+    f, u = buffers(), buffers()
+    hm.hmoe_router_route_permute(d, xd, wd, T, f["lg"], f["idx"], f["w"], f["offs"], f["perm"], f["inv"], f["counts"],
+                                 ws, ws_bytes)
+    torch.cuda.synchronize()
+    hm.hmoe_router_logits(d, xd, wd, T, u["lg"])
+    hm.hmoe_route(d, u["lg"], T, u["idx"], u["w"])
+    hm.hmoe_permute(d, u["idx"], T, None, None, u["offs"], u["perm"], u["inv"], u["counts"], ws, ws_bytes)
+    torch.cuda.synchronize()
+    for k in f:
+        assert torch.equal(f[k].cpu(), u[k].cpu()), k
+    if T:
+        lg = f["lg"].cpu().numpy()[:T]
+        ridx, _ = orc.route(lg, K)
+        ro, rp, ri = orc.permute(ridx, E)
+        assert np.array_equal(f["idx"].cpu().numpy()[:T], ridx) and np.array_equal(f["offs"].cpu().numpy(), ro)
+        assert np.array_equal(f["perm"].cpu().numpy()[:A], rp) and np.array_equal(f["inv"].cpu().numpy()[:A], ri)
+        ref = orc.router_logits(wl.as_f64(x[:T]), wl.as_f64(wg))
+        assert np.abs(lg - ref).max() <= 1e-5 * np.abs(ref).max()
 
 
 @pytest.mark.parametrize("T", [3, 70])
