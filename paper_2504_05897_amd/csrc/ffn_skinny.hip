@@ -5,8 +5,9 @@
 // observes GPU expert time flat in the workload at small batch, Section III / Fig. 3(f)), so the
 // kernel is organised around the weight stream:
 //   * a block owns `gpb` consecutive 32-row groups of one matrix of one expert (for gate/up: the
-//     matching gate and up groups); its NW waves split K, every wave walks its K range of group
-//     after group as one long stream of 1 KiB tiles;
+//     matching gate and up groups); its NW waves split K in batches of U tiles dealt round-robin, so
+//     at any moment the block reads one contiguous stretch of the group's stream (measured 3-5 %
+//     faster than a contiguous K range per wave: consecutive tiles share DRAM pages);
 //   * a tile is one fully coalesced 16-byte non-temporal load per lane and is already in 32x32x16
 //     bf16 MFMA operand order (packed slot layout), so it goes from HBM to the matrix core through
 //     registers only; two register sets of U tiles alternate, so U tiles per matrix are always in
@@ -75,10 +76,9 @@ __global__ __launch_bounds__(64 * NW) void ffn_skinny_kernel(SkinnyCtx c, const 
   const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
   const u32x4* wbase = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
   const size_t group_stride = (size_t)kt * 64 * NMAT;  // u32x4 per group (gate/up: the pair)
-  // this wave's share of the K tiles, in batches of U
+  // batches of U tiles per wave and group (the last ones may lie partly or wholly past the end of K)
   const int per_wave = ((kt + NW - 1) / NW + U - 1) / U * U;
   const int bpg = per_wave / U;                    // batches per group
-  const int kb_wave = wave * per_wave;
   const int half = lane / 32, col = lane % 32;
   const int n_batches = (g_end - g_begin) * bpg;
 
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(64 * NW) void ffn_skinny_kernel(SkinnyCtx c, const 
     int load_g = g_begin, load_j = 0;  // cursor of the next batch to load
     auto load_batch = [&](int set, bool live) {
       const u32x4* w0 = wbase + (size_t)load_g * group_stride;
-      const int kb = kb_wave + load_j * U;
+      const int kb = (load_j * NW + wave) * U;  // batches dealt round-robin: the block sweeps its stream front to back
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const bool ok = live && kb + u < kt;
