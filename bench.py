@@ -43,7 +43,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="mixtral", choices=sorted(PHASES))
-    ap.add_argument("--layers", type=int, default=0, help="stress: stacked layers (default 27); others: weight sets rotated")
+    ap.add_argument("--layers", type=int, default=0, help="stress: stacked layers (default 27); others: weight sets rotated (default 3)")
     ap.add_argument("--phase", default="", help="run only this phase of the workload (e.g. decode1), for profiling")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true")
@@ -68,7 +68,9 @@ def main() -> int:
     elem = 2 if bf16 else 4
     E, K, H, F = shape.n_experts, shape.top_k, shape.hidden, shape.ffn
     Fs = sum(shape.shared_ffn)
-    n_layers = args.layers or (27 if args.workload == "stress" else 1)
+    # stress: the 27 stacked layers are the step.  Others: three weight sets taken in turn, so that a step
+    # cannot be served from the 256 MB memory-side cache by the previous step's reads
+    n_layers = args.layers or (27 if args.workload == "stress" else 3)
     phases = [p for p in PHASES[args.workload] if not args.phase or p[0] == args.phase]
     assert phases, "workload %s has no phase %r" % (args.workload, args.phase)
     max_T = max(t for _, t in phases)
@@ -157,9 +159,8 @@ def main() -> int:
         routed_ms = ms[0::2] if Fs else ms        # routed call first, shared call second
         shared_ms = ms[1::2] if Fs else np.zeros(0, np.float32)
         # what the routed gate/up kernel touched (distinct experts with rows, last step's routing)
-        li_last = (steps - 1) % n_layers if args.workload != "stress" else n_layers - 1
-        offs = layers[li_last].offsets.cpu().numpy()
-        distinct = int((np.diff(offs) > 0).sum())
+        used = range(n_layers) if args.workload == "stress" else range(min(n_layers, steps))
+        distinct = float(np.mean([(np.diff(layers[li].offsets.cpu().numpy()) > 0).sum() for li in used]))
         return ms_step, float(np.mean(routed_ms)), float(np.mean(shared_ms)) if shared_ms.size else 0.0, distinct
 
     results = {}

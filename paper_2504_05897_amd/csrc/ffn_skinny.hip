@@ -193,15 +193,14 @@ static skinny_launch_fn pick(int shape) {
 }
 
 // Work split for one of the two GEMVs: n_groups 32-row groups per expert, at most busy_max experts
-// with rows.  Measured on the decode shapes, 8 waves per block with 2 tiles per register set is at or
-// near the best everywhere; very few (expert, group) tasks get 16 waves, very many get two groups
-// per block.
+// with rows.  Measured on the decode shapes, 8 waves per block with 2 tiles per register set and one
+// group per block is at or near the best everywhere; very few (expert, group) tasks get 16 waves.
 template <bool GATEUP>
 static void launch_stage(SkinnyCtx c, int n_groups, int busy_max, int max_rows, int kt, const bf16_t* in, bf16_t* out,
                          hipStream_t s) {
   const long tasks = (long)n_groups * busy_max;
   int shape = tasks < 200 ? 5 : 4;
-  int gpb = tasks >= 2048 ? 2 : 1;
+  int gpb = 1;
   if (const char* env = getenv("HMOE_SKINNY")) {  // tuning override: "<shape>,<groups per block>"
     int es = -1, eg = -1;
     if (sscanf(env, "%d,%d", &es, &eg) >= 1 && es >= 0 && es < kNumShapes) shape = es;
