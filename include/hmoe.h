@@ -130,8 +130,8 @@ int32_t hmoe_permute(const hmoe_layer_desc* desc, const int32_t* topk_idx, int32
 
 /*
  * hmoe_route followed by hmoe_permute (without the row gather; see hmoe_expert_ffn_grouped_gather)
- * as one call.  For small batches (T*K <= 1024: every decode shape) both run in a single one-block
- * launch; larger batches run the two calls above.  Arguments and results as in those calls.
+ * as one call.  For small batches (T <= 64 and T*K <= 1024: every decode shape) both run in a single
+ * one-block launch; larger batches run the two calls above.  Arguments and results as in those calls.
  */
 int32_t hmoe_route_permute(const hmoe_layer_desc* desc, const float* logits, int32_t T, int32_t* topk_idx,
                            float* topk_w, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,

@@ -108,20 +108,31 @@ __global__ __launch_bounds__(256) void router_logits_bf16_kernel(const bf16_t* _
   f32x16_t acc[NF];
 #pragma unroll
   for (int j = 0; j < NF; ++j) acc[j] = f32x16_t{0};
-  constexpr int U = 4;
-  for (int kb = kb0; kb < kb1; kb += U) {
-    u32x4 xa[U], wb[U][NF];
+  // two register sets of U k-tiles alternate: the loads of one are in flight while the other is multiplied
+  constexpr int U = NF == 1 ? 8 : NF == 2 ? 4 : NF == 4 ? 2 : 1;
+  u32x4 xa[2][U], wb[2][U][NF];
+  auto load = [&](int set, int kb) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool in_range = kb + u < kb1;
-      xa[u] = (in_range && has_tok) ? xp[(long)(kb + u) * 2] : u32x4{0, 0, 0, 0};
+      xa[set][u] = (in_range && has_tok) ? xp[(long)(kb + u) * 2] : u32x4{0, 0, 0, 0};
 #pragma unroll
-      for (int j = 0; j < NF; ++j) wb[u][j] = (in_range && has_exp[j]) ? wp[j][(long)(kb + u) * 2] : u32x4{0, 0, 0, 0};
+      for (int j = 0; j < NF; ++j)
+        wb[set][u][j] = (in_range && has_exp[j]) ? wp[j][(long)(kb + u) * 2] : u32x4{0, 0, 0, 0};
     }
+  };
+  auto multiply = [&](int set) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int j = 0; j < NF; ++j) acc[j] = mfma_32x32x16_bf16(xa[u], wb[u][j], acc[j]);
+      for (int j = 0; j < NF; ++j) acc[j] = mfma_32x32x16_bf16(xa[set][u], wb[set][u][j], acc[j]);
+  };
+  load(0, kb0);
+  for (int kb = kb0; kb < kb1; kb += 2 * U) {
+    load(1, kb + U);
+    multiply(0);
+    load(0, kb + 2 * U);
+    multiply(1);
   }
   if (wave > 0) {
 #pragma unroll
