@@ -278,6 +278,37 @@ int32_t hmoe_combine(const hmoe_layer_desc* desc, const void* o_perm, const int3
                      const float* topk_w, const void* o_shared, int32_t T, void* y, void* stream);
 
 /* ------------------------------------------------------------------------------------
+ * Hybrid CPU-GPU scheduling simulation (Section IV-B).  HOST ONLY: no device work, no stream.
+ * The activated experts of a layer (load > 0) are placed on three timelines -- CPU compute, GPU
+ * compute, host-to-GPU transfer -- by the paper's priority rules: the GPU takes experts whose weights
+ * are on the GPU, highest load first; the CPU takes uncached experts, lowest load first, and with none
+ * left the lowest-load cached expert; the link moves uncached experts, highest load first, and a moved
+ * expert joins the GPU's list when it has arrived.  Whichever timeline is free first acts next (ties:
+ * CPU, GPU, link; equal loads: lower id).  Cost model: an expert with L rows takes
+ * gpu_base + gpu_per_token * L on the GPU, cpu_base + cpu_per_token * L on the CPU; a transfer takes
+ * `transfer`; all in one unit of the caller's choice, >= 0.
+ *   h_load [n] rows per expert (hmoe_permute's h_counts_pinned); h_cached [n] nonzero = weights in a slot
+ *   h_device [n] out: HMOE_ON_* or -1 (not activated); h_start / h_end [n] out: compute interval (-1 if
+ *   not activated); h_transfer_start [n] out: -1 if not transferred; *makespan out.
+ * hmoe_schedule_simulate runs one rule set (`rules`: which of the three optional operations exist);
+ * HMOE_ERR_UNSUPPORTED if the rules leave an activated expert that nothing may compute.
+ * hmoe_schedule_plan simulates four rule sets -- all rules; without the CPU taking cached experts; the two
+ * fixed mappings the paper compares against (uncached experts on the CPU, no transfers; no CPU, every
+ * uncached expert loaded) -- and returns the first with the smallest makespan (*rules_out, may be NULL).
+ */
+typedef struct hmoe_sched_cost {
+  double gpu_base, gpu_per_token, cpu_base, cpu_per_token, transfer;
+} hmoe_sched_cost;
+enum { HMOE_ON_GPU_CACHED = 0, HMOE_ON_GPU_LOADED = 1, HMOE_ON_CPU = 2 };
+enum { HMOE_SCHED_CPU_UNCACHED = 1, HMOE_SCHED_CPU_CACHED = 2, HMOE_SCHED_TRANSFERS = 4, HMOE_SCHED_ALL = 7 };
+int32_t hmoe_schedule_simulate(int32_t n_experts, const int32_t* h_load, const int32_t* h_cached,
+                               const hmoe_sched_cost* cost, int32_t rules, int32_t* h_device, double* h_start,
+                               double* h_end, double* h_transfer_start, double* makespan);
+int32_t hmoe_schedule_plan(int32_t n_experts, const int32_t* h_load, const int32_t* h_cached,
+                           const hmoe_sched_cost* cost, int32_t* h_device, double* h_start, double* h_end,
+                           double* h_transfer_start, double* makespan, int32_t* rules_out);
+
+/* ------------------------------------------------------------------------------------
  * Timing probe for benchmarks: while armed, every hmoe_expert_ffn_grouped call brackets
  * its first (gate/up) kernel launch with a pair of HIP events on the call's stream.
  * hmoe_probe_arm(max_pairs) creates the events; hmoe_probe_read synchronises them and

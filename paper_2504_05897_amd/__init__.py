@@ -43,6 +43,7 @@ EXPORTS = [
     "hmoe_combine",
     "hmoe_cache_set_policy", "hmoe_cache_update_scores", "hmoe_cache_get_scores",
     "hmoe_route_scores_workspace_bytes", "hmoe_route_scores",
+    "hmoe_schedule_simulate", "hmoe_schedule_plan",
     "hmoe_probe_arm", "hmoe_probe_read",
 ]
 HMOE_POLICY_LRU, HMOE_POLICY_MRS = 0, 1
@@ -54,6 +55,12 @@ class HmoeError(RuntimeError):
         msg = _lib.hmoe_status_string(status).decode()
         detail = _lib.hmoe_last_error().decode() if status == HMOE_ERR_HIP else ""
         super().__init__("%s: %s (%d) %s" % (where, msg, status, detail))
+
+
+class SchedCost(ctypes.Structure):
+    """Cost model of the scheduling simulation (Section IV-B): time = base + per_token * load."""
+    _fields_ = [("gpu_base", ctypes.c_double), ("gpu_per_token", ctypes.c_double), ("cpu_base", ctypes.c_double),
+                ("cpu_per_token", ctypes.c_double), ("transfer", ctypes.c_double)]
 
 
 class LayerDesc(ctypes.Structure):
@@ -105,6 +112,10 @@ def _load() -> ctypes.CDLL:
     lib.hmoe_route_scores_workspace_bytes.restype = sz
     lib.hmoe_route_scores_workspace_bytes.argtypes = [dp, i32]
     lib.hmoe_route_scores.argtypes = [dp, vp, i32, vp, vp, vp, sz, vp]
+    lib.hmoe_schedule_simulate.argtypes = [i32, vp, vp, ctypes.POINTER(SchedCost), i32, vp, vp, vp, vp,
+                                           ctypes.POINTER(ctypes.c_double)]
+    lib.hmoe_schedule_plan.argtypes = [i32, vp, vp, ctypes.POINTER(SchedCost), vp, vp, vp, vp,
+                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     lib.hmoe_probe_arm.argtypes = [i32]
     lib.hmoe_probe_read.argtypes = [vp, i32, ctypes.POINTER(i32)]
     for name in EXPORTS:
@@ -294,6 +305,37 @@ def hmoe_route_scores_workspace_bytes(desc, T) -> int:
 def hmoe_route_scores(desc, logits, T, scores, h_scores_pinned, workspace, workspace_bytes, stream=None):
     _check(_lib.hmoe_route_scores(ctypes.byref(desc), _ptr(logits), T, _ptr(scores), _ptr(h_scores_pinned),
                                   _ptr(workspace), workspace_bytes, _stream(stream)), "hmoe_route_scores")
+
+
+HMOE_ON_GPU_CACHED, HMOE_ON_GPU_LOADED, HMOE_ON_CPU = 0, 1, 2
+HMOE_SCHED_CPU_UNCACHED, HMOE_SCHED_CPU_CACHED, HMOE_SCHED_TRANSFERS, HMOE_SCHED_ALL = 1, 2, 4, 7
+
+
+def _sched_call(fn_name, load, cached, cost, rules):
+    load = np.ascontiguousarray(load, dtype=np.int32)
+    cached = np.ascontiguousarray(cached, dtype=np.int32)
+    n = int(load.shape[0])
+    device = np.zeros(max(n, 1), np.int32)
+    start, end, xfer = (np.zeros(max(n, 1), np.float64) for _ in range(3))
+    makespan = ctypes.c_double(0.0)
+    if rules is None:
+        chosen = ctypes.c_int32(0)
+        _check(_lib.hmoe_schedule_plan(n, _ptr(load), _ptr(cached), ctypes.byref(cost), _ptr(device), _ptr(start),
+                                       _ptr(end), _ptr(xfer), ctypes.byref(makespan), ctypes.byref(chosen)), fn_name)
+        return device[:n], start[:n], end[:n], xfer[:n], makespan.value, chosen.value
+    _check(_lib.hmoe_schedule_simulate(n, _ptr(load), _ptr(cached), ctypes.byref(cost), rules, _ptr(device), _ptr(start),
+                                       _ptr(end), _ptr(xfer), ctypes.byref(makespan)), fn_name)
+    return device[:n], start[:n], end[:n], xfer[:n], makespan.value
+
+
+def hmoe_schedule_simulate(load, cached, cost: SchedCost, rules: int = HMOE_SCHED_ALL):
+    """-> (device [n], start [n], end [n], transfer_start [n], makespan); host only."""
+    return _sched_call("hmoe_schedule_simulate", load, cached, cost, rules)
+
+
+def hmoe_schedule_plan(load, cached, cost: SchedCost):
+    """-> (device, start, end, transfer_start, makespan, rules of the winning strategy); host only."""
+    return _sched_call("hmoe_schedule_plan", load, cached, cost, None)
 
 
 def hmoe_probe_arm(max_pairs: int):

@@ -19,7 +19,7 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhmoe.so")
 
 SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "ffn_reference.hip", "ffn_skinny.hip",
-           "ffn_tiled.hip"]
+           "ffn_tiled.hip", "schedule.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
