@@ -44,6 +44,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="mixtral", choices=sorted(PHASES))
     ap.add_argument("--layers", type=int, default=0, help="stress: stacked layers (default 27); others: weight sets rotated (default 3)")
+    ap.add_argument("--weights", default="bf16", choices=["bf16", "w4"],
+                    help="w4: 4-bit group-wise expert weights (bf16 workloads, decode phases only)")
     ap.add_argument("--phase", default="", help="run only this phase of the workload (e.g. decode1), for profiling")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true")
@@ -72,6 +74,11 @@ def main() -> int:
     # cannot be served from the 256 MB memory-side cache by the previous step's reads
     n_layers = args.layers or (27 if args.workload == "stress" else 3)
     phases = [p for p in PHASES[args.workload] if not args.phase or p[0] == args.phase]
+    w4 = args.weights == "w4"
+    if w4:      # the 4-bit path is the weight-streaming decode kernel
+        assert bf16, "4-bit weights go with bf16 activations"
+        phases = [p for p in phases if p[0].startswith("decode")]
+    w_bytes = (0.5 + 2.0 / 128) if w4 else elem      # bytes per stored expert weight (4-bit: codes + one bf16 scale per 128)
     assert phases, "workload %s has no phase %r" % (args.workload, args.phase)
     max_T = max(t for _, t in phases)
     threads = min(16, len(os.sched_getaffinity(0)))
@@ -91,7 +98,8 @@ def main() -> int:
 
     # ---- layers: all experts resident for the kernel-only figure ------------------------------
     t0 = time.time()
-    desc = hm.make_desc(H, F, E, K, E, hm.HMOE_BF16 if bf16 else hm.HMOE_F32)
+    dtype_id = hm.HMOE_BF16_W4 if w4 else (hm.HMOE_BF16 if bf16 else hm.HMOE_F32)
+    desc = hm.make_desc(H, F, E, K, E, dtype_id)
     layers, host_layers = [], []
     for li in range(n_layers):
         seed = (5000 + li) if args.workload == "stress" else {"toy": 0, "mixtral": 1, "dsv2lite": 2, "qwen2moe": 3}[args.workload] + 100 * li
@@ -171,11 +179,11 @@ def main() -> int:
         tokens = T * (n_layers if args.workload == "stress" else 1)
         # algorithmic work of the routed gate/up kernel: 2 of an expert's 3 matrices per distinct
         # touched expert + activations in/out; 4*H*F flops per assignment
-        gu_bytes = distinct * 2 * H * F * elem + A * H * elem + A * F * elem
+        gu_bytes = distinct * 2 * H * F * w_bytes + A * H * elem + A * F * elem
         gu_flops = 4.0 * H * F * A
         hbm_frac = gu_bytes / (gu_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         mfma_frac = gu_flops / (gu_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS
-        layer_bytes = distinct * 3 * H * F * elem + (3 * H * Fs * elem if Fs else 0)
+        layer_bytes = distinct * 3 * H * F * w_bytes + (3 * H * Fs * w_bytes if Fs else 0)
         layer_flops = 6.0 * H * F * A + 6.0 * H * Fs * T
         per_layer_ms = ms_step / (n_layers if args.workload == "stress" else 1)
         results[name] = {
@@ -202,7 +210,7 @@ def main() -> int:
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):   # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs (see profiles/)
         with open(traffic_file) as fh:
-            roofline["traffic"] = json.load(fh).get("%s/%s" % (args.workload, main_name))
+            roofline["traffic"] = json.load(fh).get("%s/%s%s" % (args.workload, main_name, "+w4" if w4 else ""))
     roofline["kernel"] = "ffn gate/up (routed experts), phase " + main_name
     roofline["kernel_ms"] = main["gate_up_kernel_ms"]
 
@@ -210,7 +218,7 @@ def main() -> int:
     staging = None
     if not args.no_staging and shape.n_slots < E and args.workload != "stress":
         lay0 = host_layers[0]
-        d2 = hm.make_desc(H, F, E, K, shape.n_slots, hm.HMOE_BF16 if bf16 else hm.HMOE_F32)
+        d2 = hm.make_desc(H, F, E, K, shape.n_slots, dtype_id)
         for l in layers[1:]:
             l.close()
         part = hm.MoELayer(d2, lay0.experts, lay0.shared, lay0.w_router, max_tokens=max_T)
@@ -250,11 +258,15 @@ def main() -> int:
             logits = orc.router_logits(wl.as_f64(lay0.x[:main_T]), wl.as_f64(lay0.w_router))
         else:
             logits = lay0.logits[:main_T]
+        decode_weights = wl.as_f64
+        if w4:      # the oracle's own quantiser: every weight replaced by the value its 4-bit code stands for
+            from oracle import w4_oracle
+            decode_weights = lambda m: w4_oracle.dequantize_w4(*w4_oracle.quantize_w4(wl.as_f32(m)))
         t1 = time.time()
         reps = 0
         while True:                       # repeat until about 10 s of host work have been timed
             orc.moe_layer(wl.as_f64(lay0.x[:main_T]), logits, K, lay0.experts, lay0.shared, token_subset=sub,
-                          to_f64=wl.as_f64)
+                          to_f64=decode_weights)
             reps += 1
             dt = time.time() - t1
             if dt >= 10.0 or reps >= 50:
@@ -266,8 +278,8 @@ def main() -> int:
     out = {
         "metric": "MoE-layer tokens/s", "value": main["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": main["ms_per_step"], "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "config": {"workload": "%s/%s" % (args.workload, main_name), "hidden": H, "ffn": F, "experts": E, "top_k": K,
+        "scaling": "weak", "vs_baseline": None, "dtype": ("bf16 (4-bit weights)" if w4 else "bf16") if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": "%s/%s%s" % (args.workload, main_name, "+w4" if w4 else ""), "hidden": H, "ffn": F, "experts": E, "top_k": K,
                    "shared_ffn": list(shape.shared_ffn), "tokens": main_T, "layers": n_layers, "launch": "eager" if args.no_graph else "hip-graph replay",
                    "resident": "all needed experts resident in HBM slots (staging reported separately)"},
         "roofline": roofline, "cpu_baseline": cpu, "phases": results, "staging": staging, "setup_s": setup_s,

@@ -57,7 +57,19 @@ enum {
   HMOE_ERR_HIP = -6
 };
 
-enum { HMOE_F32 = 0, HMOE_BF16 = 1 };
+enum { HMOE_F32 = 0, HMOE_BF16 = 1, HMOE_BF16_W4 = 2 };
+
+/*
+ * HMOE_BF16_W4: activations bfloat16 as for HMOE_BF16, expert weights stored in 4 bits (the paper runs
+ * its experts in 4 bits, Section V, without defining a format; this one is group-wise symmetric):
+ * a matrix W [N, K] is cut along K into groups of 128; scale of (row, group) s = bf16(max|W| / 7), the
+ * maximum and the division in fp32; code q = clamp(rint(W / s), -8, 7) + 8 in fp32 (nearest even), a
+ * group of zeros has s = 0 and codes 8; the value used in the FFN is (q - 8) * s.  hmoe_pack_expert
+ * quantises bfloat16 weights into this format (4.125 bits per weight in the slot).  Needs
+ * H % 128 == 0 and F % 128 == 0.  FFN paths: HMOE_FFN_SKINNY (AUTO at every batch size) and
+ * HMOE_FFN_REFERENCE; HMOE_FFN_TILED -> HMOE_ERR_UNSUPPORTED.  Everything else (router, route, permute,
+ * combine) behaves as for HMOE_BF16.
+ */
 
 /* Which FFN kernels hmoe_expert_ffn_grouped uses.  AUTO picks by token count. */
 enum {
@@ -78,7 +90,7 @@ typedef struct hmoe_layer_desc {
   int32_t n_experts; /* E, 1..HMOE_MAX_EXPERTS                     */
   int32_t top_k;     /* K, 1..min(E, HMOE_MAX_TOP_K)               */
   int32_t n_slots;   /* S, 1..E                                    */
-  int32_t dtype;     /* HMOE_F32 or HMOE_BF16                      */
+  int32_t dtype;     /* HMOE_F32, HMOE_BF16 or HMOE_BF16_W4        */
 } hmoe_layer_desc;
 
 /* Host-side cache object: slot table mirror, use ticks, events.  Opaque. */

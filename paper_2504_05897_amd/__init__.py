@@ -30,6 +30,7 @@ HMOE_ERR_SLOT_BUSY = -5
 HMOE_ERR_HIP = -6
 HMOE_F32 = 0
 HMOE_BF16 = 1
+HMOE_BF16_W4 = 2      # bf16 activations, 4-bit group-wise expert weights
 HMOE_FFN_AUTO, HMOE_FFN_REFERENCE, HMOE_FFN_SKINNY, HMOE_FFN_TILED = 0, 1, 2, 3
 
 # every symbol include/hmoe.h declares
@@ -157,7 +158,7 @@ def make_desc(hidden: int, ffn: int, n_experts: int, top_k: int, n_slots: int, d
 
 
 def torch_dtype(desc: LayerDesc):
-    return torch.bfloat16 if desc.dtype == HMOE_BF16 else torch.float32
+    return torch.float32 if desc.dtype == HMOE_F32 else torch.bfloat16
 
 
 # ---------------------------------------------------------------------------------------------

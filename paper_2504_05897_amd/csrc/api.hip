@@ -3,6 +3,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <cmath>
 #include <new>
 #include <string>
 
@@ -23,7 +24,7 @@ int check_desc(const hmoe_layer_desc* d) {
   if (d->hidden <= 0 || d->ffn <= 0 || d->n_experts <= 0 || d->top_k <= 0 || d->n_slots <= 0)
     return HMOE_ERR_INVALID_ARG;
   if (d->top_k > d->n_experts || d->n_slots > d->n_experts) return HMOE_ERR_INVALID_ARG;
-  if (d->dtype != HMOE_F32 && d->dtype != HMOE_BF16) return HMOE_ERR_INVALID_ARG;
+  if (d->dtype != HMOE_F32 && d->dtype != HMOE_BF16 && d->dtype != HMOE_BF16_W4) return HMOE_ERR_INVALID_ARG;
   if (d->n_experts > HMOE_MAX_EXPERTS || d->top_k > HMOE_MAX_TOP_K) return HMOE_ERR_UNSUPPORTED;
   return HMOE_OK;
 }
@@ -32,6 +33,7 @@ static int check_ffn_shape(const hmoe_layer_desc* d) {
   int rc = check_desc(d);
   if (rc != HMOE_OK) return rc;
   if (d->dtype == HMOE_BF16 && (d->hidden % 64 != 0 || d->ffn % 64 != 0)) return HMOE_ERR_UNSUPPORTED;
+  if (d->dtype == HMOE_BF16_W4 && (d->hidden % W4_GROUP != 0 || d->ffn % W4_GROUP != 0)) return HMOE_ERR_UNSUPPORTED;
   return HMOE_OK;
 }
 
@@ -105,9 +107,53 @@ extern "C" int32_t hmoe_probe_read(float* h_ms, int32_t max, int32_t* n) {
 // ---- weights ---------------------------------------------------------------------------
 extern "C" size_t hmoe_slot_bytes(const hmoe_layer_desc* desc) {
   if (check_desc(desc) != HMOE_OK) return 0;
+  if (desc->dtype == HMOE_BF16_W4) {
+    if (check_ffn_shape(desc) != HMOE_OK) return 0;
+    return w4_offsets((size_t)desc->hidden, (size_t)desc->ffn).total;  // a multiple of 256 for valid shapes
+  }
   const size_t elem = desc->dtype == HMOE_BF16 ? 2 : 4;
   const size_t raw = 3 * (size_t)desc->hidden * desc->ffn * elem;
   return (raw + 255) & ~(size_t)255;
+}
+
+// ---- 4-bit quantisation (host) ------------------------------------------------------------
+static float bf16_bits_to_f32(bf16_t b) {
+  const uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+static bf16_t f32_to_bf16_bits_rne(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+// Quantises src [N, K] (bfloat16, row-major) into the unit stream `units` and the scale array `scales`
+// of a matrix whose packed 16-row group index of source rows [16 q, 16 q + 16) is q * stride + first.
+static void quantize_matrix_w4(const bf16_t* src, int N, int K, uint32_t* units, bf16_t* scales, int stride, int first) {
+  const int n_groups = K / W4_GROUP;
+  for (int n = 0; n < N; ++n) {
+    const int packed_n = ((n / 16) * stride + first) * 16 + n % 16;
+    for (int g = 0; g < n_groups; ++g) {
+      const bf16_t* w = src + (size_t)n * K + (size_t)g * W4_GROUP;
+      float amax = 0.0f;
+      for (int k = 0; k < W4_GROUP; ++k) amax = std::max(amax, std::fabs(bf16_bits_to_f32(w[k])));
+      const bf16_t sb = f32_to_bf16_bits_rne(amax / 7.0f);
+      const float s = bf16_bits_to_f32(sb);
+      scales[w4_scale_index(packed_n, g, n_groups)] = sb;
+      for (int k = 0; k < W4_GROUP; ++k) {
+        int q = 8;
+        if (s != 0.0f) {
+          float r = std::nearbyintf(bf16_bits_to_f32(w[k]) / s);  // nearest even (default rounding mode)
+          r = std::min(7.0f, std::max(-8.0f, r));
+          q = (int)r + 8;
+        }
+        const int kk = g * W4_GROUP + k;
+        units[w4_dword_index(packed_n, kk, K)] |= (uint32_t)q << w4_code_shift(kk);
+      }
+    }
+  }
 }
 
 // rows [n0, n0+32) of src [*, K] -> one 32-row group of tiles at dst
@@ -133,6 +179,16 @@ extern "C" int32_t hmoe_pack_expert(const hmoe_layer_desc* desc, const void* h_w
     memcpy(out, h_w_gate, F * H * 4);
     memcpy(out + F * H, h_w_up, F * H * 4);
     memcpy(out + 2 * F * H, h_w_down, F * H * 4);
+    return HMOE_OK;
+  }
+  if (desc->dtype == HMOE_BF16_W4) {
+    const W4Offsets off = w4_offsets(H, F);
+    char* base = (char*)h_packed_out;
+    memset(base, 0, off.total);
+    quantize_matrix_w4((const bf16_t*)h_w_gate, (int)F, (int)H, (uint32_t*)base, (bf16_t*)(base + off.gate_up_scales), 2, 0);
+    quantize_matrix_w4((const bf16_t*)h_w_up, (int)F, (int)H, (uint32_t*)base, (bf16_t*)(base + off.gate_up_scales), 2, 1);
+    quantize_matrix_w4((const bf16_t*)h_w_down, (int)H, (int)F, (uint32_t*)(base + off.down_units),
+                       (bf16_t*)(base + off.down_scales), 1, 0);
     return HMOE_OK;
   }
   bf16_t* out = (bf16_t*)h_packed_out;
@@ -356,7 +412,7 @@ extern "C" int32_t hmoe_cache_get_scores(const hmoe_cache* c, double* h_out) {
 // ---- FFN dispatch ------------------------------------------------------------------------
 extern "C" size_t hmoe_ffn_workspace_bytes(const hmoe_layer_desc* desc, int32_t A) {
   if (check_desc(desc) != HMOE_OK || A < 0) return 0;
-  const size_t elem = desc->dtype == HMOE_BF16 ? 2 : 4;
+  const size_t elem = desc->dtype == HMOE_F32 ? 4 : 2;
   return (((size_t)A * desc->ffn * elem) + 255) & ~(size_t)255;
 }
 
@@ -401,11 +457,13 @@ static int32_t ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, const
 
   if (path == HMOE_FFN_AUTO) {
     if (desc->dtype == HMOE_F32) path = HMOE_FFN_REFERENCE;
+    else if (desc->dtype == HMOE_BF16_W4) path = HMOE_FFN_SKINNY;  // the weight-streaming kernel at every batch size
     else path = (A / desc->top_k <= 32) ? HMOE_FFN_SKINNY : HMOE_FFN_TILED;
   }
   if (desc->dtype == HMOE_F32 && path != HMOE_FFN_REFERENCE) return HMOE_ERR_UNSUPPORTED;
+  if (desc->dtype == HMOE_BF16_W4 && path == HMOE_FFN_TILED) return HMOE_ERR_UNSUPPORTED;
   if (path == HMOE_FFN_REFERENCE) rc = launch_ffn_reference(a);
-  else if (path == HMOE_FFN_SKINNY) rc = launch_ffn_skinny(a);
+  else if (path == HMOE_FFN_SKINNY) rc = desc->dtype == HMOE_BF16_W4 ? launch_ffn_skinny_w4(a) : launch_ffn_skinny(a);
   else rc = launch_ffn_tiled(a);
   if (rc != HMOE_OK) return rc;
 

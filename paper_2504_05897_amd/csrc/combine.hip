@@ -176,7 +176,7 @@ extern "C" int32_t hmoe_combine(const hmoe_layer_desc* desc, const void* o_perm,
   if (!o_perm || !inv_perm || !topk_w || !y) return HMOE_ERR_INVALID_ARG;
   if (!aligned16(o_perm) || !aligned16(y) || (o_shared && !aligned16(o_shared))) return HMOE_ERR_INVALID_ARG;
   hipStream_t s = (hipStream_t)stream;
-  if (desc->dtype == HMOE_BF16) {
+  if (desc->dtype != HMOE_F32) {
     if (desc->hidden % 8 != 0) return HMOE_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(combine_bf16_kernel, dim3((unsigned)T), dim3(256), 0, s, (const uint4*)o_perm, inv_perm, topk_w,
                        (const uint4*)o_shared, desc->top_k, desc->hidden / 8, (uint4*)y);
@@ -198,7 +198,7 @@ extern "C" int32_t hmoe_router_logits(const hmoe_layer_desc* desc, const void* x
   if (!x || !w_g || !logits) return HMOE_ERR_INVALID_ARG;
   hipStream_t s = (hipStream_t)stream;
   const int E = desc->n_experts, H = desc->hidden;
-  if (desc->dtype == HMOE_BF16) {
+  if (desc->dtype != HMOE_F32) {
     if (H % 16 != 0) return HMOE_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(w_g)) return HMOE_ERR_INVALID_ARG;
     const dim3 grid((unsigned)((T + 31) / 32)), block(256);

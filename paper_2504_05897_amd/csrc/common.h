@@ -22,6 +22,14 @@ __device__ __forceinline__ f32x16_t mfma_32x32x16_bf16(u32x4 a, u32x4 b, f32x16_
                                                  0, 0, 0);
 }
 
+// D = A(16x32) * B(32x16) + C.  Lane l supplies A[l%16][8*(l/16) .. +8] and B[8*(l/16) .. +8][l%16];
+// accumulator register r of lane l is D[4*(l/16) + r][l%16].
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f32x4_t mfma_16x16x32_bf16(u32x4 a, u32x4 b, f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                 0, 0, 0);
+}
+
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
 // round to nearest, ties to even (inputs are finite on this path)
@@ -77,6 +85,39 @@ void probe_before(hipStream_t s);
 void probe_after(hipStream_t s);
 
 // kernel launchers, one per source file ---------------------------------------------------
+// --- 4-bit weight layout (HMOE_BF16_W4) -------------------------------------------------------
+// A matrix W [N, K] is stored as a stream of 1 KiB units, each 16 rows x 128 k (one scale group),
+// ordered [N/16][K/128] (k fastest), followed by its scales [N/16][K/128][16 rows] in bfloat16.
+// Inside a unit lane l of a wavefront (row l % 16, k block l / 16) owns 16 bytes: dword t holds the 8
+// codes of k = 128 unit + 32 t + 8 (l / 16) + j, code j at bit 16 (j & 1) + 4 (j >> 1) -- the operand
+// order of v_mfma_f32_16x16x32_bf16 (B operand: column l % 16, k = 8 (l / 16) .. + 8), one k-step of 32
+// per dword.  With that nibble order ((dword >> 4 i) & 0x000F000F) | 0x43004300 is register i of the
+// operand holding the bfloat16 values 128 + q (bfloat16 0x4300 is 128 and its mantissa step there is 1).
+// A slot is [gate/up units][gate/up scales][down units][down scales]; gate and up rows are interleaved
+// in 16-row groups (packed group 2 q = gate rows 16 q .., 2 q + 1 = up rows 16 q ..).
+constexpr int W4_GROUP = 128;
+struct W4Offsets {
+  size_t gate_up_scales, down_units, down_scales, total;  // byte offsets within a slot (gate/up units at 0)
+};
+__host__ __device__ inline W4Offsets w4_offsets(size_t hidden, size_t ffn) {
+  W4Offsets o;
+  const size_t hf = hidden * ffn;
+  o.gate_up_scales = hf;                       // 2F x H codes, two per byte
+  o.down_units = o.gate_up_scales + hf / 32;   // 2F x H/128 scales of 2 bytes
+  o.down_scales = o.down_units + hf / 2;
+  o.total = o.down_scales + hf / 64;
+  return o;
+}
+// index of the dword that holds the code of W[n][k] (K columns), and the bit position of the code in it
+__host__ __device__ inline size_t w4_dword_index(int n, int k, int K) {
+  const int lane = ((k % 32) / 8) * 16 + n % 16;
+  return (((size_t)(n / 16) * (K / W4_GROUP) + k / W4_GROUP) * 64 + lane) * 4 + (k % W4_GROUP) / 32;
+}
+__host__ __device__ inline int w4_code_shift(int k) { return 16 * (k & 1) + 4 * ((k % 8) >> 1); }
+__host__ __device__ inline size_t w4_scale_index(int n, int group, int n_groups) {
+  return ((size_t)(n / 16) * n_groups + group) * 16 + n % 16;
+}
+
 struct FfnArgs {
   const hmoe_layer_desc* desc = nullptr;
   const void* x_perm = nullptr;       // rows of the gate/up input; with row_map: the un-permuted x [T, H]
@@ -95,6 +136,7 @@ struct FfnArgs {
 int launch_ffn_reference(const FfnArgs& a);
 int launch_ffn_skinny(const FfnArgs& a);
 int launch_ffn_tiled(const FfnArgs& a);
+int launch_ffn_skinny_w4(const FfnArgs& a);
 
 }  // namespace hmoe
 

@@ -1,5 +1,6 @@
 // Reference FFN kernels (HMOE_FFN_REFERENCE): one wavefront per output element, lanes stride
-// the reduction dimension.  Any shape; fp32 (plain row-major slots) and bf16 (packed slots).
+// the reduction dimension.  Any shape; fp32 (plain row-major slots), bf16 (packed slots) and 4-bit
+// weights (decoded element by element).
 // This is the path of the fp32 toy workload and the in-library cross-check for the MFMA paths.
 #include "common.h"
 
@@ -111,6 +112,51 @@ __global__ __launch_bounds__(256) void ref_down_bf16(RefCtx c, const bf16_t* __r
   if (lane == 0) o[(size_t)p * c.hidden + n] = f32_to_bf16(acc);
 }
 
+// 4-bit weights: value of W[n][k] of a matrix with K columns stored at `units` / `scales`
+__device__ __forceinline__ float w4_value(const uint32_t* __restrict__ units, const bf16_t* __restrict__ scales, int n, int k,
+                                          int K) {
+  const int q = (units[w4_dword_index(n, k, K)] >> w4_code_shift(k)) & 15;
+  return (float)(q - 8) * bf16_to_f32(scales[w4_scale_index(n, k / W4_GROUP, K / W4_GROUP)]);
+}
+
+__global__ __launch_bounds__(256) void ref_gateup_w4(RefCtx c, const bf16_t* __restrict__ x, bf16_t* __restrict__ h) {
+  const int p = blockIdx.x, wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int f = blockIdx.y * 4 + wave;
+  if (f >= c.ffn) return;
+  const char* slot = row_slot(c, p);
+  if (!slot) return;
+  const W4Offsets off = w4_offsets((size_t)c.hidden, (size_t)c.ffn);
+  const uint32_t* units = (const uint32_t*)slot;
+  const bf16_t* scales = (const bf16_t*)(slot + off.gate_up_scales);
+  const int n_gate = 32 * (f / 16) + f % 16, n_up = n_gate + 16;  // gate and up interleaved in 16-row groups
+  const bf16_t* xr = x + (size_t)mapped_row(c.row_map, c.map_div, p) * c.hidden;
+  float g = 0.0f, u = 0.0f;
+  for (int k = lane; k < c.hidden; k += 64) {
+    const float xv = bf16_to_f32(xr[k]);
+    g = fmaf(w4_value(units, scales, n_gate, k, c.hidden), xv, g);
+    u = fmaf(w4_value(units, scales, n_up, k, c.hidden), xv, u);
+  }
+  g = wave_sum(g);
+  u = wave_sum(u);
+  if (lane == 0) h[(size_t)p * c.ffn + f] = f32_to_bf16(g / (1.0f + expf(-g)) * u);
+}
+
+__global__ __launch_bounds__(256) void ref_down_w4(RefCtx c, const bf16_t* __restrict__ h, bf16_t* __restrict__ o) {
+  const int p = blockIdx.x, wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int n = blockIdx.y * 4 + wave;
+  if (n >= c.hidden) return;
+  const char* slot = row_slot(c, p);
+  if (!slot) return;
+  const W4Offsets off = w4_offsets((size_t)c.hidden, (size_t)c.ffn);
+  const uint32_t* units = (const uint32_t*)(slot + off.down_units);
+  const bf16_t* scales = (const bf16_t*)(slot + off.down_scales);
+  const bf16_t* hr = h + (size_t)p * c.ffn;
+  float acc = 0.0f;
+  for (int k = lane; k < c.ffn; k += 64) acc = fmaf(w4_value(units, scales, n, k, c.ffn), bf16_to_f32(hr[k]), acc);
+  acc = wave_sum(acc);
+  if (lane == 0) o[(size_t)p * c.hidden + n] = f32_to_bf16(acc);
+}
+
 int launch_ffn_reference(const FfnArgs& a) {
   const hmoe_layer_desc& d = *a.desc;
   if (a.n_rows == 0) return HMOE_OK;
@@ -120,11 +166,15 @@ int launch_ffn_reference(const FfnArgs& a) {
   probe_before(a.stream);
   if (d.dtype == HMOE_F32)
     hipLaunchKernelGGL(ref_gateup_f32, g1, dim3(256), 0, a.stream, c, (const float*)a.x_perm, (float*)a.h);
+  else if (d.dtype == HMOE_BF16_W4)
+    hipLaunchKernelGGL(ref_gateup_w4, g1, dim3(256), 0, a.stream, c, (const bf16_t*)a.x_perm, (bf16_t*)a.h);
   else
     hipLaunchKernelGGL(ref_gateup_bf16, g1, dim3(256), 0, a.stream, c, (const bf16_t*)a.x_perm, (bf16_t*)a.h);
   probe_after(a.stream);
   if (d.dtype == HMOE_F32)
     hipLaunchKernelGGL(ref_down_f32, g2, dim3(256), 0, a.stream, c, (const float*)a.h, (float*)a.o_perm);
+  else if (d.dtype == HMOE_BF16_W4)
+    hipLaunchKernelGGL(ref_down_w4, g2, dim3(256), 0, a.stream, c, (const bf16_t*)a.h, (bf16_t*)a.o_perm);
   else
     hipLaunchKernelGGL(ref_down_bf16, g2, dim3(256), 0, a.stream, c, (const bf16_t*)a.h, (bf16_t*)a.o_perm);
   HMOE_HIP(hipGetLastError());

@@ -229,4 +229,197 @@ int launch_ffn_skinny(const FfnArgs& a) {
   return HMOE_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// 4-bit weights (HMOE_BF16_W4): the same organisation around the weight stream, a quarter of the bytes.
+//
+// A block owns two adjacent packed 16-row groups of one busy expert: gate and up of 16 features, or 32
+// features of the down projection.  The unit of work is a scale
+// group of 128 k: one 1 KiB unit of codes per 16-row group (one 16-byte non-temporal load per lane), four
+// token fragments and one scale per lane and 16-row group.  Scale groups are dealt round-robin to the NW
+// waves (the block sweeps a contiguous stretch of the stream) and the codes of DEPTH groups are in
+// flight per wave: a group is multiplied in a fraction of the memory latency, so a single group of
+// lookahead would leave the wave waiting.
+//
+// The matrix instruction is v_mfma_f32_16x16x32_bf16: up to 16 tokens x 16 features x 32 k, four
+// accumulator registers, which suits decode (the 32x32x16 shape spends twice the cycles and four times the
+// registers on rows that are padding).  Codes go to it without an integer-to-float conversion: a dword of
+// 8 codes becomes the four operand registers of bfloat16 values 128 + q with one shift and one and-or
+// each (see the layout note in common.h).  The offset is taken out again with one more MFMA per k-step
+// against a tile of ones, which yields sum_k x_k per token in the accumulator layout:
+//     sum_k x_k (q_k - 8) = sum_k x_k (128 + q_k) - 136 sum_k x_k,
+// and the group's scale (per feature = per lane) multiplies that difference as it is added to the
+// running fp32 result.  Products x * (128 + q) are exact in fp32; the cancellation costs about 5 of
+// its 24 mantissa bits.
+template <bool GATEUP, int NW>
+__global__ __launch_bounds__(64 * NW) void ffn_skinny_w4_kernel(SkinnyCtx c, const bf16_t* __restrict__ in,
+                                                                 bf16_t* __restrict__ out) {
+  constexpr int NU = 2;                    // packed 16-row groups per block
+  constexpr int FEAT = GATEUP ? 16 : 32;   // output features per block
+  constexpr int MR = 16;              // rows per pass
+  constexpr int DEPTH = 4;
+  __shared__ float red[(NW > 1 ? NW - 1 : 1) * NU * 4 * 64];
+
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int e = nth_busy_expert(c, blockIdx.y, lane);
+  if (e < 0) return;  // uniform over the block
+  const int row_first = c.offsets[e], row_end = c.offsets[e + 1];
+  const int K = GATEUP ? c.hidden : c.ffn;      // reduction length
+  const int n_out = GATEUP ? c.ffn : c.hidden;  // row length of `out`
+  const int n_groups = K / W4_GROUP;
+  const int fb = blockIdx.x;                    // features [FEAT fb, FEAT fb + FEAT) of `out`
+  if (fb >= n_out / FEAT) return;
+  const int j = lane % 16, kblk = lane / 16;
+  const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
+  const W4Offsets off = w4_offsets((size_t)c.hidden, (size_t)c.ffn);
+  const u32x4* units = (const u32x4*)(slot + (GATEUP ? 0 : off.down_units));
+  const bf16_t* scales = (const bf16_t*)(slot + (GATEUP ? off.gate_up_scales : off.down_scales));
+  // packed 16-row group 2 fb + u: gate/up u = 0, 1 are gate and up of features 16 fb .. + 16; down u = 0, 1 are
+  // features 32 fb .. + 16 and the next 16
+  const u32x4* wq[NU];
+  const bf16_t* ws[NU];
+#pragma unroll
+  for (int u = 0; u < NU; ++u) {
+    const size_t grp = (size_t)NU * fb + u;
+    wq[u] = units + grp * (size_t)n_groups * 64 + lane;
+    ws[u] = scales + grp * (size_t)n_groups * 16 + j;
+  }
+  const int per_wave = (n_groups + NW - 1) / NW;  // scale groups per wave (the last ones may lie past the end)
+  const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+
+  for (int row0 = row_first; row0 < row_end; row0 += MR) {
+    const int rows = min(MR, row_end - row0);
+    const int tok = j < rows ? j : 0;  // lane (j, kblk) supplies token j, k block kblk of the token operand (clamped)
+    const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row0 + tok) : row0 + tok;
+    const u32x4* xin = (const u32x4*)(in + (size_t)in_row * K) + kblk;
+
+    // ring of DEPTH scale groups per wave: codes, scales and the matching token fragments (the fragments
+    // come from L1/L2, but a group is multiplied faster than even that latency).  Every load is issued
+    // unconditionally from a clamped, valid address -- no branches around loads, so the compiler's count
+    // of outstanding loads stays exact and a multiply waits only for its own group.  A group past the end
+    // contributes nothing because its scale is replaced by zero at use; token rows past `rows` only reach
+    // accumulator rows that are never stored.
+    u32x4 codes[DEPTH][NU], xa[DEPTH][4];
+    uint32_t scale_bits[DEPTH][NU];  // raw bfloat16: converting here would make the wave wait for the load at once
+    bool live[DEPTH];
+    auto load_group = [&](int slot_id, int i) {
+      const int g = i * NW + wave;
+      live[slot_id] = i < per_wave && g < n_groups;
+      const int gc = min(g, n_groups - 1);
+#pragma unroll
+      for (int u = 0; u < NU; ++u) {
+        codes[slot_id][u] = __builtin_nontemporal_load(wq[u] + (size_t)gc * 64);
+        scale_bits[slot_id][u] = (uint32_t)ws[u][(size_t)gc * 16];
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) xa[slot_id][t] = xin[(size_t)(16 * gc + 4 * t)];
+    };
+
+    f32x4_t acc[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) acc[u] = f32x4_t{0, 0, 0, 0};
+    auto multiply_group = [&](int slot_id) {
+      f32x4_t part[NU], xsum = {0, 0, 0, 0};
+#pragma unroll
+      for (int u = 0; u < NU; ++u) part[u] = f32x4_t{0, 0, 0, 0};
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        xsum = mfma_16x16x32_bf16(xa[slot_id][t], ones, xsum);
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+          const uint32_t d = codes[slot_id][u][t];
+          const u32x4 w = {(d & 0x000F000Fu) | 0x43004300u, ((d >> 4) & 0x000F000Fu) | 0x43004300u,
+                           ((d >> 8) & 0x000F000Fu) | 0x43004300u, ((d >> 12) & 0x000F000Fu) | 0x43004300u};
+          part[u] = mfma_16x16x32_bf16(xa[slot_id][t], w, part[u]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < NU; ++u) {
+        const float sc = live[slot_id] ? __uint_as_float(scale_bits[slot_id][u] << 16) : 0.0f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[u][r] += sc * (part[u][r] - 136.0f * xsum[r]);
+      }
+    };
+
+    // the scheduling barriers keep the loads where they are written: left alone, the compiler moves them
+    // down to their uses to save registers, and with them the lookahead
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) load_group(d, d);
+    __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < per_wave; i += DEPTH) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        multiply_group(d);
+        __builtin_amdgcn_sched_barrier(0);
+        load_group(d, i + d + DEPTH);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+
+    // ---- cross-wave reduction, epilogue, store ---------------------------------------------
+    // accumulator register r of lane (j, kblk) is token 4 kblk + r, feature j of the 16-row group
+    if (NW > 1 && wave > 0) {
+      float* dst = red + (size_t)(wave - 1) * NU * 4 * 64;
+#pragma unroll
+      for (int u = 0; u < NU; ++u)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dst[(u * 4 + r) * 64 + lane] = acc[u][r];
+    }
+    if (NW > 1) __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int u = 0; u < NU; ++u)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          for (int w = 0; w < NW - 1; ++w) acc[u][r] += red[((size_t)w * NU * 4 + u * 4 + r) * 64 + lane];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = 4 * kblk + r;
+        if (m >= rows) continue;
+        bf16_t* orow = out + (size_t)(row0 + m) * n_out + FEAT * fb + j;
+        if (GATEUP) {
+          orow[0] = f32_to_bf16(silu_f32(acc[0][r]) * acc[1][r]);
+        } else {
+          orow[0] = f32_to_bf16(acc[0][r]);
+          orow[16] = f32_to_bf16(acc[1][r]);
+        }
+      }
+    }
+    if (NW > 1) __syncthreads();  // the reduction area is reused by the next row pass
+  }
+}
+
+template <bool GATEUP>
+static void launch_stage_w4(const SkinnyCtx& c, int n_out, int busy_max, const bf16_t* in, bf16_t* out, hipStream_t s) {
+  const dim3 grid((unsigned)(n_out / (GATEUP ? 16 : 32)), (unsigned)busy_max);
+  // Waves per block (they split K).  A wave that walks many scale groups keeps its ring of loads full; a
+  // block whose waves each see only a few groups spends its life filling and draining it.  So: as few waves
+  // per block as still put about eight waves on every CU (measured: one wave per block is best for the wide
+  // gate/up launch, eight for the down projection of two experts).
+  const long blocks = (long)grid.x * grid.y;
+  const int n_groups = (GATEUP ? c.hidden : c.ffn) / W4_GROUP;
+  int waves = 1;
+  while (waves < 8 && blocks * waves < 2048 && n_groups / (2 * waves) >= 2) waves *= 2;
+  if (const char* env = getenv("HMOE_W4_WAVES")) waves = atoi(env);  // tuning override: 1, 2, 4 or 8
+  switch (waves) {
+    case 1: hipLaunchKernelGGL((ffn_skinny_w4_kernel<GATEUP, 1>), grid, dim3(64), 0, s, c, in, out); break;
+    case 2: hipLaunchKernelGGL((ffn_skinny_w4_kernel<GATEUP, 2>), grid, dim3(128), 0, s, c, in, out); break;
+    case 4: hipLaunchKernelGGL((ffn_skinny_w4_kernel<GATEUP, 4>), grid, dim3(256), 0, s, c, in, out); break;
+    default: hipLaunchKernelGGL((ffn_skinny_w4_kernel<GATEUP, 8>), grid, dim3(512), 0, s, c, in, out); break;
+  }
+}
+
+int launch_ffn_skinny_w4(const FfnArgs& a) {
+  const hmoe_layer_desc& d = *a.desc;
+  if (d.dtype != HMOE_BF16_W4) return HMOE_ERR_UNSUPPORTED;
+  if (a.n_rows == 0) return HMOE_OK;
+  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div};
+  const int busy_max = std::min(d.n_experts, a.n_rows);  // every busy expert has at least one row
+  probe_before(a.stream);
+  launch_stage_w4<true>(c, d.ffn, busy_max, (const bf16_t*)a.x_perm, (bf16_t*)a.h, a.stream);
+  probe_after(a.stream);
+  launch_stage_w4<false>(c, d.hidden, busy_max, (const bf16_t*)a.h, (bf16_t*)a.o_perm, a.stream);
+  HMOE_HIP(hipGetLastError());
+  return HMOE_OK;
+}
+
 }  // namespace hmoe

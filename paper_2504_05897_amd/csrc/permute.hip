@@ -252,7 +252,7 @@ extern "C" int32_t hmoe_permute(const hmoe_layer_desc* desc, const int32_t* topk
   if (A > 0x7fffffffL - PB_CHUNK) return HMOE_ERR_UNSUPPORTED;
   if (A > 0 && (!topk_idx || !perm || !inv_perm)) return HMOE_ERR_INVALID_ARG;
   if ((x == nullptr) != (x_perm == nullptr)) return HMOE_ERR_INVALID_ARG;
-  const size_t elem = desc->dtype == HMOE_BF16 ? 2 : 4;
+  const size_t elem = desc->dtype == HMOE_F32 ? 4 : 2;
   const size_t row_bytes = (size_t)desc->hidden * elem;
   if (x && (row_bytes % 16 != 0)) return HMOE_ERR_UNSUPPORTED;
   if (x && (!aligned16(x) || !aligned16(x_perm))) return HMOE_ERR_INVALID_ARG;
@@ -334,7 +334,7 @@ extern "C" int32_t hmoe_router_route_permute(const hmoe_layer_desc* desc, const 
   if (rc != HMOE_OK) return rc;
   if (T < 0 || !expert_offsets) return HMOE_ERR_INVALID_ARG;
   const long A = (long)T * desc->top_k;
-  if (T == 0 || T > ROUTER_SMALL_T || A > PB_CHUNK || desc->dtype != HMOE_BF16) {  // the separate calls
+  if (T == 0 || T > ROUTER_SMALL_T || A > PB_CHUNK || desc->dtype == HMOE_F32) {  // the separate calls
     rc = hmoe_router_logits(desc, x, w_g, T, logits, stream);
     if (rc != HMOE_OK) return rc;
     return hmoe_route_permute(desc, logits, T, topk_idx, topk_w, expert_offsets, perm, inv_perm, h_counts_pinned,
