@@ -34,6 +34,20 @@ def _run(cmd):
     return out
 
 
+def kernels_with_scratch(remarks: str):
+    """Kernel names whose resource-usage remarks report private (scratch) memory, i.e. register spills."""
+    bad, name = [], None
+    for line in remarks.splitlines():
+        if "remark:" not in line:
+            continue
+        text = line.split("remark:", 1)[1]
+        if "Function Name:" in text:
+            name = text.split("Function Name:", 1)[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in text and int(text.split(":", 1)[1].split("[")[0]) > 0:
+            bad.append(name)
+    return bad
+
+
 def build(verbose: bool = False, extra_flags=()) -> str:
     os.makedirs(BUILD, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -41,10 +55,20 @@ def build(verbose: bool = False, extra_flags=()) -> str:
 
     def compile_one(pair):
         src, obj = pair
-        return _run([hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj])
+        return _run([hipcc, *FLAGS, "-Rpass-analysis=kernel-resource-usage", *extra_flags, "-c", os.path.join(CSRC, src),
+                     "-o", obj])
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
         logs = list(pool.map(compile_one, zip(SOURCES, objs)))
+    # No kernel of this library may spill registers.  The prefill kernels issue their loads by hand and count the
+    # outstanding ones themselves; the compiler treats the destination of such a load as written at once, so under
+    # register pressure it may spill and reuse that register before the data lands (observed: a late load then
+    # overwrote a pointer and the launch faulted).  A variant that does not fit the register file is a build error.
+    spilled = [k for log in logs for k in kernels_with_scratch(log)]
+    if spilled:
+        raise RuntimeError("kernels that spill registers (private memory) are not allowed:\n  " + "\n  ".join(spilled))
+    logs = ["\n".join(l for l in log.splitlines() if "kernel-resource-usage" not in l and not l.lstrip().startswith(("|", "^"))
+                      and not l.strip()[:1].isdigit()) for log in logs]
     logs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]))
     if verbose:
         for log in logs:
