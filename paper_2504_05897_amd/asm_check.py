@@ -1,0 +1,91 @@
+"""Build-time check of the device assembly for registers reused while a hand-issued load is in flight.
+
+The prefill kernels issue their weight loads from inline assembly and wait for them with explicit
+s_waitcnt vmcnt(N).  The compiler does not know that such a load completes later: a destination register
+whose value it considers dead may be handed out again at once, as the destination of the next load or as
+scratch for an address computation, and the data that lands afterwards then corrupts that value (seen once:
+the clobbered value was an address and the launch faulted).  The sources keep every such register alive up
+to a wait; this scan is the net under that rule.
+
+The scan is linear over each kernel's text, with the hardware's counter model: every vector-memory
+instruction enters a queue, s_waitcnt vmcnt(N) retires all but the youngest N.  While a hand-issued load is
+queued, any instruction that writes one of its destination registers, or that uses one as an address, is
+reported.  Reads by arithmetic instructions are not checked (the sources tie those to the waits, and the
+compiler places some of them out of line, which a linear scan cannot follow).
+"""
+from __future__ import annotations
+
+import re
+from typing import Iterable, List, Set, Tuple
+
+_SPLIT = re.compile(r",\s*(?![^\[]*\])")
+
+
+def _vregs(operand: str) -> Set[int]:
+    operand = operand.split(" ")[0]
+    m = re.fullmatch(r"v\[(\d+):(\d+)\]", operand)
+    if m:
+        return set(range(int(m.group(1)), int(m.group(2)) + 1))
+    m = re.fullmatch(r"v(\d+)", operand)
+    return {int(m.group(1))} if m else set()
+
+
+def _scan_kernel(name: str, lines: Iterable[Tuple[int, str]]) -> List[str]:
+    queue: List[Tuple[Set[int], int]] = []   # (destination registers of a hand-issued load or empty, line)
+    found: List[str] = []
+    in_asm = False
+    for no, raw in lines:
+        text = raw.strip()
+        if text.startswith(";;#ASMSTART"):
+            in_asm = True
+            continue
+        if text.startswith(";;#ASMEND"):
+            in_asm = False
+            continue
+        text = text.split(";")[0].strip()
+        if not text or text.startswith(".") or text.endswith(":"):
+            continue
+        op, _, rest = text.partition(" ")
+        ops = [o.strip() for o in _SPLIT.split(rest) if o.strip()] if rest else []
+        if op == "s_waitcnt":
+            m = re.search(r"vmcnt\((\d+)\)", rest)
+            if m and int(m.group(1)) < len(queue):
+                queue = queue[len(queue) - int(m.group(1)):] if int(m.group(1)) else []
+            continue
+        is_vmem = op.startswith(("global_", "flat_", "buffer_", "scratch_"))
+        is_lds = op.startswith("ds_")
+        is_load = is_vmem and "_load" in op and "_lds" not in op
+        writes: Set[int] = set()
+        addresses: Set[int] = set()
+        if is_load or op.startswith("ds_read") or (op.startswith("v_") and not op.startswith(("v_cmp", "v_readfirstlane", "v_readlane"))):
+            writes = _vregs(ops[0]) if ops else set()
+        if is_vmem or is_lds:
+            for o in (ops[1:] if (is_load or op.startswith("ds_read")) else ops):
+                addresses |= _vregs(o)
+        for dest, issued in queue:
+            if dest & writes:
+                found.append("%s: line %d: %s writes v%s while the load of line %d may be in flight"
+                             % (name, no, op, sorted(dest & writes), issued))
+            if dest & addresses:
+                found.append("%s: line %d: %s takes an address or data from v%s while the load of line %d may be in flight"
+                             % (name, no, op, sorted(dest & addresses), issued))
+        if is_vmem:
+            queue.append((writes if (is_load and in_asm) else set(), no))
+    return found
+
+
+def find_inflight_hazards(asm_text: str) -> List[str]:
+    """Scans every function of a device assembly listing; returns one message per finding."""
+    found: List[str] = []
+    name, lines = None, []
+    for no, line in enumerate(asm_text.splitlines(), 1):
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            name, lines = m.group(1), []
+        elif line.startswith(".Lfunc_end"):
+            if name:
+                found += _scan_kernel(name, lines)
+            name, lines = None, []
+        elif name:
+            lines.append((no, line))
+    return found

@@ -8,11 +8,15 @@ tests and the benchmark load.
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, HERE)
+import asm_check  # noqa: E402  (a sibling file: this script also runs before the package can be imported)
+sys.path.pop(0)
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
@@ -20,6 +24,7 @@ LIB = os.path.join(HERE, "libhmoe.so")
 
 SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "ffn_reference.hip", "ffn_skinny.hip",
            "ffn_tiled.hip", "schedule.hip"]
+HAND_ISSUED_LOADS = ["ffn_tiled.hip"]   # sources whose kernels load into registers from inline assembly
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -38,12 +43,11 @@ def kernels_with_scratch(remarks: str):
     """Kernel names whose resource-usage remarks report private (scratch) memory, i.e. register spills."""
     bad, name = [], None
     for line in remarks.splitlines():
-        if "remark:" not in line:
-            continue
-        text = line.split("remark:", 1)[1]
-        if "Function Name:" in text:
-            name = text.split("Function Name:", 1)[1].split("[")[0].strip()
-        elif "ScratchSize [bytes/lane]:" in text and int(text.split(":", 1)[1].split("[")[0]) > 0:
+        found = re.search(r"Function Name:\s*(\S+)", line)
+        if found:
+            name = found.group(1)
+        found = re.search(r"ScratchSize \[bytes/lane\]:\s*(\d+)", line)
+        if found and int(found.group(1)) > 0:
             bad.append(name)
     return bad
 
@@ -52,14 +56,27 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     os.makedirs(BUILD, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = [os.path.join(BUILD, s.replace(".hip", ".o")) for s in SOURCES]
+    listings = [os.path.join(BUILD, s.replace(".hip", ".s")) for s in HAND_ISSUED_LOADS]
 
     def compile_one(pair):
-        src, obj = pair
+        src, out = pair
+        if out.endswith(".s"):   # device assembly, for the in-flight register check below
+            return _run([hipcc, *FLAGS, *extra_flags, "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", out])
         return _run([hipcc, *FLAGS, "-Rpass-analysis=kernel-resource-usage", *extra_flags, "-c", os.path.join(CSRC, src),
-                     "-o", obj])
+                     "-o", out])
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
-        logs = list(pool.map(compile_one, zip(SOURCES, objs)))
+    jobs = list(zip(HAND_ISSUED_LOADS, listings)) + list(zip(SOURCES, objs))
+    with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as pool:
+        logs = list(pool.map(compile_one, jobs))[len(listings):]
+    # No register of a load issued from inline assembly may be written, or used as an address, before the wait
+    # that covers the load (see asm_check.py).
+    hazards = []
+    for path in listings:
+        with open(path) as f:
+            hazards += asm_check.find_inflight_hazards(f.read())
+        os.remove(path)
+    if hazards:
+        raise RuntimeError("registers reused while a hand-issued load is in flight:\n  " + "\n  ".join(hazards[:20]))
     # No kernel of this library may spill registers.  The prefill kernels issue their loads by hand and count the
     # outstanding ones themselves; the compiler treats the destination of such a load as written at once, so under
     # register pressure it may spill and reuse that register before the data lands (observed: a late load then

@@ -24,6 +24,7 @@
 //   * Tiles are numbered expert-major, then n-tile, then m-tile, and block ids are dealt to the
 //     8 XCDs in contiguous ranges so that blocks sharing a weight panel share an L2.
 #include <stdlib.h>
+#include <string.h>
 
 #include <algorithm>
 
@@ -349,11 +350,12 @@ __device__ __forceinline__ void wait_vmcnt_regs(u32x4& a, u32x4& b) {
   asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
 
-template <bool GATEUP_, int BM_, int NWV, int SA, bool SKIP, bool NT>
+template <bool GATEUP_, int BM_, int NWV, int SA, bool SKIP, bool NT, int DB = 8>
 struct StreamTile {
   static constexpr bool GATEUP = GATEUP_;
   static constexpr int BM = BM_;
-  static constexpr int FN = 2, BN = NWV * 64, FM = BM / 32, BKT = 64, KK = 4, DB = 8;
+  static constexpr int FN = 2, BN = NWV * 64, FM = BM / 32, BKT = 64, KK = 4;
+  static_assert(DB % KK == 0, "the weight ring holds whole K steps");
   static constexpr int CPR = BKT / 8, RP = 256 / (BKT * 2);
   static constexpr int A_CHUNKS = BM * CPR;
   static constexpr int A_OPS = A_CHUNKS / (64 * NWV);
@@ -373,13 +375,12 @@ struct StreamTile {
                                                   int k_begin, int k_steps, u32x4* lds, Acc& acc) {
     const int e = loc.e, row_first = loc.row_first, m_rows = loc.m_rows, mt = loc.mt, nt = loc.nt;
     const int K = GATEUP ? c.hidden : c.ffn;
-    const int n_out = GATEUP ? c.ffn : c.hidden;
     const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;
     const int kt16 = K / TILE_K;
     const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
     const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
     const int m0 = mt * BM;
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int tid = threadIdx.x % THREADS, wave = tid / 64, lane = tid % 64;  // a block may hold two groups of NWV waves
     const int half = lane / 32, col = lane % 32;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
 
@@ -479,19 +480,31 @@ struct StreamTile {
       }
     }
     wait_vmcnt<0>();  // the clamped tail copies must not outlive the block's LDS
-
+    // The tail's weight loads are never multiplied.  The compiler knows nothing of their latency: without a use
+    // after the wait it may give two of them the same destination, or build the next address in a register that
+    // a load still in flight is about to overwrite.  Keeping every ring slot alive up to here rules that out.
+#pragma unroll
+    for (int s = 0; s < DB; ++s)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) asm volatile("" ::"v"(ring[s][j]));
   }
 
   static __device__ __forceinline__ void epilogue(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
                                                   const Acc& acc) {
+    epilogue_part(c, out, loc, acc, 0, FM);
+  }
+  // stores the 32-row fragments i_first <= i < i_last of the tile
+  static __device__ __forceinline__ void epilogue_part(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
+                                                       const Acc& acc, int i_first, int i_last) {
     const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
     const int n_out = GATEUP ? c.ffn : c.hidden;
     const int m0 = loc.mt * BM;
-    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int tid = threadIdx.x % THREADS, wave = tid / 64, lane = tid % 64;
     const int half = lane / 32, col = lane % 32;
     // ---- epilogue: accumulator register r of lane (half, col) is row 8*(r/4) + 4*half + r%4 ----
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
+      if (i < i_first || i >= i_last) continue;  // uniform
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps the accumulator reads from piling up
@@ -537,6 +550,56 @@ __global__ __launch_bounds__(TILE::THREADS) void ffn_tile_kernel(TiledCtx c, con
   TILE::epilogue(c, out, loc, acc);
 }
 
+// One block per tile, two groups of TILE::THREADS threads: each group runs the tile's main loop over one
+// half of the K range with an activation ring of its own (the groups execute the same number of
+// barriers, so the block-wide barriers of the main loop line up), then the groups swap halves of their
+// accumulators through LDS and each finishes half of the tile's row fragments.  This doubles the waves
+// that stream weights per tile, for launches with fewer tiles than the chip has CUs.  The caller
+// guarantees an even number of K steps.
+template <class TILE>
+__global__ __launch_bounds__(2 * TILE::THREADS) void ffn_tile_k2_kernel(TiledCtx c, const bf16_t* __restrict__ in,
+                                                                         bf16_t* __restrict__ out) {
+  constexpr int HALF = TILE::FM / 2, QUADS = HALF * TILE::FN * 4, T = TILE::THREADS;
+  static_assert(TILE::FM % 2 == 0 && 2 * QUADS * T <= 2 * TILE::LDS_VEC, "the exchange reuses the activation rings");
+  __shared__ u32x4 lds[2 * TILE::LDS_VEC];
+  TileLoc loc;
+  if (!locate_tile<TILE::BM>(c, loc)) return;  // uniform over the block
+  const int group = __builtin_amdgcn_readfirstlane(threadIdx.x / T);
+  const int steps = (TILE::GATEUP ? c.hidden : c.ffn) / TILE::BKT / 2;
+  typename TILE::Acc acc;
+  zero_acc<TILE>(acc);
+  TILE::mainloop(c, in, loc, group * steps, steps, lds + group * TILE::LDS_VEC, acc);
+
+  // group g finishes row fragments [g * HALF, (g + 1) * HALF); the others go to the partner
+  f32x4_t* xch = (f32x4_t*)lds;
+  const int lt = threadIdx.x % T;
+  __syncthreads();  // every wave has read its last activation fragments
+#pragma unroll
+  for (int i = 0; i < TILE::FM; ++i) {
+    if (i / HALF == group) continue;
+#pragma unroll
+    for (int j = 0; j < TILE::FN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        xch[(group * QUADS + ((i % HALF) * TILE::FN + j) * 4 + q) * T + lt] =
+            f32x4_t{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TILE::FM; ++i) {
+    if (i / HALF != group) continue;
+#pragma unroll
+    for (int j = 0; j < TILE::FN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x4_t v = xch[((1 - group) * QUADS + ((i % HALF) * TILE::FN + j) * 4 + q) * T + lt];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[i][j][4 * q + u] += v[u];
+      }
+  }
+  TILE::epilogue_part(c, out, loc, acc, group * HALF, (group + 1) * HALF);
+}
+
 // upper bound of the tile count of a launch (sum over experts of ceil(rows / BM) is at most this)
 static long tiles_upper_bound(const TiledCtx& c, int n_rows, int bm) {
   return ((long)n_rows / bm + std::min(c.n_experts, n_rows)) * c.n_tiles_n;
@@ -548,6 +611,14 @@ static void launch_tiles(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, 
   c.n_tiles_n = (n_total + TILE::BN - 1) / TILE::BN;
   c.grid_padded = (int)((tiles_upper_bound(c, n_rows, TILE::BM) + 7) / 8 * 8);
   hipLaunchKernelGGL((ffn_tile_kernel<TILE>), dim3((unsigned)c.grid_padded), dim3(TILE::THREADS), 0, s, c, in, out);
+}
+
+template <class TILE>
+static void launch_tiles_k2(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
+  const int n_total = TILE::GATEUP ? 2 * c.ffn : c.hidden;
+  c.n_tiles_n = (n_total + TILE::BN - 1) / TILE::BN;
+  c.grid_padded = (int)((tiles_upper_bound(c, n_rows, TILE::BM) + 7) / 8 * 8);
+  hipLaunchKernelGGL((ffn_tile_k2_kernel<TILE>), dim3((unsigned)c.grid_padded), dim3(2 * TILE::THREADS), 0, s, c, in, out);
 }
 
 // Tile shapes built into the library.  hmoe picks one from the average rows per expert; the
@@ -563,6 +634,8 @@ struct TiledVariant {
     launch_tiles<LdsRingTile<false, BM, BN, BKT, ST, WM, WN>> }
 #define HMOE_STREAM(NAME, NWV, SKIP, NT) \
   { NAME, launch_tiles<StreamTile<true, 128, NWV, 4, SKIP, NT>>, launch_tiles<StreamTile<false, 128, NWV, 4, SKIP, NT>> }
+#define HMOE_STREAM_K2(NAME, NT) \
+  { NAME, launch_tiles_k2<StreamTile<true, 128, 4, 4, false, NT, 4>>, launch_tiles_k2<StreamTile<false, 128, 4, 4, false, NT, 4>> }
 static const TiledVariant kVariants[] = {
     HMOE_LDS_RING(256, 256, 64, 2, 2, 4),  // 0: 8 waves, 128x64 per wave
     HMOE_LDS_RING(128, 256, 64, 3, 2, 4),  // 1: 8 waves, 64x64 per wave, 3 stages
@@ -579,7 +652,10 @@ static const TiledVariant kVariants[] = {
     HMOE_STREAM("stream 128x512 s4 skip", 8, true, true),     // 12: 10 + skip padded fragments
     HMOE_STREAM("stream 128x256 s4 plain", 4, false, false),  // 13: 9 with plain weight loads
     HMOE_STREAM("stream 128x512 s4 plain", 8, false, false),  // 14: 10 with plain weight loads
+    HMOE_STREAM_K2("stream 128x256 s4 k2", true),             // 15: 9 with two wave groups that split K
+    HMOE_STREAM_K2("stream 128x256 s4 k2 plain", false),      // 16: 15 with plain weight loads
 };
+constexpr int kFirstSplitK = 15;  // these need an even number of K steps of 64
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 int launch_ffn_tiled(const FfnArgs& a) {
@@ -591,20 +667,30 @@ int launch_ffn_tiled(const FfnArgs& a) {
   bf16_t* h = (bf16_t*)a.h;
   bf16_t* o = (bf16_t*)a.o_perm;
   // Kernel choice (measured on the workload shapes; the tile counts are the launch's upper bounds).  The
-  // weight-streaming family with 8 waves and a 128x512 tile wins whenever it yields several rounds of
-  // blocks per CU.  With fewer tiles the round-up to whole rounds costs more than the kernel gains:
+  // weight-streaming family with 8 waves and a 128x512 tile wins whenever it yields two rounds of blocks
+  // per CU or more.  With fewer tiles the round-up to whole rounds costs more than the kernel gains:
   // gate/up then takes the 128x256 LDS-ring tile (twice the blocks), and the down projection of few,
-  // large experts (small N) the 128x256 streaming tile with 4 waves.
+  // large experts (small N) the 128x256 streaming tile with 4 waves.  A launch whose 128x256 tiles cover at
+  // most half of the CUs (a shared expert at a moderate batch) takes that tile with two wave groups that
+  // split K: per-tile time is all that matters there and the second group nearly halves it.
   const long m_tiles = (long)a.n_rows / 128 + std::min(d.n_experts, a.n_rows);
   const long tiles_gate_up = m_tiles * ((2 * d.ffn + 511) / 512);
   const long tiles_down = m_tiles * ((d.hidden + 511) / 512);
   // Many m-tiles per expert (512 rows or more on average): the panel is shared through L2, plain loads.
   const bool shared_panels = a.n_rows / d.n_experts >= 512;
-  int v_gate_up = tiles_gate_up < 1024 ? 1 : (shared_panels ? 14 : 10);
+  auto split_k_fits = [](int variant, int k) { return variant < kFirstSplitK || (k / 64) % 2 == 0; };
+  const int v_split_k = shared_panels ? 16 : 15;
+  int v_gate_up = tiles_gate_up < 512 ? 1 : (shared_panels ? 14 : 10);
   int v_down = tiles_down < 256 ? (shared_panels ? 13 : 9) : (shared_panels ? 14 : 10);
+  if (m_tiles * ((2 * d.ffn + 255) / 256) <= 128 && split_k_fits(v_split_k, d.hidden)) v_gate_up = v_split_k;
+  if (m_tiles * ((d.hidden + 255) / 256) <= 128 && split_k_fits(v_split_k, d.ffn)) v_down = v_split_k;
   if (const char* env = getenv("HMOE_TILED_VARIANT")) {
-    const int want = atoi(env);
-    if (want >= 0 && want < kNumVariants) v_gate_up = v_down = want;
+    // "<index>" for both projections or "<gate/up index>,<down index>"
+    const int want_gate_up = atoi(env);
+    const char* comma = strchr(env, ',');
+    const int want_down = comma ? atoi(comma + 1) : want_gate_up;
+    if (want_gate_up >= 0 && want_gate_up < kNumVariants && split_k_fits(want_gate_up, d.hidden)) v_gate_up = want_gate_up;
+    if (want_down >= 0 && want_down < kNumVariants && split_k_fits(want_down, d.ffn)) v_down = want_down;
   }
   probe_before(a.stream);
   kVariants[v_gate_up].gate_up(c, a.n_rows, x, h, a.stream);

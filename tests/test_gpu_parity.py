@@ -203,15 +203,24 @@ def test_ffn_bf16_paths(hm, path, hidden, ffn, counts):
     assert np.abs(ref).max() > 1e-2
 
 
-@pytest.mark.parametrize("variant", range(15))
+@pytest.mark.parametrize("variant", range(17))
 def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
     """The library's tuning override selects each built-in prefill kernel (LDS-ring tiles 0-8, weight-streaming
-    tiles 9-14) in turn; ragged groups spanning several m-tiles, partial n-tiles for every tile width."""
+    tiles 9-14, weight-streaming tiles with two wave groups that split K 15-16) in turn; ragged groups spanning
+    several m-tiles, partial n-tiles for every tile width.  The split-K tiles apply to a projection whose K is
+    an even number of 64-wide steps (the other projection then runs the default kernel): the shapes give
+    them 1, 2, 3 and 4 steps per wave group in both projections."""
     say("ffn prefill variant", variant)
     monkeypatch.setenv("HMOE_TILED_VARIANT", str(variant))
     shape = wl.small_shape(dtype=wl.BF16, hidden=256, ffn=320, n_experts=8, top_k=2)
     got, ref = _ffn_case(hm, shape, [33, 1, 0, 0, 300, 5, 64, 129], 3, seed=variant)
     assert max_rel_err(got, ref) < TOL[wl.BF16]
+    if variant >= 15:
+        for hidden, ffn in ((128, 384), (384, 128), (512, 512)):
+            say("ffn prefill variant", variant, "hidden", hidden, "ffn", ffn)
+            shape = wl.small_shape(dtype=wl.BF16, hidden=hidden, ffn=ffn, n_experts=4, top_k=2)
+            got, ref = _ffn_case(hm, shape, [130, 0, 7, 128], 3, seed=variant + hidden)
+            assert max_rel_err(got, ref) < TOL[wl.BF16]
 
 
 @pytest.mark.parametrize("shape_id", range(6))
