@@ -245,6 +245,29 @@ def main() -> int:
             staging[name] = {"tokens_per_s_incl_pcie": T * n_steps / dt, "ms_per_step": dt / n_steps * 1e3,
                              "hit_rate": hits / max(1, needed), "staged_GB_per_step": part.staged_bytes / n_steps / 1e9,
                              "pcie_GBps_lower_bound": part.staged_bytes / dt / 1e9}
+        # replacement policies on consecutive decode steps with temporal locality (Section IV-D, Fig. 8):
+        # the same logit sequence served under LRU and under the score-aware policy of Eq. (3)
+        policies = {}
+        name, T = phases[0]
+        if "decode" in name:
+            n_seq, n_skip = 72, 8
+            seq = wl.make_logit_sequence(shape, 4242, T, n_seq, 0.9)
+            x_dev = to_dev(wl.make_x(shape, 4243, T))
+            for pol_name, pol in (("lru", hm.HMOE_POLICY_LRU), ("mrs", hm.HMOE_POLICY_MRS)):
+                part.set_policy(pol, 0.5)
+                needed = hits = 0
+                for i in range(n_seq):
+                    lg_dev = to_dev(seq[i])
+                    part.forward(x_dev, lg_dev)
+                    if pol == hm.HMOE_POLICY_MRS:
+                        part.update_scores(lg_dev)
+                    if i >= n_skip:     # the first steps only bring the cache from the other policy's state
+                        wave = part.last_plan[0]
+                        needed += int((wave >= 0).sum())
+                        hits += int((wave == 0).sum())
+                policies[pol_name] = hits / max(1, needed)
+            torch.cuda.synchronize()
+            staging[name]["hit_rate_correlated_steps"] = dict(policies, steps=n_seq - n_skip, rho=0.9, alpha=0.5)
         part.close()
 
     # ---- CPU baseline: the oracle as it stands, bounded sample -------------------------------

@@ -287,6 +287,16 @@ def test_workload_recipes():
     lay_a = wl.make_layer(wl.small_shape(), 9, 4)
     lay_b = wl.make_layer(wl.small_shape(), 9, 4)
     assert np.array_equal(lay_a.experts[3][2], lay_b.experts[3][2])
+    # decode-step sequences: stationary N(0,1) per step, lag-1 correlation rho, the workload's forcing at every step
+    seq = wl.make_logit_sequence(wl.small_shape(n_experts=8), 4, 16, 400, 0.9)
+    assert seq.shape == (400, 16, 8) and seq.dtype == np.float32
+    assert abs(seq.std() - 1.0) < 0.05 and abs(seq[300:].std() - seq[:100].std()) < 0.1
+    lag1 = np.mean(seq[:-1] * seq[1:]) / np.mean(seq * seq)
+    assert abs(lag1 - 0.9) < 0.03
+    indep = wl.make_logit_sequence(wl.small_shape(n_experts=8), 4, 16, 400, 0.0)
+    assert abs(np.mean(indep[:-1] * indep[1:])) < 0.02
+    hot = wl.make_logit_sequence(wl.QWEN2MOE, 3, 20, 5, 0.9)
+    assert np.all(np.argmax(hot[:, ::10], axis=2) == 0)
 
 
 # ----------------------------------------------------------------------------- score-aware replacement, Eq. (3)

@@ -157,6 +157,28 @@ def make_logits(shape: LayerShape, seed: int, n_tokens: int) -> Optional[np.ndar
     return np.ascontiguousarray(lg, dtype=np.float32)
 
 
+def make_logit_sequence(shape: LayerShape, seed: int, n_tokens: int, n_steps: int, rho: float = 0.9) -> np.ndarray:
+    """fp32 router logits [n_steps, T, E] of consecutive decode steps with temporal locality: an AR(1)
+    process per (token slot, expert), l_s = rho * l_(s-1) + sqrt(1 - rho^2) * N(0,1), started from N(0,1),
+    plus the workload's per-expert bias ("zipf") or forcing ("hot0").  The stationary distribution per step is
+    that of make_logits; rho = 0 gives independent steps.  Stands in for the step-to-step similarity of
+    routing scores in real decoding traces, which is what a score-aware replacement policy exploits."""
+    e = shape.n_experts
+    noise = _normal(seed, _STREAM_LOGITS, (n_steps, n_tokens, e), 1.0)
+    out = np.empty_like(noise)
+    cur = noise[0]
+    for s in range(n_steps):
+        if s:
+            cur = np.float32(rho) * cur + np.float32(np.sqrt(1.0 - rho * rho)) * noise[s]
+        out[s] = cur
+    if shape.logits_mode == "zipf":
+        out = out + zipf_bias(e)[None, None, :]
+    elif shape.logits_mode == "hot0":
+        hot = np.arange(n_tokens) % 10 == 0
+        out[:, hot, 0] = out[:, hot].max(axis=2) + np.float32(1.0)
+    return np.ascontiguousarray(out, dtype=np.float32)
+
+
 def make_expert(shape: LayerShape, seed: int, e: int, ffn: Optional[int] = None, shared: bool = False):
     """One expert's three matrices in logical form and storage dtype:
     W_gate [F, H], W_up [F, H], W_down [H, F]."""
