@@ -156,14 +156,14 @@ def main() -> int:
         # second pass: HIP events around the gate/up kernel of the routed-expert FFN call
         calls_per_step = (n_layers if args.workload == "stress" else 1) * (2 if Fs else 1)
         for l in layers:                 # kernels one after the other, so that each probe pair times one kernel alone
-            l.overlap_shared = False
+            l.overlap_shared = l.merge_shared = False
         hm.hmoe_probe_arm(steps * calls_per_step)
         for i in range(steps):
             one_step(i)
         torch.cuda.synchronize()
         ms = hm.hmoe_probe_read(steps * calls_per_step)
         for l in layers:
-            l.overlap_shared = l.fused
+            l.overlap_shared = l.merge_shared = l.fused
         routed_ms = ms[0::2] if Fs else ms        # routed call first, shared call second
         shared_ms = ms[1::2] if Fs else np.zeros(0, np.float32)
         # what the routed gate/up kernel touched (distinct experts with rows, last step's routing)

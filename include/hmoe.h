@@ -280,6 +280,25 @@ int32_t hmoe_expert_ffn_grouped_gather(const hmoe_layer_desc* desc, hmoe_cache* 
                                        const int32_t* h_active, int32_t n_active, void* o_perm,
                                        void* workspace, size_t workspace_bytes, int32_t path, void* stream);
 
+/*
+ * hmoe_expert_ffn_grouped_gather for the routed experts and, on the same stream, the dense FFN of the
+ * layer's shared experts (Section II-A: they see every token) over the same un-permuted x:
+ *     o_perm   as hmoe_expert_ffn_grouped_gather(desc, cache, x, perm, expert_offsets, A, ...)
+ *     o_shared as hmoe_expert_ffn_grouped(shared_desc, shared_cache, x, shared_offsets, T, NULL, 0, ...)
+ * with the same bits as those two calls.  shared_desc is a 1-expert layer (E = K = S = 1) of the same
+ * hidden size and dtype whose expert is resident in shared_cache; shared_offsets is the device array
+ * {0, T}; o_shared [T, H]; shared_workspace holds hmoe_ffn_workspace_bytes(shared_desc, T) bytes.
+ * When both parts are decode-sized bf16 calls (path resolves to HMOE_FFN_SKINNY for both), the shared
+ * FFN is computed by extra blocks of the routed experts' two launches instead of two launches of its own,
+ * which is what a layer of a few microseconds per kernel needs; in every other case the two calls run
+ * one after the other.  Errors as in the two calls; nothing is enqueued when an argument is rejected.
+ */
+int32_t hmoe_expert_ffn_grouped_with_shared(
+    const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x, const int32_t* perm, const int32_t* expert_offsets,
+    int32_t A, const int32_t* h_active, int32_t n_active, void* o_perm, void* workspace, size_t workspace_bytes,
+    const hmoe_layer_desc* shared_desc, hmoe_cache* shared_cache, const int32_t* shared_offsets, int32_t T,
+    void* o_shared, void* shared_workspace, size_t shared_workspace_bytes, int32_t path, void* stream);
+
 /* ------------------------------------------------------------------------------------
  * The sum of Eq. (1) in gather form:
  *     y[t] = sum_{j<K} topk_w[t, j] * o_perm[inv_perm[t*K + j]]  (+ o_shared[t])

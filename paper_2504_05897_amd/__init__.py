@@ -40,7 +40,7 @@ EXPORTS = [
     "hmoe_cache_create", "hmoe_cache_destroy", "hmoe_cache_lookup", "hmoe_cache_occupant",
     "hmoe_cache_evict", "hmoe_cache_pin_slot", "hmoe_cache_stage", "hmoe_cache_plan",
     "hmoe_ffn_workspace_bytes", "hmoe_expert_ffn_grouped", "hmoe_expert_ffn_grouped_gather", "hmoe_route_permute",
-    "hmoe_router_route_permute",
+    "hmoe_router_route_permute", "hmoe_expert_ffn_grouped_with_shared",
     "hmoe_combine",
     "hmoe_cache_set_policy", "hmoe_cache_update_scores", "hmoe_cache_get_scores",
     "hmoe_route_scores_workspace_bytes", "hmoe_route_scores",
@@ -104,6 +104,8 @@ def _load() -> ctypes.CDLL:
     lib.hmoe_ffn_workspace_bytes.argtypes = [dp, i32]
     lib.hmoe_expert_ffn_grouped.argtypes = [dp, vp, vp, vp, i32, vp, i32, vp, vp, sz, i32, vp]
     lib.hmoe_expert_ffn_grouped_gather.argtypes = [dp, vp, vp, vp, vp, i32, vp, i32, vp, vp, sz, i32, vp]
+    lib.hmoe_expert_ffn_grouped_with_shared.argtypes = [dp, vp, vp, vp, vp, i32, vp, i32, vp, vp, sz,
+                                                        dp, vp, vp, i32, vp, vp, sz, i32, vp]
     lib.hmoe_route_permute.argtypes = [dp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.hmoe_router_route_permute.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.hmoe_combine.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp]
@@ -264,6 +266,17 @@ def hmoe_expert_ffn_grouped_gather(desc, cache, x, perm, expert_offsets, A, h_ac
            "hmoe_expert_ffn_grouped_gather")
 
 
+def hmoe_expert_ffn_grouped_with_shared(desc, cache, x, perm, expert_offsets, A, h_active, o_perm, workspace,
+                                        workspace_bytes, shared_desc, shared_cache, shared_offsets, T, o_shared,
+                                        shared_workspace, shared_workspace_bytes, path=HMOE_FFN_AUTO, stream=None):
+    act = None if h_active is None else np.ascontiguousarray(h_active, dtype=np.int32)
+    _check(_lib.hmoe_expert_ffn_grouped_with_shared(
+        ctypes.byref(desc), cache, _ptr(x), _ptr(perm), _ptr(expert_offsets), A, _ptr(act),
+        0 if act is None else int(act.shape[0]), _ptr(o_perm), _ptr(workspace), workspace_bytes,
+        ctypes.byref(shared_desc), shared_cache, _ptr(shared_offsets), T, _ptr(o_shared), _ptr(shared_workspace),
+        shared_workspace_bytes, path, _stream(stream)), "hmoe_expert_ffn_grouped_with_shared")
+
+
 def hmoe_route_permute(desc, logits, T, topk_idx, topk_w, expert_offsets, perm, inv_perm, h_counts_pinned, workspace,
                        workspace_bytes, stream=None):
     _check(_lib.hmoe_route_permute(ctypes.byref(desc), _ptr(logits), T, _ptr(topk_idx), _ptr(topk_w),
@@ -375,6 +388,7 @@ class MoELayer:
         self.desc = desc
         self.fused = fused          # route+permute in one call, gather fused into the FFN
         self.overlap_shared = fused  # shared-expert FFN on a side stream, next to the routed path
+        self.merge_shared = fused    # decode-sized batches: shared-expert FFN inside the routed experts' launches
         self.dev = torch.device(device)
         self.dt = torch_dtype(desc)
         E, S, K, H, F = desc.n_experts, desc.n_slots, desc.top_k, desc.hidden, desc.ffn
@@ -477,6 +491,10 @@ class MoELayer:
         counts = None if all_resident else self.h_counts
         cur = torch.cuda.current_stream()
         o_shared = None
+        # one call for routed and shared experts when the kernels are a few microseconds each (the library
+        # merges the launches for T <= 32 in bfloat16) and the routed experts need a single call
+        merged = (self.shared_desc is not None and self.fused and self.merge_shared and all_resident and T <= 32
+                  and d.dtype == HMOE_BF16)
         if self.shared_desc is not None:
             # shared experts (Section II-A) see every token and do not depend on the routing: with
             # `fused` they run on a side stream next to the routed path
@@ -484,7 +502,7 @@ class MoELayer:
                 self.shared_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
                 self._shared_T = T
             o_shared = self.o_shared
-            if self.overlap_shared:
+            if self.overlap_shared and not merged:
                 self.ev_fork.record(cur)
                 self.side_stream.wait_event(self.ev_fork)
                 with torch.cuda.stream(self.side_stream):
@@ -517,7 +535,12 @@ class MoELayer:
                 hmoe_expert_ffn_grouped(d, self.cache, self.x_perm, self.offsets, A, active, self.o_perm, self.ffn_ws,
                                         self.ffn_ws_bytes, path)
 
-        if all_resident:
+        if merged:
+            hmoe_expert_ffn_grouped_with_shared(d, self.cache, x, self.perm, self.offsets, A, None, self.o_perm,
+                                                self.ffn_ws, self.ffn_ws_bytes, self.shared_desc, self.shared_cache,
+                                                self.shared_offsets, T, self.o_shared, self.shared_ws,
+                                                self.shared_ws_bytes, path)
+        elif all_resident:
             routed_ffn(None)
         else:
             cur.synchronize()          # the host needs the per-expert loads
@@ -532,7 +555,7 @@ class MoELayer:
                         self.staged_bytes += self.slot_bytes
                 if members.size:
                     routed_ffn(members)
-        if self.shared_desc is not None:
+        if self.shared_desc is not None and not merged:
             if self.overlap_shared:
                 cur.wait_event(self.ev_join)
             else:

@@ -416,21 +416,25 @@ extern "C" size_t hmoe_ffn_workspace_bytes(const hmoe_layer_desc* desc, int32_t 
   return (((size_t)A * desc->ffn * elem) + 255) & ~(size_t)255;
 }
 
-static int32_t ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x_perm, const int32_t* row_map,
+// Checks the arguments of one grouped-FFN call, fills the launch arguments and resolves HMOE_FFN_AUTO.
+// *skip is set when there is nothing to compute (A == 0).
+static int32_t ffn_prepare(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x_perm, const int32_t* row_map,
                            const int32_t* expert_offsets, int32_t A, const int32_t* h_active, int32_t n_active,
-                           void* o_perm, void* workspace, size_t workspace_bytes, int32_t path, void* stream) {
+                           void* o_perm, void* workspace, size_t workspace_bytes, int32_t* path, void* stream, FfnArgs* out,
+                           bool* skip) {
   int rc = check_ffn_shape(desc);
   if (rc != HMOE_OK) return rc;
   if (!cache || A < 0 || !expert_offsets) return HMOE_ERR_INVALID_ARG;
   if (memcmp(desc, &cache->desc, sizeof(*desc)) != 0) return HMOE_ERR_INVALID_ARG;
-  if (path < HMOE_FFN_AUTO || path > HMOE_FFN_TILED) return HMOE_ERR_INVALID_ARG;
+  if (*path < HMOE_FFN_AUTO || *path > HMOE_FFN_TILED) return HMOE_ERR_INVALID_ARG;
+  *skip = A == 0;
   if (A == 0) return HMOE_OK;
   if (!x_perm || !o_perm) return HMOE_ERR_INVALID_ARG;
   if (!aligned16(x_perm) || !aligned16(o_perm) || !aligned16(workspace)) return HMOE_ERR_INVALID_ARG;
   if (!workspace || workspace_bytes < hmoe_ffn_workspace_bytes(desc, A)) return HMOE_ERR_WORKSPACE;
   if (h_active && n_active < 0) return HMOE_ERR_INVALID_ARG;
 
-  FfnArgs a;
+  FfnArgs& a = *out;
   a.desc = desc;
   a.x_perm = x_perm;
   a.row_map = row_map;
@@ -455,25 +459,43 @@ static int32_t ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, const
     for (int e = 0; e < desc->n_experts; ++e) a.active.w[e >> 6] |= 1ull << (e & 63);
   }
 
-  if (path == HMOE_FFN_AUTO) {
-    if (desc->dtype == HMOE_F32) path = HMOE_FFN_REFERENCE;
-    else if (desc->dtype == HMOE_BF16_W4) path = HMOE_FFN_SKINNY;  // the weight-streaming kernel at every batch size
-    else path = (A / desc->top_k <= 32) ? HMOE_FFN_SKINNY : HMOE_FFN_TILED;
+  if (*path == HMOE_FFN_AUTO) {
+    if (desc->dtype == HMOE_F32) *path = HMOE_FFN_REFERENCE;
+    else if (desc->dtype == HMOE_BF16_W4) *path = HMOE_FFN_SKINNY;  // the weight-streaming kernel at every batch size
+    else *path = (A / desc->top_k <= 32) ? HMOE_FFN_SKINNY : HMOE_FFN_TILED;
   }
-  if (desc->dtype == HMOE_F32 && path != HMOE_FFN_REFERENCE) return HMOE_ERR_UNSUPPORTED;
-  if (desc->dtype == HMOE_BF16_W4 && path == HMOE_FFN_TILED) return HMOE_ERR_UNSUPPORTED;
-  if (path == HMOE_FFN_REFERENCE) rc = launch_ffn_reference(a);
-  else if (path == HMOE_FFN_SKINNY) rc = desc->dtype == HMOE_BF16_W4 ? launch_ffn_skinny_w4(a) : launch_ffn_skinny(a);
-  else rc = launch_ffn_tiled(a);
-  if (rc != HMOE_OK) return rc;
-
-  if (cache->track_reads) {
-    const uint64_t seq = ++cache->use_seq;
-    HMOE_HIP(hipEventRecord(cache->use_ev[seq % hmoe_cache::RING], a.stream));
-    for (int e = 0; e < desc->n_experts; ++e)
-      if (a.active.test(e) && cache->slot_of[e] >= 0) cache->slot_last_read[cache->slot_of[e]] = seq;
-  }
+  if (desc->dtype == HMOE_F32 && *path != HMOE_FFN_REFERENCE) return HMOE_ERR_UNSUPPORTED;
+  if (desc->dtype == HMOE_BF16_W4 && *path == HMOE_FFN_TILED) return HMOE_ERR_UNSUPPORTED;
   return HMOE_OK;
+}
+
+static int32_t ffn_launch(const FfnArgs& a, int32_t path) {
+  if (path == HMOE_FFN_REFERENCE) return launch_ffn_reference(a);
+  if (path == HMOE_FFN_SKINNY) return a.desc->dtype == HMOE_BF16_W4 ? launch_ffn_skinny_w4(a) : launch_ffn_skinny(a);
+  return launch_ffn_tiled(a);
+}
+
+// remembers, per slot, the last call that read it, so that a later copy into the slot can wait for it
+static int32_t ffn_record_reads(hmoe_cache* cache, const FfnArgs& a) {
+  if (!cache->track_reads) return HMOE_OK;
+  const uint64_t seq = ++cache->use_seq;
+  HMOE_HIP(hipEventRecord(cache->use_ev[seq % hmoe_cache::RING], a.stream));
+  for (int e = 0; e < cache->desc.n_experts; ++e)
+    if (a.active.test(e) && cache->slot_of[e] >= 0) cache->slot_last_read[cache->slot_of[e]] = seq;
+  return HMOE_OK;
+}
+
+static int32_t ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x_perm, const int32_t* row_map,
+                           const int32_t* expert_offsets, int32_t A, const int32_t* h_active, int32_t n_active,
+                           void* o_perm, void* workspace, size_t workspace_bytes, int32_t path, void* stream) {
+  FfnArgs a;
+  bool skip = false;
+  int rc = ffn_prepare(desc, cache, x_perm, row_map, expert_offsets, A, h_active, n_active, o_perm, workspace,
+                       workspace_bytes, &path, stream, &a, &skip);
+  if (rc != HMOE_OK || skip) return rc;
+  rc = ffn_launch(a, path);
+  if (rc != HMOE_OK) return rc;
+  return ffn_record_reads(cache, a);
 }
 
 extern "C" int32_t hmoe_expert_ffn_grouped(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x_perm,
@@ -491,4 +513,38 @@ extern "C" int32_t hmoe_expert_ffn_grouped_gather(const hmoe_layer_desc* desc, h
   if (A > 0 && !perm) return HMOE_ERR_INVALID_ARG;
   return ffn_grouped(desc, cache, x, perm, expert_offsets, A, h_active, n_active, o_perm, workspace, workspace_bytes,
                      path, stream);
+}
+
+extern "C" int32_t hmoe_expert_ffn_grouped_with_shared(
+    const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x, const int32_t* perm, const int32_t* expert_offsets,
+    int32_t A, const int32_t* h_active, int32_t n_active, void* o_perm, void* workspace, size_t workspace_bytes,
+    const hmoe_layer_desc* shared_desc, hmoe_cache* shared_cache, const int32_t* shared_offsets, int32_t T, void* o_shared,
+    void* shared_workspace, size_t shared_workspace_bytes, int32_t path, void* stream) {
+  if (A > 0 && !perm) return HMOE_ERR_INVALID_ARG;
+  if (!shared_desc || T < 0) return HMOE_ERR_INVALID_ARG;
+  if (shared_desc->n_experts != 1 || shared_desc->n_slots != 1 || shared_desc->top_k != 1) return HMOE_ERR_INVALID_ARG;
+  FfnArgs routed, dense;
+  bool skip_routed = false, skip_dense = false;
+  int32_t path_routed = path, path_dense = path;
+  int rc = ffn_prepare(desc, cache, x, perm, expert_offsets, A, h_active, n_active, o_perm, workspace, workspace_bytes,
+                       &path_routed, stream, &routed, &skip_routed);
+  if (rc != HMOE_OK) return rc;
+  rc = ffn_prepare(shared_desc, shared_cache, x, nullptr, shared_offsets, T, nullptr, 0, o_shared, shared_workspace,
+                   shared_workspace_bytes, &path_dense, stream, &dense, &skip_dense);
+  if (rc != HMOE_OK) return rc;
+  if (desc->hidden != shared_desc->hidden || desc->dtype != shared_desc->dtype) return HMOE_ERR_INVALID_ARG;
+  // One pair of launches for both when both are decode-sized bf16 calls; otherwise the two calls one after the other.
+  const bool together = !skip_routed && !skip_dense && desc->dtype == HMOE_BF16 && path_routed == HMOE_FFN_SKINNY &&
+                        path_dense == HMOE_FFN_SKINNY && shared_cache->slot_of[0] >= 0;
+  if (together) {
+    dense.slots = shared_cache->slots + (size_t)shared_cache->slot_of[0] * shared_cache->slot_bytes;
+    rc = launch_ffn_skinny(routed, &dense);
+    if (rc != HMOE_OK) return rc;
+  } else {
+    if (!skip_routed && (rc = ffn_launch(routed, path_routed)) != HMOE_OK) return rc;
+    if (!skip_dense && (rc = ffn_launch(dense, path_dense)) != HMOE_OK) return rc;
+  }
+  if (!skip_routed && (rc = ffn_record_reads(cache, routed)) != HMOE_OK) return rc;
+  if (!skip_dense && (rc = ffn_record_reads(shared_cache, dense)) != HMOE_OK) return rc;
+  return HMOE_OK;
 }

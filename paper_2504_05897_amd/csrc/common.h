@@ -134,7 +134,7 @@ struct FfnArgs {
   hipStream_t stream = nullptr;
 };
 int launch_ffn_reference(const FfnArgs& a);
-int launch_ffn_skinny(const FfnArgs& a);
+int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense = nullptr);
 int launch_ffn_tiled(const FfnArgs& a);
 int launch_ffn_skinny_w4(const FfnArgs& a);
 

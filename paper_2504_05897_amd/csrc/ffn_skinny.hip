@@ -25,6 +25,19 @@
 
 namespace hmoe {
 
+// A dense FFN over the first `rows` rows of its own input that rides along in the launches of the routed
+// experts (the shared experts of a layer, Section II-A): the first grid_rows grid rows hold its 32-row
+// groups, gridDim.x of them per grid row, the routed experts follow.  Its blocks come first because they are
+// dispatched first and may be the longest of the launch (the down projection's K is the dense FFN's width).
+// grid_rows == 0: none.
+struct SkinnyShared {
+  const char* slot;     // packed weights
+  const bf16_t* x;      // [rows, H]
+  bf16_t* h;            // [rows, ffn]
+  bf16_t* o;            // [rows, H]
+  int ffn, rows, grid_rows;
+};
+
 struct SkinnyCtx {
   const int32_t* offsets;
   const int32_t* slot_of;
@@ -35,6 +48,7 @@ struct SkinnyCtx {
   int gpb;  // 32-row groups per block
   const int32_t* row_map;  // gate/up only: input row of sorted row p is row_map[p] / map_div
   int map_div;
+  SkinnyShared shared;
 };
 
 // id of the `want`-th expert (ascending) that is active, resident and has rows; -1 if fewer
@@ -65,16 +79,36 @@ __global__ __launch_bounds__(64 * NW) void ffn_skinny_kernel(SkinnyCtx c, const 
   __shared__ float red[2][RED];
 
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-  const int e = nth_busy_expert(c, blockIdx.y, lane);
-  if (e < 0) return;  // uniform over the block
-  const int row_first = c.offsets[e], row_end = c.offsets[e + 1];
-  const int K = GATEUP ? c.hidden : c.ffn;        // reduction length
-  const int n_out = GATEUP ? c.ffn : c.hidden;    // row length of `out`
+  // what this block works on: a routed expert's rows, or (the first shared.grid_rows grid rows) the dense FFN
+  // that shares the launch.  Everything below is uniform over the block.
+  const bool dense = (int)blockIdx.y < c.shared.grid_rows;
+  int row_first, row_end, ffn, block_in_matrix;
+  const char* slot;
+  const int32_t* row_map = nullptr;
+  if (dense) {
+    row_first = 0;
+    row_end = c.shared.rows;
+    ffn = c.shared.ffn;
+    slot = c.shared.slot;
+    block_in_matrix = (int)blockIdx.y * (int)gridDim.x + (int)blockIdx.x;
+    in = GATEUP ? c.shared.x : c.shared.h;
+    out = GATEUP ? c.shared.h : c.shared.o;
+  } else {
+    const int e = nth_busy_expert(c, (int)blockIdx.y - c.shared.grid_rows, lane);
+    if (e < 0) return;
+    row_first = c.offsets[e];
+    row_end = c.offsets[e + 1];
+    ffn = c.ffn;
+    slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
+    block_in_matrix = blockIdx.x;
+    row_map = c.row_map;
+  }
+  const int K = GATEUP ? c.hidden : ffn;        // reduction length
+  const int n_out = GATEUP ? ffn : c.hidden;    // row length of `out`
   const int kt = K / TILE_K;
-  const int g_begin = blockIdx.x * c.gpb, g_end = min(g_begin + c.gpb, n_out / TILE_N);
+  const int g_begin = block_in_matrix * c.gpb, g_end = min(g_begin + c.gpb, n_out / TILE_N);
   if (g_begin >= g_end) return;
-  const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
-  const u32x4* wbase = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
+  const u32x4* wbase = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)ffn * c.hidden);
   const size_t group_stride = (size_t)kt * 64 * NMAT;  // u32x4 per group (gate/up: the pair)
   // batches of U tiles per wave and group (the last ones may lie partly or wholly past the end of K)
   const int per_wave = ((kt + NW - 1) / NW + U - 1) / U * U;
@@ -85,7 +119,7 @@ __global__ __launch_bounds__(64 * NW) void ffn_skinny_kernel(SkinnyCtx c, const 
   for (int row0 = row_first; row0 < row_end; row0 += MR) {
     const int rows = min(MR, row_end - row0);
     const bool has_row = col < rows;
-    const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row0 + (has_row ? col : 0)) : row0 + (has_row ? col : 0);
+    const int in_row = GATEUP ? mapped_row(row_map, c.map_div, row0 + (has_row ? col : 0)) : row0 + (has_row ? col : 0);
     const u32x4* xin = (const u32x4*)(in + (size_t)in_row * K) + half;
 
     u32x4 wa[2][U], wb[2][U], xa[2][U];
@@ -195,10 +229,11 @@ static skinny_launch_fn pick(int shape) {
 // Work split for one of the two GEMVs: n_groups 32-row groups per expert, at most busy_max experts
 // with rows.  Measured on the decode shapes, 8 waves per block with 2 tiles per register set and one
 // group per block is at or near the best everywhere; very few (expert, group) tasks get 16 waves.
+// n_groups_dense: 32-row groups of the dense FFN that shares the launch (0: none); they fill extra grid rows.
 template <bool GATEUP>
-static void launch_stage(SkinnyCtx c, int n_groups, int busy_max, int max_rows, int kt, const bf16_t* in, bf16_t* out,
-                         hipStream_t s) {
-  const long tasks = (long)n_groups * busy_max;
+static void launch_stage(SkinnyCtx c, int n_groups, int busy_max, int max_rows, int n_groups_dense, const bf16_t* in,
+                         bf16_t* out, hipStream_t s) {
+  const long tasks = (long)n_groups * busy_max + n_groups_dense;
   int shape = tasks < 200 ? 5 : 4;
   int gpb = 1;
   if (const char* env = getenv("HMOE_SKINNY")) {  // tuning override: "<shape>,<groups per block>"
@@ -206,25 +241,40 @@ static void launch_stage(SkinnyCtx c, int n_groups, int busy_max, int max_rows, 
     if (sscanf(env, "%d,%d", &es, &eg) >= 1 && es >= 0 && es < kNumShapes) shape = es;
     if (eg > 0) gpb = eg;
   }
-  (void)kt;
   c.gpb = std::min(gpb, n_groups);
-  const dim3 grid((unsigned)((n_groups + c.gpb - 1) / c.gpb), (unsigned)busy_max);
+  const int grid_x = (n_groups + c.gpb - 1) / c.gpb;
+  c.shared.grid_rows = 0;
+  if (n_groups_dense > 0) {
+    const int blocks_dense = (n_groups_dense + c.gpb - 1) / c.gpb;
+    c.shared.grid_rows = (blocks_dense + grid_x - 1) / grid_x;
+  }
+  const dim3 grid((unsigned)grid_x, (unsigned)(c.shared.grid_rows + busy_max));
   (max_rows > 8 ? pick<GATEUP, 32>(shape) : pick<GATEUP, 8>(shape))(c, grid, in, out, s);
 }
 
-int launch_ffn_skinny(const FfnArgs& a) {
+// dense (or NULL): a dense FFN of the same hidden size over dense->n_rows rows (one resident expert: weights
+// at dense->slots, offsets {0, n_rows} implied), computed by extra blocks of the same two launches.
+int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense) {
   const hmoe_layer_desc& d = *a.desc;
   if (d.dtype != HMOE_BF16) return HMOE_ERR_UNSUPPORTED;
-  if (a.n_rows == 0) return HMOE_OK;
-  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div};
+  if (dense && (dense->desc->dtype != HMOE_BF16 || dense->desc->hidden != d.hidden)) return HMOE_ERR_UNSUPPORTED;
+  if (dense && dense->n_rows == 0) dense = nullptr;
+  if (a.n_rows == 0 && !dense) return HMOE_OK;
+  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div, {}};
+  int ffn_dense = 0;
+  if (dense) {
+    ffn_dense = dense->desc->ffn;
+    c.shared = SkinnyShared{dense->slots, (const bf16_t*)dense->x_perm, (bf16_t*)dense->h, (bf16_t*)dense->o_perm, ffn_dense,
+                            dense->n_rows, 0};
+  }
   const int busy_max = std::min(d.n_experts, a.n_rows);     // every busy expert has at least one row
-  const int max_rows = std::max(1, a.n_rows / d.top_k);     // a token names an expert at most once
+  int max_rows = std::max(1, a.n_rows / d.top_k);           // a token names an expert at most once
+  if (dense) max_rows = std::max(max_rows, dense->n_rows);
   probe_before(a.stream);
-  launch_stage<true>(c, d.ffn / TILE_N, busy_max, max_rows, d.hidden / TILE_K, (const bf16_t*)a.x_perm, (bf16_t*)a.h,
-                     a.stream);
+  launch_stage<true>(c, d.ffn / TILE_N, busy_max, max_rows, ffn_dense / TILE_N, (const bf16_t*)a.x_perm, (bf16_t*)a.h, a.stream);
   probe_after(a.stream);
-  launch_stage<false>(c, d.hidden / TILE_N, busy_max, max_rows, d.ffn / TILE_K, (const bf16_t*)a.h, (bf16_t*)a.o_perm,
-                      a.stream);
+  launch_stage<false>(c, d.hidden / TILE_N, busy_max, max_rows, dense ? d.hidden / TILE_N : 0, (const bf16_t*)a.h,
+                      (bf16_t*)a.o_perm, a.stream);
   HMOE_HIP(hipGetLastError());
   return HMOE_OK;
 }
@@ -412,7 +462,7 @@ int launch_ffn_skinny_w4(const FfnArgs& a) {
   const hmoe_layer_desc& d = *a.desc;
   if (d.dtype != HMOE_BF16_W4) return HMOE_ERR_UNSUPPORTED;
   if (a.n_rows == 0) return HMOE_OK;
-  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div};
+  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div, {}};
   const int busy_max = std::min(d.n_experts, a.n_rows);  // every busy expert has at least one row
   probe_before(a.stream);
   launch_stage_w4<true>(c, d.ffn, busy_max, (const bf16_t*)a.x_perm, (bf16_t*)a.h, a.stream);

@@ -475,3 +475,71 @@ def test_fused_and_unfused_layers_agree(hm, T):
         layer.close()
     assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
     assert np.array_equal(outs[0][0], outs[1][0])      # same kernels on the same rows: bit-identical outputs
+
+
+@pytest.mark.parametrize("T,hidden,ffn,shared_ffn,dtype", [
+    (1, 128, 192, (448,), "bf16"),       # 6 routed groups per expert, 14 shared groups: extra grid rows, the last one partly empty
+    (4, 256, 64, (64, 64), "bf16"),      # two shared experts packed as one
+    (8, 128, 320, (64,), "bf16"),        # fewer shared groups than one grid row holds
+    (9, 128, 128, (192,), "bf16"),       # more than 8 rows: the 32-row form of the kernel
+    (32, 64, 64, (192,), "bf16"),
+    (40, 128, 128, (128,), "bf16"),      # prefill-sized: the two calls run one after the other
+    (3, 64, 64, (64,), "f32"),           # fp32: likewise
+])
+def test_ffn_with_shared_equals_the_two_calls(hm, T, hidden, ffn, shared_ffn, dtype):
+    """hmoe_expert_ffn_grouped_with_shared writes the same bits into o_perm and o_shared as the gather call for the
+    routed experts followed by the plain call for the shared expert, whether or not the launches are merged; a
+    layer that uses it matches the oracle."""
+    say("ffn with shared", T, hidden, ffn, shared_ffn, dtype)
+    shape = wl.small_shape(dtype=wl.BF16 if dtype == "bf16" else wl.F32, hidden=hidden, ffn=ffn, n_experts=8, top_k=2,
+                           shared_ffn=shared_ffn)
+    lay = wl.make_layer(shape, 31 + T, T)
+    layer = build_layer(hm, lay, max_tokens=T)
+    d, K = layer.desc, 2
+    A = T * K
+    x = to_device(lay.x)
+    lg = lay.logits if lay.logits is not None else orc.router_logits(wl.as_f64(lay.x), wl.as_f64(lay.w_router)).astype(np.float32)
+    hm.hmoe_route_permute(d, to_device(lg), T, layer.topk_idx, layer.topk_w, layer.offsets, layer.perm, layer.inv_perm, None,
+                          layer.perm_ws, layer.perm_ws_bytes)
+    layer.shared_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
+    o_a, s_a = torch.full_like(layer.o_perm, 5.0), torch.full_like(layer.o_shared, 5.0)
+    o_b, s_b = torch.full_like(layer.o_perm, 6.0), torch.full_like(layer.o_shared, 6.0)
+    hm.hmoe_expert_ffn_grouped_with_shared(d, layer.cache, x, layer.perm, layer.offsets, A, None, o_a, layer.ffn_ws,
+                                           layer.ffn_ws_bytes, layer.shared_desc, layer.shared_cache, layer.shared_offsets, T,
+                                           s_a, layer.shared_ws, layer.shared_ws_bytes)
+    torch.cuda.synchronize()
+    hm.hmoe_expert_ffn_grouped_gather(d, layer.cache, x, layer.perm, layer.offsets, A, None, o_b, layer.ffn_ws,
+                                      layer.ffn_ws_bytes)
+    hm.hmoe_expert_ffn_grouped(layer.shared_desc, layer.shared_cache, x, layer.shared_offsets, T, None, s_b, layer.shared_ws,
+                               layer.shared_ws_bytes)
+    torch.cuda.synchronize()
+    assert torch.equal(o_a.cpu(), o_b.cpu()) and torch.equal(s_a.cpu(), s_b.cpu())
+    # an active list: only the named experts' rows are written, the shared part is unaffected
+    o_c, s_c = torch.full_like(layer.o_perm, 7.0), torch.full_like(layer.o_shared, 7.0)
+    hm.hmoe_expert_ffn_grouped_with_shared(d, layer.cache, x, layer.perm, layer.offsets, A, np.array([1, 5], np.int32), o_c,
+                                           layer.ffn_ws, layer.ffn_ws_bytes, layer.shared_desc, layer.shared_cache,
+                                           layer.shared_offsets, T, s_c, layer.shared_ws, layer.shared_ws_bytes)
+    torch.cuda.synchronize()
+    offs = layer.offsets.cpu().numpy()
+    got, full = to_host_f32(o_c), to_host_f32(o_b)
+    for e in range(8):
+        rows = slice(offs[e], offs[e + 1])
+        assert np.array_equal(got[rows], full[rows]) if e in (1, 5) else np.all(got[rows] == 7.0)
+    assert torch.equal(s_c.cpu(), s_b.cpu())
+    # the layer (which takes this call for T <= 32 in bf16) against the oracle
+    y = layer.forward(x, to_device(lg))
+    torch.cuda.synchronize()
+    assert max_rel_err(to_host_f32(y), oracle_layer(lay, lg)) < TOL[shape.dtype]
+    # argument checks
+    bad = hm.make_desc(hidden, shared_ffn[0], 2, 1, 2, d.dtype)
+    with pytest.raises(hm.HmoeError) as ei:
+        hm.hmoe_expert_ffn_grouped_with_shared(d, layer.cache, x, layer.perm, layer.offsets, A, None, o_a, layer.ffn_ws,
+                                               layer.ffn_ws_bytes, bad, layer.shared_cache, layer.shared_offsets, T, s_a,
+                                               layer.shared_ws, layer.shared_ws_bytes)
+    assert ei.value.status == hm.HMOE_ERR_INVALID_ARG
+    with pytest.raises(hm.HmoeError) as ei:
+        hm.hmoe_expert_ffn_grouped_with_shared(d, layer.cache, x, layer.perm, layer.offsets, A, None, o_a, layer.ffn_ws,
+                                               layer.ffn_ws_bytes, layer.shared_desc, layer.shared_cache,
+                                               layer.shared_offsets, T, s_a, layer.shared_ws, 0)
+    assert ei.value.status == hm.HMOE_ERR_WORKSPACE
+    layer.close()
