@@ -9,9 +9,10 @@ to a wait; this scan is the net under that rule.
 
 The scan is linear over each kernel's text, with the hardware's counter model: every vector-memory
 instruction enters a queue, s_waitcnt vmcnt(N) retires all but the youngest N.  While a hand-issued load is
-queued, any instruction that writes one of its destination registers, or that uses one as an address, is
-reported.  Reads by arithmetic instructions are not checked (the sources tie those to the waits, and the
-compiler places some of them out of line, which a linear scan cannot follow).
+queued, any instruction that writes one of its destination registers, or that reads one (as an address, as
+store data, or as the source of a vector ALU instruction, e.g. a copy into another register file), is
+reported.  Reads by the matrix instructions are not checked: the sources tie those to the waits, and the
+compiler places some of them out of line, which a linear scan cannot follow.
 """
 from __future__ import annotations
 
@@ -57,17 +58,21 @@ def _scan_kernel(name: str, lines: Iterable[Tuple[int, str]]) -> List[str]:
         is_load = is_vmem and "_load" in op and "_lds" not in op
         writes: Set[int] = set()
         addresses: Set[int] = set()
-        if is_load or op.startswith("ds_read") or (op.startswith("v_") and not op.startswith(("v_cmp", "v_readfirstlane", "v_readlane"))):
+        has_dest = is_load or op.startswith("ds_read") or (
+            op.startswith("v_") and not op.startswith(("v_cmp", "v_readfirstlane", "v_readlane")))
+        if has_dest:
             writes = _vregs(ops[0]) if ops else set()
-        if is_vmem or is_lds:
-            for o in (ops[1:] if (is_load or op.startswith("ds_read")) else ops):
+        if is_vmem or is_lds or (op.startswith("v_") and not op.startswith("v_mfma")):
+            # sources: of memory instructions (addresses, store data) and of every vector ALU instruction but the
+            # matrix ones (a copy to another register file is the typical case)
+            for o in (ops[1:] if has_dest else ops):
                 addresses |= _vregs(o)
         for dest, issued in queue:
             if dest & writes:
                 found.append("%s: line %d: %s writes v%s while the load of line %d may be in flight"
                              % (name, no, op, sorted(dest & writes), issued))
             if dest & addresses:
-                found.append("%s: line %d: %s takes an address or data from v%s while the load of line %d may be in flight"
+                found.append("%s: line %d: %s reads v%s while the load of line %d may be in flight"
                              % (name, no, op, sorted(dest & addresses), issued))
         if is_vmem:
             queue.append((writes if (is_load and in_asm) else set(), no))

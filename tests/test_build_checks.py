@@ -27,7 +27,7 @@ def test_register_of_a_load_in_flight():
     bad = listing(HAND + "\tv_lshl_add_u64 v[10:11], v[4:5], 0, s[2:3]\n"
                   "\t;;#ASMSTART\n\tglobal_load_dwordx4 v[10:13], v[10:11], off nt\n\t;;#ASMEND\n\ts_waitcnt vmcnt(0)\n")
     found = check(bad)
-    assert len(found) == 3 and "v_lshl_add_u64 writes v[10, 11]" in found[0] and "address" in found[2]
+    assert len(found) == 3 and "v_lshl_add_u64 writes v[10, 11]" in found[0] and "reads v[10, 11]" in found[2]
     # the same after a wait that covers the first load: clean
     good = listing(HAND + "\ts_waitcnt vmcnt(0)\n\tv_lshl_add_u64 v[10:11], v[4:5], 0, s[2:3]\n"
                    "\t;;#ASMSTART\n\tglobal_load_dwordx4 v[10:13], v[10:11], off nt\n\t;;#ASMEND\n\ts_waitcnt vmcnt(0)\n")
@@ -37,10 +37,15 @@ def test_register_of_a_load_in_flight():
                   "\tv_mov_b32_e32 v10, 0\n\tv_mov_b32_e32 v21, 0\n")
     found = check(two)
     assert len(found) == 1 and "v_mov_b32_e32 writes v[21]" in found[0]
-    # a load the compiler issued itself is its own business; reads by arithmetic are not checked; other registers are free
+    # a load the compiler issued itself is its own business; reads by matrix instructions are not checked; other
+    # registers are free
     own = listing("\tglobal_load_dwordx4 v[10:13], v[2:3], off\n\tv_mov_b32_e32 v10, 0\n" + HAND.replace("v[10:13]", "v[30:33]")
-                  + "\tv_add_f32_e32 v5, v30, v6\n\tds_read_b128 v[40:43], v7\n\ts_waitcnt vmcnt(0)\n")
+                  + "\tv_mfma_f32_32x32x16_bf16 v[50:65], v[30:33], v[44:47], v[50:65]\n\tds_read_b128 v[40:43], v7\n"
+                  "\ts_waitcnt vmcnt(0)\n")
     assert check(own) == []
+    # a copy of a destination into the accumulation registers before the wait: reported
+    copy = listing(HAND + "\tv_accvgpr_write_b32 a4, v11\n\ts_waitcnt vmcnt(0)\n")
+    assert len(check(copy)) == 1 and "v_accvgpr_write_b32 reads v[11]" in check(copy)[0]
     # an LDS read landing in the destination, a store of it: reported
     lds = listing(HAND + "\tds_read_b128 v[12:15], v7\n\tglobal_store_dword v[4:5], v11, off\n")
     assert len(check(lds)) == 2
