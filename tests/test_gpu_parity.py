@@ -477,6 +477,48 @@ def test_fused_and_unfused_layers_agree(hm, T):
     assert np.array_equal(outs[0][0], outs[1][0])      # same kernels on the same rows: bit-identical outputs
 
 
+@pytest.mark.parametrize("T,shared_ffn,logits_mode", [(4, (), "router"), (2, (64,), "zipf"), (70, (64,), "zipf"),
+                                                      (200, (), "router")])
+def test_graph_replay_equals_eager(hm, T, shared_ffn, logits_mode):
+    """The layer captured in a HIP graph (what the benchmark times) and replayed on fresh inputs, with eager work
+    and synchronisations between the replays, gives the bits of the eager calls every time, and matches the oracle.
+    Covers the decode front end in one launch, the shared expert inside the routed launches (T <= 32) and on its
+    side stream (T > 32), and the prefill kernels."""
+    say("graph replay", T, shared_ffn, logits_mode)
+    shape = wl.small_shape(dtype=wl.BF16, hidden=128, ffn=192, n_experts=8, top_k=2, shared_ffn=shared_ffn,
+                           x_mode="rmsnorm", logits_mode=logits_mode)
+    lays = [wl.make_layer(shape, 50, T)] + [wl.make_layer(shape, 51 + i, T, with_weights=False) for i in range(3)]
+    layer = build_layer(hm, lays[0], max_tokens=T)
+    x_in = torch.zeros(T, 128, dtype=torch.bfloat16, device=DEV)
+    lg_in = None if logits_mode == "router" else torch.zeros(T, 8, dtype=torch.float32, device=DEV)
+
+    def feed(lay):
+        x_in.copy_(to_device(lay.x))
+        if lg_in is not None:
+            lg_in.copy_(to_device(lay.logits))
+
+    feed(lays[0])
+    layer.forward(x_in, lg_in)                      # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        y_graph = layer.forward(x_in, lg_in)
+    for lay in lays[1:] + lays[:1]:
+        feed(lay)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = to_host_f32(y_graph).copy()
+        idx_graph = layer.topk_idx[:T].cpu().numpy().copy()
+        y_graph.zero_()                             # eager work between the replays
+        eager = to_host_f32(layer.forward(x_in, lg_in)).copy()
+        torch.cuda.synchronize()
+        assert np.array_equal(got, eager) and np.array_equal(idx_graph, layer.topk_idx[:T].cpu().numpy())
+        lg = lay.logits if lay.logits is not None else layer.logits[:T].cpu().numpy()
+        ref = orc.moe_layer(wl.as_f64(lay.x), lg, 2, lays[0].experts, lays[0].shared, to_f64=wl.as_f64)
+        assert max_rel_err(got, ref) < TOL[wl.BF16]
+    layer.close()
+
+
 @pytest.mark.parametrize("T,hidden,ffn,shared_ffn,dtype", [
     (1, 128, 192, (448,), "bf16"),       # 6 routed groups per expert, 14 shared groups: extra grid rows, the last one partly empty
     (4, 256, 64, (64, 64), "bf16"),      # two shared experts packed as one
