@@ -45,7 +45,7 @@ def main() -> int:
     ap.add_argument("--workload", default="mixtral", choices=sorted(PHASES))
     ap.add_argument("--layers", type=int, default=0, help="stress: stacked layers (default 27); others: weight sets rotated (default 3)")
     ap.add_argument("--weights", default="bf16", choices=["bf16", "w4"],
-                    help="w4: 4-bit group-wise expert weights (bf16 workloads, decode phases only)")
+                    help="w4: 4-bit group-wise expert weights (bf16 workloads)")
     ap.add_argument("--phase", default="", help="run only this phase of the workload (e.g. decode1), for profiling")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true")
@@ -75,9 +75,8 @@ def main() -> int:
     n_layers = args.layers or (27 if args.workload == "stress" else 3)
     phases = [p for p in PHASES[args.workload] if not args.phase or p[0] == args.phase]
     w4 = args.weights == "w4"
-    if w4:      # the 4-bit path is the weight-streaming decode kernel
+    if w4:
         assert bf16, "4-bit weights go with bf16 activations"
-        phases = [p for p in phases if p[0].startswith("decode")]
     w_bytes = (0.5 + 2.0 / 128) if w4 else elem      # bytes per stored expert weight (4-bit: codes + one bf16 scale per 128)
     assert phases, "workload %s has no phase %r" % (args.workload, args.phase)
     max_T = max(t for _, t in phases)

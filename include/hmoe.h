@@ -66,9 +66,9 @@ enum { HMOE_F32 = 0, HMOE_BF16 = 1, HMOE_BF16_W4 = 2 };
  * maximum and the division in fp32; code q = clamp(rint(W / s), -8, 7) + 8 in fp32 (nearest even), a
  * group of zeros has s = 0 and codes 8; the value used in the FFN is (q - 8) * s.  hmoe_pack_expert
  * quantises bfloat16 weights into this format (4.125 bits per weight in the slot).  Needs
- * H % 128 == 0 and F % 128 == 0.  FFN paths: HMOE_FFN_SKINNY (AUTO at every batch size) and
- * HMOE_FFN_REFERENCE; HMOE_FFN_TILED -> HMOE_ERR_UNSUPPORTED.  Everything else (router, route, permute,
- * combine) behaves as for HMOE_BF16.
+ * H % 128 == 0 and F % 128 == 0.  FFN paths: HMOE_FFN_SKINNY (AUTO up to 64 tokens), HMOE_FFN_TILED
+ * (AUTO above) and HMOE_FFN_REFERENCE.  Everything else (router, route, permute, combine) behaves as for
+ * HMOE_BF16.
  */
 
 /* Which FFN kernels hmoe_expert_ffn_grouped uses.  AUTO picks by token count. */
@@ -260,7 +260,7 @@ int32_t hmoe_route_scores(const hmoe_layer_desc* desc, const float* logits, int3
  *       HMOE_ERR_NOT_RESIDENT, nothing enqueued.  Rows of experts that are not active or not
  *       resident are left untouched.
  *   workspace: hmoe_ffn_workspace_bytes(desc, A) bytes of device scratch (holds h [A, F]).
- *   path: HMOE_FFN_*; AUTO = SKINNY when T = A/K <= 32 else TILED (bf16), REFERENCE (fp32).
+ *   path: HMOE_FFN_*; AUTO = SKINNY when T = A/K <= 32 (4-bit weights: 64) else TILED, REFERENCE for fp32.
  * Shared experts (Section II-A) use the same call with a 1-expert layer (E = K = S = 1,
  * offsets {0, T}).
  */

@@ -23,7 +23,7 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhmoe.so")
 
 SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "ffn_reference.hip", "ffn_skinny.hip",
-           "ffn_tiled.hip", "schedule.hip"]
+           "ffn_tiled.hip", "ffn_tiled_w4.hip", "schedule.hip"]
 HAND_ISSUED_LOADS = ["ffn_tiled.hip"]   # sources whose kernels load into registers from inline assembly
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -461,18 +461,17 @@ static int32_t ffn_prepare(const hmoe_layer_desc* desc, hmoe_cache* cache, const
 
   if (*path == HMOE_FFN_AUTO) {
     if (desc->dtype == HMOE_F32) *path = HMOE_FFN_REFERENCE;
-    else if (desc->dtype == HMOE_BF16_W4) *path = HMOE_FFN_SKINNY;  // the weight-streaming kernel at every batch size
+    else if (desc->dtype == HMOE_BF16_W4) *path = (A / desc->top_k <= 64) ? HMOE_FFN_SKINNY : HMOE_FFN_TILED;
     else *path = (A / desc->top_k <= 32) ? HMOE_FFN_SKINNY : HMOE_FFN_TILED;
   }
   if (desc->dtype == HMOE_F32 && *path != HMOE_FFN_REFERENCE) return HMOE_ERR_UNSUPPORTED;
-  if (desc->dtype == HMOE_BF16_W4 && *path == HMOE_FFN_TILED) return HMOE_ERR_UNSUPPORTED;
   return HMOE_OK;
 }
 
 static int32_t ffn_launch(const FfnArgs& a, int32_t path) {
   if (path == HMOE_FFN_REFERENCE) return launch_ffn_reference(a);
   if (path == HMOE_FFN_SKINNY) return a.desc->dtype == HMOE_BF16_W4 ? launch_ffn_skinny_w4(a) : launch_ffn_skinny(a);
-  return launch_ffn_tiled(a);
+  return a.desc->dtype == HMOE_BF16_W4 ? launch_ffn_tiled_w4(a) : launch_ffn_tiled(a);
 }
 
 // remembers, per slot, the last call that read it, so that a later copy into the slot can wait for it

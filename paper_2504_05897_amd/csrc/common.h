@@ -137,6 +137,7 @@ int launch_ffn_reference(const FfnArgs& a);
 int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense = nullptr);
 int launch_ffn_tiled(const FfnArgs& a);
 int launch_ffn_skinny_w4(const FfnArgs& a);
+int launch_ffn_tiled_w4(const FfnArgs& a);
 
 }  // namespace hmoe
 

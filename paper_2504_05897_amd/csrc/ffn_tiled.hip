@@ -29,21 +29,9 @@
 #include <algorithm>
 
 #include "common.h"
+#include "tile_locate.h"
 
 namespace hmoe {
-
-struct TiledCtx {
-  const int32_t* offsets;
-  const int32_t* slot_of;
-  const char* slots;
-  size_t slot_bytes;
-  ActiveMask active;
-  int n_experts, hidden, ffn;
-  int n_tiles_n;  // n-tiles per expert
-  int grid_padded;  // blocks launched: an upper bound of the tile count, a multiple of 8
-  const int32_t* row_map;  // gate/up only: input row of sorted row p is row_map[p] / map_div
-  int map_div;
-};
 
 // One 16-byte global -> LDS copy per lane; the wave's 64 chunks land at lds_base .. +1024 in lane
 // order.  lds_base must be wave-uniform.  Completion is tracked by vmcnt like any vector load.
@@ -63,65 +51,6 @@ __device__ __forceinline__ void block_barrier() {
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-}
-
-// The tile a block works on.  The logical tile list is: for each busy expert in ascending id (rows > 0,
-// selected by the mask, resident), for each n-tile, every m-tile of BM rows.  The hardware deals
-// consecutive block ids round-robin to the 8 XCDs, so block b takes entry (b / 8) of the (b % 8)-th
-// eighth of the list: each XCD works through one contiguous range (blocks that share a weight panel
-// share an L2) and the eight ranges differ by at most one tile.  The launch only knows an upper bound
-// of the list length; the exact length comes from expert_offsets here, lane-parallel over the
-// experts, and every wave of the block computes the same answer.  Returns false for surplus blocks.
-struct TileLoc {
-  int e, row_first, m_rows, mt, nt;
-};
-template <int BM>
-__device__ __forceinline__ bool locate_tile(const TiledCtx& c, TileLoc& t) {
-  constexpr int CH = HMOE_MAX_EXPERTS / 64;
-  const int lane = threadIdx.x % 64;
-  int first[CH], rows[CH], incl[CH];
-  int total = 0;
-#pragma unroll
-  for (int j = 0; j < CH; ++j) {
-    first[j] = rows[j] = 0;
-    incl[j] = total;
-    if (j * 64 < c.n_experts) {  // uniform
-      const int i = j * 64 + lane;
-      if (i < c.n_experts && ((c.active.w[j] >> lane) & 1ull) && c.slot_of[i] >= 0) {
-        first[j] = c.offsets[i];
-        rows[j] = c.offsets[i + 1] - first[j];
-      }
-      int v = (rows[j] + BM - 1) / BM * c.n_tiles_n;
-#pragma unroll
-      for (int d = 1; d < 64; d *= 2) {
-        const int below = __shfl_up(v, d);
-        if (lane >= d) v += below;
-      }
-      incl[j] = total + v;
-      total += __shfl(v, 63);
-    }
-  }
-  const int per_xcd = (total + 7) / 8;
-  const int idx = blockIdx.x / 8;
-  const int tile_id = (blockIdx.x % 8) * per_xcd + idx;
-  if (idx >= per_xcd || tile_id >= total) return false;
-#pragma unroll
-  for (int j = 0; j < CH; ++j) {
-    const unsigned long long past = __ballot(incl[j] > tile_id);  // inclusive prefix sums are monotone
-    if (past) {
-      const int src = __ffsll((long long)past) - 1;
-      // wave-uniform by construction; readfirstlane tells the compiler so (scalar registers, scalar loads)
-      t.e = j * 64 + src;
-      t.row_first = __builtin_amdgcn_readfirstlane(__shfl(first[j], src));
-      t.m_rows = __builtin_amdgcn_readfirstlane(__shfl(rows[j], src));
-      const int mts = (t.m_rows + BM - 1) / BM;
-      const int within = __builtin_amdgcn_readfirstlane(tile_id - (__shfl(incl[j], src) - mts * c.n_tiles_n));
-      t.nt = within / mts;
-      t.mt = within % mts;
-      return true;
-    }
-  }
-  return false;
 }
 
 template <bool GATEUP_, int BM_, int BN_, int BKT_, int STAGES, int WM, int WN>
@@ -598,11 +527,6 @@ __global__ __launch_bounds__(2 * TILE::THREADS) void ffn_tile_k2_kernel(TiledCtx
       }
   }
   TILE::epilogue_part(c, out, loc, acc, group * HALF, (group + 1) * HALF);
-}
-
-// upper bound of the tile count of a launch (sum over experts of ceil(rows / BM) is at most this)
-static long tiles_upper_bound(const TiledCtx& c, int n_rows, int bm) {
-  return ((long)n_rows / bm + std::min(c.n_experts, n_rows)) * c.n_tiles_n;
 }
 
 template <class TILE>

@@ -1,5 +1,5 @@
-"""4-bit expert weights (HMOE_BF16_W4) on the GPU: the weight-streaming kernel and the reference kernel against
-the oracle, which evaluates the FFN with every weight replaced by the value its 4-bit code stands for."""
+"""4-bit expert weights (HMOE_BF16_W4) on the GPU: the weight-streaming decode kernel, the prefill tile kernel and
+the reference kernel against the oracle, which evaluates the FFN with every weight replaced by the value its 4-bit code stands for."""
 import sys
 
 import numpy as np
@@ -30,12 +30,13 @@ def as_quantised(m):
     return w4.dequantize_w4(*w4.quantize_w4(wl.as_f32(m)))
 
 
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 @pytest.mark.parametrize("hidden,ffn,counts", [
     (256, 128, [3, 0, 7, 1, 40, 0, 9, 2]),       # decode-sized groups and one of 40 rows (two passes of 32)
-    (128, 384, [33, 1, 0, 0, 70, 5, 8, 32]),     # one scale group in gate/up, three in down
+    (128, 384, [33, 1, 0, 0, 70, 5, 8, 32]),     # one scale group in gate/up, three in down; half-filled column tile in down
     (1024, 256, [0, 0, 0, 1, 0, 0, 0, 0]),       # as many scale groups as waves
     (2048, 128, [8, 9]),                         # more scale groups than waves: two per wave
+    (640, 512, [130, 0, 64, 257]),               # several row tiles with ragged ends; 5 and 4 scale groups (not a multiple of the ring)
 ])
 def test_ffn_w4_paths(hm, path, hidden, ffn, counts):
     say("ffn w4 path", path, hidden, ffn, counts)
@@ -60,9 +61,6 @@ def test_ffn_w4_paths(hm, path, hidden, ffn, counts):
             ref[lo:hi] = orc.expert_ffn(wl.as_f64(xp[lo:hi]), *(as_quantised(m) for m in lay.experts[e]))
     assert max_rel_err(to_host_f32(o), ref) < TOL[wl.BF16]
     assert np.abs(ref).max() > 1e-3
-    with pytest.raises(hm.HmoeError) as ei:                               # no prefill-tile kernels for 4-bit weights
-        hm.hmoe_expert_ffn_grouped(d, layer.cache, to_device(xp), to_device(offsets), A, None, o, ws, ws_bytes, 3)
-    assert ei.value.status == hm.HMOE_ERR_UNSUPPORTED
     layer.close()
 
 
@@ -82,10 +80,11 @@ def test_w4_layer_with_shared_experts_and_partial_cache(hm, T):
     layer.close()
 
 
-@pytest.mark.parametrize("T", [1, 8])
-def test_mixtral_decode_w4_full_size(hm, T):
-    """The Mixtral-style shape at full size with 4-bit experts, all resident, as the benchmark runs it."""
-    say("mixtral w4 decode", T)
+@pytest.mark.parametrize("T", [1, 8, 512])
+def test_mixtral_w4_full_size(hm, T):
+    """The Mixtral-style shape at full size with 4-bit experts, all resident, as the benchmark runs it: the decode
+    kernel (1 and 8 tokens) and the prefill tile kernel (512 tokens)."""
+    say("mixtral w4", T)
     shape = wl.SHAPES["mixtral"]
     lay = wl.make_layer(shape, 1, T, threads=16)
     d = hm.make_desc(shape.hidden, shape.ffn, shape.n_experts, shape.top_k, shape.n_experts, hm.HMOE_BF16_W4)
