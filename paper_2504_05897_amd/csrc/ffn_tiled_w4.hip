@@ -27,7 +27,6 @@
 #include "tile_locate.h"
 
 namespace hmoe {
-namespace {
 
 constexpr int W4T_WAVES = 8;
 constexpr int W4T_NU = 2;        // packed 16-row units per wave
@@ -236,14 +235,12 @@ __global__ __launch_bounds__(64 * W4T_WAVES) void ffn_tile_w4_kernel(TiledCtx c,
 }
 
 template <bool GATEUP, int BM, int RING>
-void launch_stage_tile_w4(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
+static void launch_stage_tile_w4(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
   const int units_total = (GATEUP ? 2 * c.ffn : c.hidden) / 16;
   c.n_tiles_n = (units_total + W4T_UNITS - 1) / W4T_UNITS;
   c.grid_padded = (int)((tiles_upper_bound(c, n_rows, BM) + 7) / 8 * 8);
   hipLaunchKernelGGL((ffn_tile_w4_kernel<GATEUP, BM, RING>), dim3((unsigned)c.grid_padded), dim3(64 * W4T_WAVES), 0, s, c, in, out);
 }
-
-}  // namespace
 
 int launch_ffn_tiled_w4(const FfnArgs& a) {
   const hmoe_layer_desc& d = *a.desc;
