@@ -279,11 +279,17 @@ __device__ __forceinline__ void wait_vmcnt_regs(u32x4& a, u32x4& b) {
   asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
 
-template <bool GATEUP_, int BM_, int NWV, int SA, bool SKIP, bool NT, int DB = 8>
+// FMC (0: off): the tile multiplies only its first FMC 32-row fragments and consecutive m-tiles of an expert
+// start 32 * FMC rows apart (the activation copies still move BM rows).  The kernel picks FMC per expert so
+// that the expert's m-tiles are equally high (see ffn_tile_fit_kernel).
+template <bool GATEUP_, int BM_, int NWV, int SA, bool SKIP, bool NT, int DB = 8, int FMC = 0>
 struct StreamTile {
   static constexpr bool GATEUP = GATEUP_;
   static constexpr int BM = BM_;
-  static constexpr int FN = 2, BN = NWV * 64, FM = BM / 32, BKT = 64, KK = 4;
+  static constexpr int FN = 2, BN = NWV * 64, BKT = 64, KK = 4;
+  static constexpr int FM = FMC > 0 ? FMC : BM / 32;   // fragments multiplied
+  static constexpr int MSTRIDE = 32 * FM;              // rows between the starts of consecutive m-tiles
+  static_assert(FM * 32 <= BM, "");
   static_assert(DB % KK == 0, "the weight ring holds whole K steps");
   static constexpr int CPR = BKT / 8, RP = 256 / (BKT * 2);
   static constexpr int A_CHUNKS = BM * CPR;
@@ -308,7 +314,7 @@ struct StreamTile {
     const int kt16 = K / TILE_K;
     const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
     const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
-    const int m0 = mt * BM;
+    const int m0 = mt * MSTRIDE;
     const int tid = threadIdx.x % THREADS, wave = tid / 64, lane = tid % 64;  // a block may hold two groups of NWV waves
     const int half = lane / 32, col = lane % 32;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
@@ -427,7 +433,7 @@ struct StreamTile {
                                                        const Acc& acc, int i_first, int i_last) {
     const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
     const int n_out = GATEUP ? c.ffn : c.hidden;
-    const int m0 = loc.mt * BM;
+    const int m0 = loc.mt * MSTRIDE;
     const int tid = threadIdx.x % THREADS, wave = tid / 64, lane = tid % 64;
     const int half = lane / 32, col = lane % 32;
     // ---- epilogue: accumulator register r of lane (half, col) is row 8*(r/4) + 4*half + r%4 ----
@@ -466,6 +472,15 @@ __device__ __forceinline__ void zero_acc(typename TILE::Acc& acc) {
     for (int j = 0; j < TILE::FN; ++j) acc[i][j] = f32x16_t{0};
 }
 
+template <class TILE>
+__device__ __forceinline__ void run_tile(const TiledCtx& c, const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
+                                         const TileLoc& loc, u32x4* lds) {
+  typename TILE::Acc acc;
+  zero_acc<TILE>(acc);
+  TILE::mainloop(c, in, loc, 0, (TILE::GATEUP ? c.hidden : c.ffn) / TILE::BKT, lds, acc);
+  TILE::epilogue(c, out, loc, acc);
+}
+
 // One block per tile, the whole K range.
 template <class TILE>
 __global__ __launch_bounds__(TILE::THREADS) void ffn_tile_kernel(TiledCtx c, const bf16_t* __restrict__ in,
@@ -473,10 +488,36 @@ __global__ __launch_bounds__(TILE::THREADS) void ffn_tile_kernel(TiledCtx c, con
   __shared__ u32x4 lds[TILE::LDS_VEC];
   TileLoc loc;
   if (!locate_tile<TILE::BM>(c, loc)) return;  // uniform over the block
-  typename TILE::Acc acc;
-  zero_acc<TILE>(acc);
-  TILE::mainloop(c, in, loc, 0, (TILE::GATEUP ? c.hidden : c.ffn) / TILE::BKT, lds, acc);
-  TILE::epilogue(c, out, loc, acc);
+  run_tile<TILE>(c, in, out, loc, lds);
+}
+
+// One block per tile, tile height fitted to the expert.  An expert of R rows has ceil(R / 128) m-tiles whatever
+// their height; instead of 128 rows each (the last one mostly padding when R is just above a multiple of 128)
+// they all get ceil(R / tiles) rows, rounded up to whole 32-row fragments, and the block runs the tile type
+// that multiplies that many fragments.  The m-tiles of one weight panel stay equally long -- their blocks run
+// side by side and share the panel through L2, which uneven tiles would break -- and the padding rows that are
+// multiplied drop from up to 127 to at most 31 per m-tile.
+template <bool GATEUP, int NWV, bool NT>
+__global__ __launch_bounds__(64 * NWV) void ffn_tile_fit_kernel(TiledCtx c, const bf16_t* __restrict__ in,
+                                                                 bf16_t* __restrict__ out) {
+  typedef StreamTile<GATEUP, 128, NWV, 4, false, NT, 8, 4> FULL;
+  __shared__ u32x4 lds[FULL::LDS_VEC];
+  TileLoc loc;
+  if (!locate_tile<128>(c, loc)) return;  // uniform over the block
+  const int tiles = (loc.m_rows + 127) / 128;
+  const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;  // per m-tile, 1..4; uniform
+  if (fragments == 4) run_tile<FULL>(c, in, out, loc, lds);
+  else if (fragments == 3) run_tile<StreamTile<GATEUP, 128, NWV, 4, false, NT, 8, 3>>(c, in, out, loc, lds);
+  else if (fragments == 2) run_tile<StreamTile<GATEUP, 128, NWV, 4, false, NT, 8, 2>>(c, in, out, loc, lds);
+  else run_tile<StreamTile<GATEUP, 128, NWV, 4, false, NT, 8, 1>>(c, in, out, loc, lds);
+}
+
+template <bool GATEUP, int NWV, bool NT>
+static void launch_tiles_fit(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
+  const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
+  c.n_tiles_n = (n_total + NWV * 64 - 1) / (NWV * 64);
+  c.grid_padded = (int)((tiles_upper_bound(c, n_rows, 128) + 7) / 8 * 8);
+  hipLaunchKernelGGL((ffn_tile_fit_kernel<GATEUP, NWV, NT>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in, out);
 }
 
 // One block per tile, two groups of TILE::THREADS threads: each group runs the tile's main loop over one
@@ -558,6 +599,7 @@ struct TiledVariant {
     launch_tiles<LdsRingTile<false, BM, BN, BKT, ST, WM, WN>> }
 #define HMOE_STREAM(NAME, NWV, SKIP, NT) \
   { NAME, launch_tiles<StreamTile<true, 128, NWV, 4, SKIP, NT>>, launch_tiles<StreamTile<false, 128, NWV, 4, SKIP, NT>> }
+#define HMOE_STREAM_FIT(NAME, NWV, NT) { NAME, launch_tiles_fit<true, NWV, NT>, launch_tiles_fit<false, NWV, NT> }
 #define HMOE_STREAM_K2(NAME, NT) \
   { NAME, launch_tiles_k2<StreamTile<true, 128, 4, 4, false, NT, 4>>, launch_tiles_k2<StreamTile<false, 128, 4, 4, false, NT, 4>> }
 static const TiledVariant kVariants[] = {
@@ -578,8 +620,10 @@ static const TiledVariant kVariants[] = {
     HMOE_STREAM("stream 128x512 s4 plain", 8, false, false),  // 14: 10 with plain weight loads
     HMOE_STREAM_K2("stream 128x256 s4 k2", true),             // 15: 9 with two wave groups that split K
     HMOE_STREAM_K2("stream 128x256 s4 k2 plain", false),      // 16: 15 with plain weight loads
+    HMOE_STREAM_FIT("stream 128x512 s4 fit", 8, true),        // 17: 10 with the tile height fitted to the expert
+    HMOE_STREAM_FIT("stream 128x512 s4 fit plain", 8, false), // 18: 14 likewise
 };
-constexpr int kFirstSplitK = 15;  // these need an even number of K steps of 64
+constexpr int kFirstSplitK = 15, kLastSplitK = 16;  // these need an even number of K steps of 64
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 int launch_ffn_tiled(const FfnArgs& a) {
@@ -591,8 +635,8 @@ int launch_ffn_tiled(const FfnArgs& a) {
   bf16_t* h = (bf16_t*)a.h;
   bf16_t* o = (bf16_t*)a.o_perm;
   // Kernel choice (measured on the workload shapes; the tile counts are the launch's upper bounds).  The
-  // weight-streaming family with 8 waves and a 128x512 tile wins whenever it yields two rounds of blocks
-  // per CU or more.  With fewer tiles the round-up to whole rounds costs more than the kernel gains:
+  // weight-streaming family with 8 waves and a 128x512 tile (tile height fitted to each expert: 2-4 % over
+  // fixed 128 rows on every workload) wins whenever it yields two rounds of blocks per CU or more.  With fewer tiles the round-up to whole rounds costs more than the kernel gains:
   // gate/up then takes the 128x256 LDS-ring tile (twice the blocks), and the down projection of few,
   // large experts (small N) the 128x256 streaming tile with 4 waves.  A launch whose 128x256 tiles cover at
   // most half of the CUs (a shared expert at a moderate batch) takes that tile with two wave groups that
@@ -602,10 +646,10 @@ int launch_ffn_tiled(const FfnArgs& a) {
   const long tiles_down = m_tiles * ((d.hidden + 511) / 512);
   // Many m-tiles per expert (512 rows or more on average): the panel is shared through L2, plain loads.
   const bool shared_panels = a.n_rows / d.n_experts >= 512;
-  auto split_k_fits = [](int variant, int k) { return variant < kFirstSplitK || (k / 64) % 2 == 0; };
+  auto split_k_fits = [](int variant, int k) { return variant < kFirstSplitK || variant > kLastSplitK || (k / 64) % 2 == 0; };
   const int v_split_k = shared_panels ? 16 : 15;
-  int v_gate_up = tiles_gate_up < 512 ? 1 : (shared_panels ? 14 : 10);
-  int v_down = tiles_down < 256 ? (shared_panels ? 13 : 9) : (shared_panels ? 14 : 10);
+  int v_gate_up = tiles_gate_up < 512 ? 1 : (shared_panels ? 18 : 17);
+  int v_down = tiles_down < 256 ? (shared_panels ? 13 : 9) : (shared_panels ? 18 : 17);
   if (m_tiles * ((2 * d.ffn + 255) / 256) <= 128 && split_k_fits(v_split_k, d.hidden)) v_gate_up = v_split_k;
   if (m_tiles * ((d.hidden + 255) / 256) <= 128 && split_k_fits(v_split_k, d.ffn)) v_down = v_split_k;
   if (const char* env = getenv("HMOE_TILED_VARIANT")) {
