@@ -80,6 +80,46 @@ __global__ __launch_bounds__(PB_THREADS) void permute_scan_kernel(int32_t* __res
   }
 }
 
+// The whole permutation of at most 64 assignments (every decode batch) by one wavefront, without LDS and
+// without barriers: lane a holds assignment a, learns every other key through readlane, and counts the
+// keys that sort before its own (smaller key, or equal key in a lower lane: the stable order); lane l
+// does the same counting for experts l, 64 + l, ... to produce the offsets.  Same integers as the general
+// path.  Call with the first wavefront of a block.
+__device__ __forceinline__ void permute_rank_one_wave(const int32_t* topk_idx, int n_assign, int n_experts,
+                                                      int32_t* __restrict__ expert_offsets,
+                                                      int32_t* __restrict__ counts_out, int32_t* __restrict__ perm,
+                                                      int32_t* __restrict__ inv_perm) {
+  constexpr int CH = HMOE_MAX_EXPERTS / 64;
+  const int lane = threadIdx.x % 64;
+  const bool valid = lane < n_assign;
+  const int key = valid ? clamp_key(topk_idx[lane], n_experts) : n_experts;
+  int before = 0, below[CH], equal[CH];
+#pragma unroll
+  for (int j = 0; j < CH; ++j) below[j] = equal[j] = 0;
+  for (int i = 0; i < n_assign; ++i) {  // uniform
+    const int ki = __builtin_amdgcn_readlane(key, i);
+    before += (ki < key) | ((ki == key) & (i < lane));
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      below[j] += ki < j * 64 + lane;
+      equal[j] += ki == j * 64 + lane;
+    }
+  }
+  if (valid) {
+    perm[before] = lane;
+    inv_perm[lane] = before;
+  }
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int e = j * 64 + lane;
+    if (e < n_experts) {
+      expert_offsets[e] = below[j];
+      if (counts_out) counts_out[e] = equal[j];
+    }
+  }
+  if (lane == 0) expert_offsets[n_experts] = n_assign;
+}
+
 // Ranks one chunk.  SINGLE: the chunk is the whole input and this block also builds the offsets.
 template <bool SINGLE>
 __device__ __forceinline__ void permute_rank_body(const int32_t* topk_idx, int n_assign, int n_experts, int key_bits,
@@ -90,6 +130,10 @@ __device__ __forceinline__ void permute_rank_body(const int32_t* topk_idx, int n
   __shared__ int wave_base[PB_WAVES][HMOE_MAX_EXPERTS];  // first counts, then running bases
   __shared__ int scan_tmp[HMOE_MAX_EXPERTS];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  if (SINGLE && n_assign <= 64) {  // uniform over the block: nothing below runs, so no barrier is left unmatched
+    if (wave == 0) permute_rank_one_wave(topk_idx, n_assign, n_experts, expert_offsets, counts_out, perm, inv_perm);
+    return;
+  }
   for (int i = threadIdx.x; i < PB_WAVES * HMOE_MAX_EXPERTS; i += PB_THREADS) (&wave_base[0][0])[i] = 0;
   __syncthreads();
 

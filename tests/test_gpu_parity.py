@@ -52,7 +52,7 @@ def test_route_bit_exact(hm, T, E, K):
 # ----------------------------------------------------------------------------------------- permute
 @pytest.mark.parametrize("T,E,K", [(1, 8, 2), (16, 8, 2), (1, 64, 6), (4, 64, 8), (512, 8, 2), (171, 64, 6),
                                    (1024, 64, 1), (1025, 64, 1), (16384, 64, 6), (3000, 200, 5), (0, 8, 2),
-                                   (2048, 64, 8)])
+                                   (2048, 64, 8), (32, 8, 2), (13, 64, 5), (2, 256, 32), (1, 256, 32), (64, 3, 1)])
 def test_permute_bit_exact(hm, T, E, K):
     say("permute", T, E, K)
     rng = np.random.default_rng(T + 17 * E)
@@ -391,7 +391,7 @@ def test_cache_stage_errors_and_pinning(hm):
 
 # ----------------------------------------------------------------------------------------- fused entry points
 @pytest.mark.parametrize("T,E,K", [(1, 8, 2), (1, 64, 6), (4, 64, 8), (32, 64, 8), (64, 16, 16), (65, 16, 8), (128, 8, 8),
-                                   (300, 64, 6), (0, 8, 2)])
+                                   (300, 64, 6), (0, 8, 2), (8, 256, 8), (2, 200, 9), (32, 8, 2), (11, 60, 6)])
 def test_route_permute_fused_equals_the_two_calls(hm, T, E, K):
     """hmoe_route_permute (one launch for T <= 64 and T*K <= 1024) against the oracle, bit for bit."""
     say("route_permute", T, E, K)
