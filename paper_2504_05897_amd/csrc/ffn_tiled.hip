@@ -644,8 +644,8 @@ int launch_ffn_tiled(const FfnArgs& a) {
   const long m_tiles = (long)a.n_rows / 128 + std::min(d.n_experts, a.n_rows);
   const long tiles_gate_up = m_tiles * ((2 * d.ffn + 511) / 512);
   const long tiles_down = m_tiles * ((d.hidden + 511) / 512);
-  // Many m-tiles per expert (512 rows or more on average): the panel is shared through L2, plain loads.
-  const bool shared_panels = a.n_rows / d.n_experts >= 512;
+  // Several m-tiles per expert (192 rows or more on average): the panel is shared through L2, plain loads.
+  const bool shared_panels = a.n_rows / d.n_experts >= 192;
   auto split_k_fits = [](int variant, int k) { return variant < kFirstSplitK || variant > kLastSplitK || (k / 64) % 2 == 0; };
   const int v_split_k = shared_panels ? 16 : 15;
   int v_gate_up = tiles_gate_up < 512 ? 1 : (shared_panels ? 18 : 17);
