@@ -127,3 +127,32 @@ def test_workload5_stress_layers(hm):
         say("  layer", li, "err", err)
         layer.close()
         assert err < TOL[wl.BF16]
+
+
+def test_bench_line_contract():
+    """bench.py prints one JSON line with the fields the harness reads: metric, value, timing, the roofline of the
+    dominant kernel and the CPU-oracle baseline; a GPU count above one is refused."""
+    import json
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    print("bench contract", flush=True)
+    run = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "3", "--warmup", "1"],
+                         capture_output=True, text=True, timeout=300, cwd=root)
+    assert run.returncode == 0, run.stderr[-2000:]
+    lines = [l for l in run.stdout.splitlines() if l.startswith("{")]
+    assert len(lines) == 1
+    out = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in out, key
+    assert out["n_gpus"] == 1 and out["steps"] == 3 and out["warmup"] == 1 and out["higher_is_better"] is True
+    assert out["value"] > 0 and out["ms_per_step"] > 0 and out["config"]["workload"] == "mixtral/prefill512"
+    roof = out["roofline"]
+    assert roof["bound"] in ("hbm", "mfma") and roof["unit"] in ("GB/s", "TFLOP/s") and roof["peak"] in (8000.0, 2500.0)
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9 and 0 < roof["frac"] < 1
+    cpu = out["cpu_baseline"]
+    assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["unit"] == out["unit"] and cpu["sample"]
+    refused = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                             timeout=120, cwd=root)
+    assert refused.returncode != 0 and "ONE GPU" in (refused.stderr + refused.stdout)
