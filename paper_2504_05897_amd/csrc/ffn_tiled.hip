@@ -282,7 +282,7 @@ __device__ __forceinline__ void wait_vmcnt_regs(u32x4& a, u32x4& b) {
 // FMC (0: off): the tile multiplies only its first FMC 32-row fragments and consecutive m-tiles of an expert
 // start 32 * FMC rows apart (the activation copies still move BM rows).  The kernel picks FMC per expert so
 // that the expert's m-tiles are equally high (see ffn_tile_fit_kernel).
-template <bool GATEUP_, int BM_, int NWV, int SA, bool SKIP, bool NT, int DB = 8, int FMC = 0>
+template <bool GATEUP_, int BM_, int NWV, int SA, bool NT, int DB = 8, int FMC = 0>
 struct StreamTile {
   static constexpr bool GATEUP = GATEUP_;
   static constexpr int BM = BM_;
@@ -347,15 +347,12 @@ struct StreamTile {
 
     u32x4 ring[DB][FN];
     u32x4 fa[2][FM];
-    // SKIP: 32-row fragments past the end of the expert (ragged last m-tile) are neither read nor
-    // multiplied; the count is the same for every wave of the block.
-    const int fm_live = SKIP ? min(FM, (m_rows - m0 + 31) / 32) : FM;
     auto read_a = [&](int buf, int stage, int kk) {
       const u32x4* sa = lds + stage * A_CHUNKS;
 #pragma unroll
       for (int i = 0; i < FM; ++i) {
         const int r = i * 32 + col;
-        if (!SKIP || i < fm_live) fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
+        fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
       }
     };
 
@@ -397,12 +394,9 @@ struct StreamTile {
             const int sl = h * KK + kk;  // ring slot of substep 4*tt + kk
             wait_vmcnt_regs<N_B>(ring[sl][0], ring[sl][1]);
 #pragma unroll
-            for (int i = 0; i < FM; ++i) {
-              if (!SKIP || i < fm_live) {
+            for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
-              }
-            }
+              for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
             __builtin_amdgcn_sched_barrier(0);
             const int s_next = tt * KK + kk + DB;
 #pragma unroll
@@ -500,16 +494,16 @@ __global__ __launch_bounds__(TILE::THREADS) void ffn_tile_kernel(TiledCtx c, con
 template <bool GATEUP, int NWV, bool NT>
 __global__ __launch_bounds__(64 * NWV) void ffn_tile_fit_kernel(TiledCtx c, const bf16_t* __restrict__ in,
                                                                  bf16_t* __restrict__ out) {
-  typedef StreamTile<GATEUP, 128, NWV, 4, false, NT, 8, 4> FULL;
+  typedef StreamTile<GATEUP, 128, NWV, 4, NT, 8, 4> FULL;
   __shared__ u32x4 lds[FULL::LDS_VEC];
   TileLoc loc;
   if (!locate_tile<128>(c, loc)) return;  // uniform over the block
   const int tiles = (loc.m_rows + 127) / 128;
   const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;  // per m-tile, 1..4; uniform
   if (fragments == 4) run_tile<FULL>(c, in, out, loc, lds);
-  else if (fragments == 3) run_tile<StreamTile<GATEUP, 128, NWV, 4, false, NT, 8, 3>>(c, in, out, loc, lds);
-  else if (fragments == 2) run_tile<StreamTile<GATEUP, 128, NWV, 4, false, NT, 8, 2>>(c, in, out, loc, lds);
-  else run_tile<StreamTile<GATEUP, 128, NWV, 4, false, NT, 8, 1>>(c, in, out, loc, lds);
+  else if (fragments == 3) run_tile<StreamTile<GATEUP, 128, NWV, 4, NT, 8, 3>>(c, in, out, loc, lds);
+  else if (fragments == 2) run_tile<StreamTile<GATEUP, 128, NWV, 4, NT, 8, 2>>(c, in, out, loc, lds);
+  else run_tile<StreamTile<GATEUP, 128, NWV, 4, NT, 8, 1>>(c, in, out, loc, lds);
 }
 
 template <bool GATEUP, int NWV, bool NT>
@@ -597,33 +591,29 @@ struct TiledVariant {
 #define HMOE_LDS_RING(BM, BN, BKT, ST, WM, WN) \
   { #BM "x" #BN "x" #BKT " s" #ST " w" #WM "x" #WN, launch_tiles<LdsRingTile<true, BM, BN, BKT, ST, WM, WN>>, \
     launch_tiles<LdsRingTile<false, BM, BN, BKT, ST, WM, WN>> }
-#define HMOE_STREAM(NAME, NWV, SKIP, NT) \
-  { NAME, launch_tiles<StreamTile<true, 128, NWV, 4, SKIP, NT>>, launch_tiles<StreamTile<false, 128, NWV, 4, SKIP, NT>> }
+#define HMOE_STREAM(NAME, NWV, NT) \
+  { NAME, launch_tiles<StreamTile<true, 128, NWV, 4, NT>>, launch_tiles<StreamTile<false, 128, NWV, 4, NT>> }
 #define HMOE_STREAM_FIT(NAME, NWV, NT) { NAME, launch_tiles_fit<true, NWV, NT>, launch_tiles_fit<false, NWV, NT> }
 #define HMOE_STREAM_K2(NAME, NT) \
-  { NAME, launch_tiles_k2<StreamTile<true, 128, 4, 4, false, NT, 4>>, launch_tiles_k2<StreamTile<false, 128, 4, 4, false, NT, 4>> }
-static const TiledVariant kVariants[] = {
-    HMOE_LDS_RING(256, 256, 64, 2, 2, 4),  // 0: 8 waves, 128x64 per wave
-    HMOE_LDS_RING(128, 256, 64, 3, 2, 4),  // 1: 8 waves, 64x64 per wave, 3 stages
-    HMOE_LDS_RING(256, 256, 32, 4, 2, 4),  // 2: as 0 with 4 stages of K 32
-    HMOE_LDS_RING(256, 128, 64, 3, 4, 2),  // 3: 8 waves, 64x64 per wave
-    HMOE_LDS_RING(128, 128, 64, 4, 2, 2),  // 4: 4 waves, 64x64 per wave, 4 stages
-    HMOE_LDS_RING(256, 256, 64, 2, 2, 2),  // 5: 4 waves, 128x128 per wave
-    HMOE_LDS_RING(256, 256, 64, 2, 4, 2),  // 6: 8 waves, 64x128 per wave
-    HMOE_LDS_RING(256, 256, 32, 5, 2, 4),  // 7: as 2 with 5 stages (all of LDS)
-    HMOE_LDS_RING(256, 256, 32, 4, 4, 2),  // 8: as 2, 64x128 per wave
-    HMOE_STREAM("stream 128x256 s4", 4, false, true),         // 9: weights bypass LDS, 4 waves
-    HMOE_STREAM("stream 128x512 s4", 8, false, true),         // 10: weights bypass LDS, 8 waves
-    HMOE_STREAM("stream 128x256 s4 skip", 4, true, true),     // 11: 9 + skip padded fragments
-    HMOE_STREAM("stream 128x512 s4 skip", 8, true, true),     // 12: 10 + skip padded fragments
-    HMOE_STREAM("stream 128x256 s4 plain", 4, false, false),  // 13: 9 with plain weight loads
-    HMOE_STREAM("stream 128x512 s4 plain", 8, false, false),  // 14: 10 with plain weight loads
-    HMOE_STREAM_K2("stream 128x256 s4 k2", true),             // 15: 9 with two wave groups that split K
-    HMOE_STREAM_K2("stream 128x256 s4 k2 plain", false),      // 16: 15 with plain weight loads
-    HMOE_STREAM_FIT("stream 128x512 s4 fit", 8, true),        // 17: 10 with the tile height fitted to the expert
-    HMOE_STREAM_FIT("stream 128x512 s4 fit plain", 8, false), // 18: 14 likewise
+  { NAME, launch_tiles_k2<StreamTile<true, 128, 4, 4, NT, 4>>, launch_tiles_k2<StreamTile<false, 128, 4, 4, NT, 4>> }
+enum {
+  V_LDS_RING = 0,       // 128x256x64 tiles through a 3-stage LDS ring, 8 waves of 64x64
+  V_STREAM4 = 1,        // weights bypass LDS, 128x256 tile, 4 waves
+  V_STREAM4_PLAIN = 2,  //   ... with plain instead of non-temporal weight loads
+  V_SPLIT_K = 3,        // V_STREAM4 with two wave groups that split K (needs an even number of K steps of 64)
+  V_SPLIT_K_PLAIN = 4,
+  V_FIT = 5,            // weights bypass LDS, 128x512 tile, 8 waves, tile height fitted to the expert
+  V_FIT_PLAIN = 6
 };
-constexpr int kFirstSplitK = 15, kLastSplitK = 16;  // these need an even number of K steps of 64
+static const TiledVariant kVariants[] = {
+    HMOE_LDS_RING(128, 256, 64, 3, 2, 4),
+    HMOE_STREAM("stream 128x256 s4", 4, true),
+    HMOE_STREAM("stream 128x256 s4 plain", 4, false),
+    HMOE_STREAM_K2("stream 128x256 s4 k2", true),
+    HMOE_STREAM_K2("stream 128x256 s4 k2 plain", false),
+    HMOE_STREAM_FIT("stream 128x512 s4 fit", 8, true),
+    HMOE_STREAM_FIT("stream 128x512 s4 fit plain", 8, false),
+};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 int launch_ffn_tiled(const FfnArgs& a) {
@@ -636,8 +626,8 @@ int launch_ffn_tiled(const FfnArgs& a) {
   bf16_t* o = (bf16_t*)a.o_perm;
   // Kernel choice (measured on the workload shapes; the tile counts are the launch's upper bounds).  The
   // weight-streaming family with 8 waves and a 128x512 tile (tile height fitted to each expert: 2-4 % over
-  // fixed 128 rows on every workload) wins whenever it yields two rounds of blocks per CU or more.  With fewer tiles the round-up to whole rounds costs more than the kernel gains:
-  // gate/up then takes the 128x256 LDS-ring tile (twice the blocks), and the down projection of few,
+  // fixed 128 rows on every workload) wins whenever it yields two rounds of blocks per CU or more.  With
+  // fewer tiles the round-up to whole rounds costs more than the kernel gains: gate/up then takes the 128x256 LDS-ring tile (twice the blocks), and the down projection of few,
   // large experts (small N) the 128x256 streaming tile with 4 waves.  A launch whose 128x256 tiles cover at
   // most half of the CUs (a shared expert at a moderate batch) takes that tile with two wave groups that
   // split K: per-tile time is all that matters there and the second group nearly halves it.
@@ -646,10 +636,13 @@ int launch_ffn_tiled(const FfnArgs& a) {
   const long tiles_down = m_tiles * ((d.hidden + 511) / 512);
   // Several m-tiles per expert (192 rows or more on average): the panel is shared through L2, plain loads.
   const bool shared_panels = a.n_rows / d.n_experts >= 192;
-  auto split_k_fits = [](int variant, int k) { return variant < kFirstSplitK || variant > kLastSplitK || (k / 64) % 2 == 0; };
-  const int v_split_k = shared_panels ? 16 : 15;
-  int v_gate_up = tiles_gate_up < 512 ? 1 : (shared_panels ? 18 : 17);
-  int v_down = tiles_down < 256 ? (shared_panels ? 13 : 9) : (shared_panels ? 18 : 17);
+  auto split_k_fits = [](int variant, int k) {
+    return (variant != V_SPLIT_K && variant != V_SPLIT_K_PLAIN) || (k / 64) % 2 == 0;
+  };
+  const int v_split_k = shared_panels ? V_SPLIT_K_PLAIN : V_SPLIT_K;
+  const int v_fit = shared_panels ? V_FIT_PLAIN : V_FIT;
+  int v_gate_up = tiles_gate_up < 512 ? V_LDS_RING : v_fit;
+  int v_down = tiles_down < 256 ? (shared_panels ? V_STREAM4_PLAIN : V_STREAM4) : v_fit;
   if (m_tiles * ((2 * d.ffn + 255) / 256) <= 128 && split_k_fits(v_split_k, d.hidden)) v_gate_up = v_split_k;
   if (m_tiles * ((d.hidden + 255) / 256) <= 128 && split_k_fits(v_split_k, d.ffn)) v_down = v_split_k;
   if (const char* env = getenv("HMOE_TILED_VARIANT")) {
