@@ -56,13 +56,21 @@ __global__ __launch_bounds__(PB_THREADS) void permute_scan_kernel(int32_t* __res
                                                                   int32_t* __restrict__ counts_out) {
   __shared__ int total[HMOE_MAX_EXPERTS];
   __shared__ int start[HMOE_MAX_EXPERTS];
+  // (the counts are read 16 blocks at a time: one after the other, a read could not start before the store in
+  // front of it, and 96 blocks of the largest workload cost 96 memory round trips)
+  constexpr int AHEAD = 16;
   const int e = threadIdx.x;
   if (e < n_experts) {
     int run = 0;
-    for (int b = 0; b < n_blocks; ++b) {
-      const int c = block_counts[(long)b * n_experts + e];
-      block_counts[(long)b * n_experts + e] = run;
-      run += c;
+    for (int b0 = 0; b0 < n_blocks; b0 += AHEAD) {
+      int c[AHEAD];
+#pragma unroll
+      for (int i = 0; i < AHEAD; ++i) c[i] = b0 + i < n_blocks ? block_counts[(long)(b0 + i) * n_experts + e] : 0;
+#pragma unroll
+      for (int i = 0; i < AHEAD; ++i) {
+        if (b0 + i < n_blocks) block_counts[(long)(b0 + i) * n_experts + e] = run;
+        run += c[i];
+      }
     }
     total[e] = run;
     if (counts_out) counts_out[e] = run;
@@ -76,7 +84,14 @@ __global__ __launch_bounds__(PB_THREADS) void permute_scan_kernel(int32_t* __res
   __syncthreads();
   if (e < n_experts) {
     const int s = start[e];
-    for (int b = 0; b < n_blocks; ++b) block_counts[(long)b * n_experts + e] += s;
+    for (int b0 = 0; b0 < n_blocks; b0 += AHEAD) {
+      int c[AHEAD];
+#pragma unroll
+      for (int i = 0; i < AHEAD; ++i) c[i] = b0 + i < n_blocks ? block_counts[(long)(b0 + i) * n_experts + e] : 0;
+#pragma unroll
+      for (int i = 0; i < AHEAD; ++i)
+        if (b0 + i < n_blocks) block_counts[(long)(b0 + i) * n_experts + e] = c[i] + s;
+    }
   }
 }
 
