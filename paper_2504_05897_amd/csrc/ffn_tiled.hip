@@ -209,7 +209,7 @@ struct LdsRingTile {
   }
 
   static __device__ __forceinline__ void epilogue(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
-                                                  const Acc& acc) {
+                                                  const Acc& acc, u32x4*) {
     const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
     const int n_out = GATEUP ? c.ffn : c.hidden;
     const int m0 = loc.mt * BM;
@@ -278,21 +278,33 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt_regs(u32x4& a, u32x4& b) {
   asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_regs(u32x4& a) {
+  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
+}
 
 // FMC (0: off): the tile multiplies only its first FMC 32-row fragments and consecutive m-tiles of an expert
 // start 32 * FMC rows apart (the activation copies still move BM rows).  The kernel picks FMC per expert so
 // that the expert's m-tiles are equally high (see ffn_tile_fit_kernel).
-template <bool GATEUP_, int BM_, int NWV, int SA, bool NT, int DB = 8, int FMC = 0>
+//
+// FN_ (2 or 1): 32-row weight groups per wave.  With one group a wave needs half the accumulators per row, which is
+// what lets a tile span 256 rows (an expert of up to 256 rows then reads its weights once, in one block, instead of
+// twice in two blocks that must keep pace to share them through L2); the gate and the up half of a SwiGLU pair then
+// sit in neighbouring waves and meet through LDS in the epilogue.  Tiles higher than 128 rows copy only the rows
+// they multiply (rounded up to what one copy instruction per thread moves).
+template <bool GATEUP_, int BM_, int NWV, int SA, bool NT, int DB = 8, int FMC = 0, int FN_ = 2>
 struct StreamTile {
   static constexpr bool GATEUP = GATEUP_;
   static constexpr int BM = BM_;
-  static constexpr int FN = 2, BN = NWV * 64, BKT = 64, KK = 4;
+  static constexpr int FN = FN_, BN = NWV * 32 * FN, BKT = 64, KK = 4;
   static constexpr int FM = FMC > 0 ? FMC : BM / 32;   // fragments multiplied
   static constexpr int MSTRIDE = 32 * FM;              // rows between the starts of consecutive m-tiles
-  static_assert(FM * 32 <= BM, "");
+  static_assert(FM * 32 <= BM && (FN == 1 || FN == 2), "");
   static_assert(DB % KK == 0, "the weight ring holds whole K steps");
   static constexpr int CPR = BKT / 8, RP = 256 / (BKT * 2);
-  static constexpr int A_CHUNKS = BM * CPR;
+  static constexpr int ROWS_PER_OP = 64 * NWV / CPR;   // rows one copy instruction of every thread moves
+  static constexpr int A_ROWS = BM > 128 ? (FM * 32 + ROWS_PER_OP - 1) / ROWS_PER_OP * ROWS_PER_OP : BM;
+  static constexpr int A_CHUNKS = A_ROWS * CPR;
   static constexpr int A_OPS = A_CHUNKS / (64 * NWV);
   static_assert(A_OPS >= 1 && A_OPS * 64 * NWV == A_CHUNKS, "activation tile must split evenly over the waves");
   static_assert(SA >= 3, "the activation ring needs three stages");
@@ -346,7 +358,14 @@ struct StreamTile {
     };
 
     u32x4 ring[DB][FN];
-    u32x4 fa[2][FM];
+    // Activation fragments: two sets with two weight groups per wave (the next substep's set is read while this one
+    // is multiplied); one set with one group, where a fragment feeds a single MFMA and is refilled right behind it.
+    constexpr int FA_SETS = FN == 1 ? 1 : 2;
+    u32x4 fa[FA_SETS][FM];
+    auto read_frag = [&](int stage, int kk, int i) {
+      const int r = i * 32 + col;
+      return lds[stage * A_CHUNKS + r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
+    };
     auto read_a = [&](int buf, int stage, int kk) {
       const u32x4* sa = lds + stage * A_CHUNKS;
 #pragma unroll
@@ -386,17 +405,26 @@ struct StreamTile {
               wait_vmcnt<N_A>();
               __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragments are in registers
               block_barrier();
-              read_a((kk + 1) & 1, next_stage, 0);
+              if constexpr (FN == 2) read_a((kk + 1) & 1, next_stage, 0);
             } else {
-              read_a((kk + 1) & 1, stage, kk + 1);
+              if constexpr (FN == 2) read_a((kk + 1) & 1, stage, kk + 1);
             }
             __builtin_amdgcn_sched_barrier(0);
             const int sl = h * KK + kk;  // ring slot of substep 4*tt + kk
-            wait_vmcnt_regs<N_B>(ring[sl][0], ring[sl][1]);
+            if constexpr (FN == 2) {
+              wait_vmcnt_regs<N_B>(ring[sl][0], ring[sl][1]);
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+              for (int i = 0; i < FM; ++i)
 #pragma unroll
-              for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
+                for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
+            } else {
+              wait_vmcnt_regs<N_B>(ring[sl][0]);
+#pragma unroll
+              for (int i = 0; i < FM; ++i) {
+                acc[i][0] = mfma_32x32x16_bf16(fa[0][i], ring[sl][0], acc[i][0]);
+                fa[0][i] = kk == KK - 1 ? read_frag(next_stage, 0, i) : read_frag(stage, kk + 1, i);
+              }
+            }
             __builtin_amdgcn_sched_barrier(0);
             const int s_next = tt * KK + kk + DB;
 #pragma unroll
@@ -419,8 +447,51 @@ struct StreamTile {
   }
 
   static __device__ __forceinline__ void epilogue(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
-                                                  const Acc& acc) {
-    epilogue_part(c, out, loc, acc, 0, FM);
+                                                  const Acc& acc, u32x4* lds) {
+    if constexpr (GATEUP && FN == 1) epilogue_pairs(c, out, loc, acc, lds);
+    else epilogue_part(c, out, loc, acc, 0, FM);
+  }
+  // Gate/up with one weight group per wave: wave 2p holds the gate half and wave 2p+1 the up half of pair p, for all
+  // rows.  The gate wave finishes the first HALF fragments and the up wave the others; each passes the partner the
+  // accumulators the partner finishes, through the (now idle) activation ring in LDS.
+  static constexpr int HALF = (FM + 1) / 2;
+  static __device__ __forceinline__ void epilogue_pairs(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
+                                                        const Acc& acc, u32x4* lds) {
+    static_assert(NWV % 2 == 0 && NWV * HALF * 1024 <= LDS_VEC * 4, "the exchange must fit the activation ring");
+    const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
+    const int n_out = c.ffn;
+    const int m0 = loc.mt * MSTRIDE;
+    const int tid = threadIdx.x % THREADS, wave = tid / 64, lane = tid % 64;
+    const int half = lane / 32, col = lane % 32;
+    const bool up_wave = wave & 1;
+    float* mine = (float*)lds + (size_t)wave * HALF * 1024;          // what this wave hands over
+    const float* theirs = (const float*)lds + (size_t)(wave ^ 1) * HALF * 1024;
+    block_barrier();  // every wave has read its last activation fragments
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      if ((i < HALF) == up_wave) {  // uniform per wave: a fragment the partner finishes
+        const int fi = i < HALF ? i : i - HALF;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mine[(fi * 16 + r) * 64 + lane] = acc[i][0][r];
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    block_barrier();
+    const int f = (nt * (BN / 64) + wave / 2) * 32 + col;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      if ((i < HALF) != up_wave) {
+        const int fi = i < HALF ? i : i - HALF;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float other = theirs[(fi * 16 + r) * 64 + lane];
+          const float g = up_wave ? other : acc[i][0][r];
+          const float u = up_wave ? acc[i][0][r] : other;
+          const int m = m0 + i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
+          if (m < m_rows && f < n_out) out[(size_t)(row_first + m) * n_out + f] = f32_to_bf16(silu_f32(g) * u);
+        }
+      }
+    }
   }
   // stores the 32-row fragments i_first <= i < i_last of the tile
   static __device__ __forceinline__ void epilogue_part(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
@@ -472,7 +543,7 @@ __device__ __forceinline__ void run_tile(const TiledCtx& c, const bf16_t* __rest
   typename TILE::Acc acc;
   zero_acc<TILE>(acc);
   TILE::mainloop(c, in, loc, 0, (TILE::GATEUP ? c.hidden : c.ffn) / TILE::BKT, lds, acc);
-  TILE::epilogue(c, out, loc, acc);
+  TILE::epilogue(c, out, loc, acc, lds);
 }
 
 // One block per tile, the whole K range.
@@ -512,6 +583,31 @@ static void launch_tiles_fit(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* o
   c.n_tiles_n = (n_total + NWV * 64 - 1) / (NWV * 64);
   c.grid_padded = (int)((tiles_upper_bound(c, n_rows, 128) + 7) / 8 * 8);
   hipLaunchKernelGGL((ffn_tile_fit_kernel<GATEUP, NWV, NT>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in, out);
+}
+
+// The same with tiles of up to 256 rows and one weight group per wave (tile width 32 * NWV columns): an expert of
+// 129..256 rows takes one m-tile instead of two.  Heights come in steps of two fragments.
+template <bool GATEUP, int NWV, bool NT>
+__global__ __launch_bounds__(64 * NWV) void ffn_tile_fit256_kernel(TiledCtx c, const bf16_t* __restrict__ in,
+                                                                    bf16_t* __restrict__ out) {
+  typedef StreamTile<GATEUP, 256, NWV, 4, NT, 8, 8, 1> FULL;
+  __shared__ u32x4 lds[FULL::LDS_VEC];
+  TileLoc loc;
+  if (!locate_tile<256>(c, loc)) return;  // uniform over the block
+  const int tiles = (loc.m_rows + 255) / 256;
+  const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;  // per m-tile, 1..8; uniform
+  if (fragments > 6) run_tile<FULL>(c, in, out, loc, lds);
+  else if (fragments > 4) run_tile<StreamTile<GATEUP, 256, NWV, 4, NT, 8, 6, 1>>(c, in, out, loc, lds);
+  else if (fragments > 2) run_tile<StreamTile<GATEUP, 256, NWV, 4, NT, 8, 4, 1>>(c, in, out, loc, lds);
+  else run_tile<StreamTile<GATEUP, 256, NWV, 4, NT, 8, 2, 1>>(c, in, out, loc, lds);
+}
+
+template <bool GATEUP, int NWV, bool NT>
+static void launch_tiles_fit256(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
+  const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
+  c.n_tiles_n = (n_total + NWV * 32 - 1) / (NWV * 32);
+  c.grid_padded = (int)((tiles_upper_bound(c, n_rows, 256) + 7) / 8 * 8);
+  hipLaunchKernelGGL((ffn_tile_fit256_kernel<GATEUP, NWV, NT>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in, out);
 }
 
 // One block per tile, two groups of TILE::THREADS threads: each group runs the tile's main loop over one
@@ -594,6 +690,8 @@ struct TiledVariant {
 #define HMOE_STREAM(NAME, NWV, NT) \
   { NAME, launch_tiles<StreamTile<true, 128, NWV, 4, NT>>, launch_tiles<StreamTile<false, 128, NWV, 4, NT>> }
 #define HMOE_STREAM_FIT(NAME, NWV, NT) { NAME, launch_tiles_fit<true, NWV, NT>, launch_tiles_fit<false, NWV, NT> }
+#define HMOE_STREAM_FIT256(NAME, NWV_GU, NWV_D, NT) \
+  { NAME, launch_tiles_fit256<true, NWV_GU, NT>, launch_tiles_fit256<false, NWV_D, NT> }
 #define HMOE_STREAM_K2(NAME, NT) \
   { NAME, launch_tiles_k2<StreamTile<true, 128, 4, 4, NT, 4>>, launch_tiles_k2<StreamTile<false, 128, 4, 4, NT, 4>> }
 enum {
@@ -603,7 +701,9 @@ enum {
   V_SPLIT_K = 3,        // V_STREAM4 with two wave groups that split K (needs an even number of K steps of 64)
   V_SPLIT_K_PLAIN = 4,
   V_FIT = 5,            // weights bypass LDS, 128x512 tile, 8 waves, tile height fitted to the expert
-  V_FIT_PLAIN = 6
+  V_FIT_PLAIN = 6,
+  V_FIT256 = 7,         // tiles of up to 256 rows, one weight group per wave: 256x256 (gate/up, 8 waves), 256x128 (down, 4 waves)
+  V_FIT256_PLAIN = 8
 };
 static const TiledVariant kVariants[] = {
     HMOE_LDS_RING(128, 256, 64, 3, 2, 4),
@@ -613,6 +713,8 @@ static const TiledVariant kVariants[] = {
     HMOE_STREAM_K2("stream 128x256 s4 k2 plain", false),
     HMOE_STREAM_FIT("stream 128x512 s4 fit", 8, true),
     HMOE_STREAM_FIT("stream 128x512 s4 fit plain", 8, false),
+    HMOE_STREAM_FIT256("stream 256x256/128 fit", 8, 4, true),
+    HMOE_STREAM_FIT256("stream 256x256/128 fit plain", 8, 4, false),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -624,27 +726,35 @@ int launch_ffn_tiled(const FfnArgs& a) {
   const bf16_t* x = (const bf16_t*)a.x_perm;
   bf16_t* h = (bf16_t*)a.h;
   bf16_t* o = (bf16_t*)a.o_perm;
-  // Kernel choice (measured on the workload shapes; the tile counts are the launch's upper bounds).  The
-  // weight-streaming family with 8 waves and a 128x512 tile (tile height fitted to each expert: 2-4 % over
-  // fixed 128 rows on every workload) wins whenever it yields two rounds of blocks per CU or more.  With
-  // fewer tiles the round-up to whole rounds costs more than the kernel gains: gate/up then takes the 128x256 LDS-ring tile (twice the blocks), and the down projection of few,
-  // large experts (small N) the 128x256 streaming tile with 4 waves.  A launch whose 128x256 tiles cover at
-  // most half of the CUs (a shared expert at a moderate batch) takes that tile with two wave groups that
-  // split K: per-tile time is all that matters there and the second group nearly halves it.
+  // Kernel choice (measured on the workload shapes and on batch-size sweeps of them; the tile counts are the
+  // launch's upper bounds).  The weight-streaming family with 8 waves and a 128x512 tile (tile height fitted to
+  // each expert: 2-4 % over fixed 128 rows on every workload) is the default.  The exceptions are launches with
+  // too few tiles to fill the CUs, where the time of one tile is what counts:
+  //  * experts of fewer than 192 rows on average: tiles of up to 256 rows and 32 columns per wave, their height
+  //    fitted to the expert in steps of 64 rows -- each wave multiplies as little as the expert needs, and an
+  //    expert of up to 256 rows streams its weights once;
+  //  * experts of 192 rows or more (a shared expert at a prefill batch, few large routed experts): the 128x256
+  //    tiles, through the LDS ring for gate/up and with weights streamed by 4 waves for the down projection, or,
+  //    when those tiles cover at most half of the CUs, with two wave groups per tile that split K.
   const long m_tiles = (long)a.n_rows / 128 + std::min(d.n_experts, a.n_rows);
   const long tiles_gate_up = m_tiles * ((2 * d.ffn + 511) / 512);
   const long tiles_down = m_tiles * ((d.hidden + 511) / 512);
+  const bool few_gate_up = m_tiles * ((2 * d.ffn + 255) / 256) <= 128, few_down = m_tiles * ((d.hidden + 255) / 256) <= 128;
   // Several m-tiles per expert (192 rows or more on average): the panel is shared through L2, plain loads.
   const bool shared_panels = a.n_rows / d.n_experts >= 192;
   auto split_k_fits = [](int variant, int k) {
     return (variant != V_SPLIT_K && variant != V_SPLIT_K_PLAIN) || (k / 64) % 2 == 0;
   };
-  const int v_split_k = shared_panels ? V_SPLIT_K_PLAIN : V_SPLIT_K;
-  const int v_fit = shared_panels ? V_FIT_PLAIN : V_FIT;
-  int v_gate_up = tiles_gate_up < 512 ? V_LDS_RING : v_fit;
-  int v_down = tiles_down < 256 ? (shared_panels ? V_STREAM4_PLAIN : V_STREAM4) : v_fit;
-  if (m_tiles * ((2 * d.ffn + 255) / 256) <= 128 && split_k_fits(v_split_k, d.hidden)) v_gate_up = v_split_k;
-  if (m_tiles * ((d.hidden + 255) / 256) <= 128 && split_k_fits(v_split_k, d.ffn)) v_down = v_split_k;
+  int v_gate_up = shared_panels ? V_FIT_PLAIN : V_FIT, v_down = v_gate_up;
+  if (shared_panels) {
+    if (tiles_gate_up < 512) v_gate_up = V_LDS_RING;
+    if (tiles_down < 256) v_down = V_STREAM4_PLAIN;
+    if (few_gate_up && split_k_fits(V_SPLIT_K_PLAIN, d.hidden)) v_gate_up = V_SPLIT_K_PLAIN;
+    if (few_down && split_k_fits(V_SPLIT_K_PLAIN, d.ffn)) v_down = V_SPLIT_K_PLAIN;
+  } else {
+    if (few_gate_up) v_gate_up = V_FIT256;
+    if (tiles_down < 256) v_down = V_FIT256;
+  }
   if (const char* env = getenv("HMOE_TILED_VARIANT")) {
     // "<index>" for both projections or "<gate/up index>,<down index>"
     const int want_gate_up = atoi(env);

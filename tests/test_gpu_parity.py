@@ -203,20 +203,22 @@ def test_ffn_bf16_paths(hm, path, hidden, ffn, counts):
     assert np.abs(ref).max() > 1e-2
 
 
-@pytest.mark.parametrize("variant", range(7))
+@pytest.mark.parametrize("variant", range(9))
 def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
     """The library's tuning override selects each built-in prefill kernel in turn (0 LDS-ring tiles, 1-2 weight-
     streaming tiles with 4 waves, 3-4 the same with two wave groups that split K, 5-6 weight-streaming tiles with
-    8 waves whose height is fitted to the expert); ragged groups spanning several m-tiles, partial n-tiles for
+    8 waves whose height is fitted to the expert, 7-8 tiles of up to 256 rows with one 32-row weight group per wave,
+    whose gate and up halves meet through LDS); ragged groups spanning several m-tiles, partial n-tiles for
     every tile width.  The split-K tiles apply to a projection whose K is an even number of 64-wide steps (the
     other projection then runs the default kernel): the shapes give them 1, 2, 3 and 4 steps per wave group in
-    both projections.  The fitted tiles get m-tiles of 1, 2, 3 and 4 fragments, alone and several per expert."""
+    both projections.  The fitted tiles get m-tiles of every height they come in (1-4 fragments of 32 rows; 2, 4, 6
+    and 8 for the 256-row tiles), alone and several per expert."""
     say("ffn prefill variant", variant)
     monkeypatch.setenv("HMOE_TILED_VARIANT", str(variant))
     shape = wl.small_shape(dtype=wl.BF16, hidden=256, ffn=320, n_experts=8, top_k=2)
     got, ref = _ffn_case(hm, shape, [33, 1, 0, 0, 300, 5, 64, 129], 3, seed=variant)
     assert max_rel_err(got, ref) < TOL[wl.BF16]
-    if variant in (5, 6):
+    if variant >= 5:
         shape = wl.small_shape(dtype=wl.BF16, hidden=192, ffn=320, n_experts=8, top_k=2)
         got, ref = _ffn_case(hm, shape, [257, 97, 96, 260, 1, 31, 32, 400], 3, seed=variant)
         assert max_rel_err(got, ref) < TOL[wl.BF16]
