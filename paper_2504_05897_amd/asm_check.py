@@ -13,6 +13,12 @@ queued, any instruction that writes one of its destination registers, or that re
 store data, or as the source of a vector ALU instruction, e.g. a copy into another register file), is
 reported.  Reads by the matrix instructions are not checked: the sources tie those to the waits, and the
 compiler places some of them out of line, which a linear scan cannot follow.
+
+Control flow is followed only as far as this: a label that execution cannot fall into (the instruction before
+it is an unconditional branch or ends the program) starts from the queue of the branches seen so far that jump
+to it (the longest of them), or from an empty queue if none was seen -- the compiler lays the alternative code
+paths of a kernel one after the other, and the text after a loop's closing branch is then another path's start,
+not the loop's exit.
 """
 from __future__ import annotations
 
@@ -35,6 +41,8 @@ def _scan_kernel(name: str, lines: Iterable[Tuple[int, str]]) -> List[str]:
     queue: List[Tuple[Set[int], int]] = []   # (destination registers of a hand-issued load or empty, line)
     found: List[str] = []
     in_asm = False
+    jumps = {}            # label -> queues at the branches to it seen so far
+    no_fall_through = False
     for no, raw in lines:
         text = raw.strip()
         if text.startswith(";;#ASMSTART"):
@@ -44,9 +52,22 @@ def _scan_kernel(name: str, lines: Iterable[Tuple[int, str]]) -> List[str]:
             in_asm = False
             continue
         text = text.split(";")[0].strip()
-        if not text or text.startswith(".") or text.endswith(":"):
+        if text.endswith(":") and not text.startswith(".L") or not text:
+            continue
+        if text.endswith(":"):
+            if no_fall_through:
+                queue = list(max(jumps.get(text[:-1], [[]]), key=len))
+                no_fall_through = False
+            continue
+        if text.startswith("."):
             continue
         op, _, rest = text.partition(" ")
+        if op in ("s_branch", "s_endpgm", "s_setpc_b64") or op.startswith("s_cbranch"):
+            if op.startswith(("s_branch", "s_cbranch")):
+                jumps.setdefault(rest.strip(), []).append(list(queue))
+            no_fall_through = not op.startswith("s_cbranch")
+            continue
+        no_fall_through = False
         ops = [o.strip() for o in _SPLIT.split(rest) if o.strip()] if rest else []
         if op == "s_waitcnt":
             m = re.search(r"vmcnt\((\d+)\)", rest)

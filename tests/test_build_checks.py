@@ -51,6 +51,21 @@ def test_register_of_a_load_in_flight():
     assert len(check(lds)) == 2
 
 
+def test_labels_without_fall_through():
+    check = _load("asm_check").find_inflight_hazards
+    tail = "\tv_mov_b32_e32 v10, 0\n\ts_waitcnt vmcnt(0)\n"
+    # the text behind an unconditional branch is another path's start: the load above it is not in flight there
+    assert check(listing(HAND + "\ts_branch .LBB0_9\n.LBB0_3:\n" + tail + ".LBB0_9:\n\ts_waitcnt vmcnt(0)\n")) == []
+    # ... unless a branch seen earlier jumps to it with the load in flight
+    found = check(listing(HAND + "\ts_cbranch_scc1 .LBB0_3\n\ts_waitcnt vmcnt(0)\n\ts_branch .LBB0_9\n.LBB0_3:\n" + tail
+                          + ".LBB0_9:\n\ts_waitcnt vmcnt(0)\n"))
+    assert len(found) == 1 and "v_mov_b32_e32 writes v[10]" in found[0]
+    # a label that execution falls into keeps the queue
+    assert len(check(listing(HAND + ".LBB0_3:\n" + tail))) == 1
+    # behind a conditional branch execution falls through
+    assert len(check(listing(HAND + "\ts_cbranch_scc1 .LBB0_9\n" + tail + ".LBB0_9:\n\ts_waitcnt vmcnt(0)\n"))) == 1
+
+
 def test_private_memory_remarks():
     build = _load("build")
     remarks = ("a.hip:5:0: remark: Function Name: _Z1av [-Rpass-analysis=kernel-resource-usage]\n"
