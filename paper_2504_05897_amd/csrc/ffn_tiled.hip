@@ -563,18 +563,19 @@ __global__ __launch_bounds__(TILE::THREADS) void ffn_tile_kernel(TiledCtx c, con
 // side by side and share the panel through L2, which uneven tiles would break -- and the padding rows that are
 // multiplied drop from up to 127 to at most 31 per m-tile.
 template <bool GATEUP, int NWV, bool NT>
-__global__ __launch_bounds__(64 * NWV) void ffn_tile_fit_kernel(TiledCtx c, const bf16_t* __restrict__ in,
+__global__ __launch_bounds__(64 * NWV, 2) void ffn_tile_fit_kernel(TiledCtx c, const bf16_t* __restrict__ in,
                                                                  bf16_t* __restrict__ out) {
-  typedef StreamTile<GATEUP, 128, NWV, 4, NT, 8, 4> FULL;
+  constexpr int RING = NWV == 4 ? 4 : 8;  // two 4-wave blocks per CU: half the ring each
+  typedef StreamTile<GATEUP, 128, NWV, 4, NT, RING, 4> FULL;
   __shared__ u32x4 lds[FULL::LDS_VEC];
   TileLoc loc;
   if (!locate_tile<128>(c, loc)) return;  // uniform over the block
   const int tiles = (loc.m_rows + 127) / 128;
   const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;  // per m-tile, 1..4; uniform
   if (fragments == 4) run_tile<FULL>(c, in, out, loc, lds);
-  else if (fragments == 3) run_tile<StreamTile<GATEUP, 128, NWV, 4, NT, 8, 3>>(c, in, out, loc, lds);
-  else if (fragments == 2) run_tile<StreamTile<GATEUP, 128, NWV, 4, NT, 8, 2>>(c, in, out, loc, lds);
-  else run_tile<StreamTile<GATEUP, 128, NWV, 4, NT, 8, 1>>(c, in, out, loc, lds);
+  else if (fragments == 3) run_tile<StreamTile<GATEUP, 128, NWV, 4, NT, RING, 3>>(c, in, out, loc, lds);
+  else if (fragments == 2) run_tile<StreamTile<GATEUP, 128, NWV, 4, NT, RING, 2>>(c, in, out, loc, lds);
+  else run_tile<StreamTile<GATEUP, 128, NWV, 4, NT, RING, 1>>(c, in, out, loc, lds);
 }
 
 template <bool GATEUP, int NWV, bool NT>
@@ -703,7 +704,9 @@ enum {
   V_FIT = 5,            // weights bypass LDS, 128x512 tile, 8 waves, tile height fitted to the expert
   V_FIT_PLAIN = 6,
   V_FIT256 = 7,         // tiles of up to 256 rows, one weight group per wave: 256x256 (gate/up, 8 waves), 256x128 (down, 4 waves)
-  V_FIT256_PLAIN = 8
+  V_FIT256_PLAIN = 8,
+  V_FIT4 = 9,           // V_FIT with 128x256 tiles, 4 waves and half the weight ring: two blocks per CU
+  V_FIT4_PLAIN = 10
 };
 static const TiledVariant kVariants[] = {
     HMOE_LDS_RING(128, 256, 64, 3, 2, 4),
@@ -715,6 +718,8 @@ static const TiledVariant kVariants[] = {
     HMOE_STREAM_FIT("stream 128x512 s4 fit plain", 8, false),
     HMOE_STREAM_FIT256("stream 256x256/128 fit", 8, 4, true),
     HMOE_STREAM_FIT256("stream 256x256/128 fit plain", 8, 4, false),
+    HMOE_STREAM_FIT("stream 128x256 s4 fit4", 4, true),
+    HMOE_STREAM_FIT("stream 128x256 s4 fit4 plain", 4, false),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -745,12 +750,10 @@ int launch_ffn_tiled(const FfnArgs& a) {
   auto split_k_fits = [](int variant, int k) {
     return (variant != V_SPLIT_K && variant != V_SPLIT_K_PLAIN) || (k / 64) % 2 == 0;
   };
-  int v_gate_up = shared_panels ? V_FIT_PLAIN : V_FIT, v_down = v_gate_up;
+  int v_gate_up = V_FIT, v_down = V_FIT;
   if (shared_panels) {
-    if (tiles_gate_up < 512) v_gate_up = V_LDS_RING;
-    if (tiles_down < 256) v_down = V_STREAM4_PLAIN;
-    if (few_gate_up && split_k_fits(V_SPLIT_K_PLAIN, d.hidden)) v_gate_up = V_SPLIT_K_PLAIN;
-    if (few_down && split_k_fits(V_SPLIT_K_PLAIN, d.ffn)) v_down = V_SPLIT_K_PLAIN;
+    v_gate_up = V_FIT4_PLAIN;
+    v_down = tiles_down < 256 || d.ffn >= 4096 ? V_FIT4_PLAIN : V_FIT_PLAIN;
   } else {
     if (few_gate_up) v_gate_up = V_FIT256;
     if (tiles_down < 256) v_down = V_FIT256;

@@ -203,7 +203,7 @@ def test_ffn_bf16_paths(hm, path, hidden, ffn, counts):
     assert np.abs(ref).max() > 1e-2
 
 
-@pytest.mark.parametrize("variant", range(9))
+@pytest.mark.parametrize("variant", range(11))
 def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
     """The library's tuning override selects each built-in prefill kernel in turn (0 LDS-ring tiles, 1-2 weight-
     streaming tiles with 4 waves, 3-4 the same with two wave groups that split K, 5-6 weight-streaming tiles with
