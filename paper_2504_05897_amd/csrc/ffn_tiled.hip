@@ -1,4 +1,4 @@
-// Prefill FFN (HMOE_FFN_TILED): grouped GEMM on bf16 MFMA with LDS-staged tiles.
+// Prefill FFN (HMOE_FFN_TILED): grouped GEMM on bf16 MFMA, weights streamed past LDS.
 //
 // Two launches per call:  h = silu(X Wgate^T) * (X Wup^T)   and   O = h Wdown^T,
 // each a grouped GEMM  C[rows of expert e, N] = A[rows, K] * W_e[N, K]^T  over the ragged row
@@ -6,21 +6,21 @@
 // expert-id -> slot table.  All dispatch happens on the device: a block turns its index into
 // (expert, m-tile, n-tile) by walking expert_offsets, so the host never reads the routing result.
 //
-// Block tile BM x BN, K step BKT, WM x WN waves, each wave owns (BM/WM) x (BN/WN) of the tile as
-// 32x32x16 bf16 MFMA fragments with fp32 accumulators.
-//   * Tiles travel global -> LDS without passing through registers (global_load_lds_dwordx4: every
-//     lane supplies a global address, the wave's 64 x 16 bytes land contiguously in LDS), into a
-//     ring of STAGES buffers.  A wave waits (s_waitcnt vmcnt) only for the loads of the K step it is
-//     about to consume, so STAGES-1 steps of loads stay in flight per block; one barrier per step.
+// A block owns a tile of up to BM rows and 32 * FN * waves columns; every wave spans all rows and owns
+// FN 32-row weight groups, as 32x32x16 bf16 MFMA fragments with fp32 accumulators.
 //   * Weights arrive pre-tiled (packed slot layout): a 32-row x 16-k tile is 1 KiB in MFMA operand
-//     order, so it is copied verbatim and read back with one conflict-free 16-byte read per lane.
-//   * Activation rows are row-major; the lane that fills LDS chunk (row, slot) fetches global chunk
-//     slot ^ f(row), an XOR swizzle that spreads the fragment reads over all banks.
+//     order.  Each wave streams the tiles of its groups straight from global memory into a ring of
+//     registers, DB k-substeps ahead; they never touch LDS.
+//   * Activation tiles travel global -> LDS without passing through registers (global_load_lds_dwordx4:
+//     every lane supplies a global address, the wave's 64 x 16 bytes land contiguously in LDS), into a
+//     ring of SA stages; one barrier per K step of 64.  Rows are row-major; the lane that fills LDS chunk
+//     (row, slot) fetches global chunk slot ^ f(row), an XOR swizzle that spreads the fragment reads over
+//     all banks.
 //   * Rows past the end of an expert and weight groups past N are loaded from a clamped (valid)
 //     address instead of being zero-filled; their products land in accumulators that are never
 //     stored.
-//   * Gate and up rows are interleaved in 32-row groups, so a wave's even fragments are gate and
-//     its odd fragments the matching up columns: SwiGLU is applied to registers.
+//   * Gate and up rows are interleaved in 32-row groups, so with FN = 2 a wave's even fragments are gate
+//     and its odd fragments the matching up columns: SwiGLU is applied to registers.
 //   * Tiles are numbered expert-major, then n-tile, then m-tile, and block ids are dealt to the
 //     8 XCDs in contiguous ranges so that blocks sharing a weight panel share an L2.
 #include <stdlib.h>
@@ -53,205 +53,15 @@ __device__ __forceinline__ void block_barrier() {
   asm volatile("" ::: "memory");
 }
 
-template <bool GATEUP_, int BM_, int BN_, int BKT_, int STAGES, int WM, int WN>
-struct LdsRingTile {
-  static constexpr bool GATEUP = GATEUP_;
-  static constexpr int BM = BM_, BN = BN_, BKT = BKT_;
-  static constexpr int NWAVES = WM * WN;
-  static constexpr int WTM = BM / WM, WTN = BN / WN;
-  static constexpr int FM = WTM / 32, FN = WTN / 32;
-  static constexpr int CPR = BKT / 8;              // 16-byte chunks per activation row per step
-  static constexpr int RP = 256 / (BKT * 2);       // rows per 256 bytes of LDS
-  static constexpr int KK = BKT / TILE_K;          // MFMA k-substeps per step
-  static constexpr int A_CHUNKS = BM * CPR;        // per stage
-  static constexpr int B_CHUNKS = BN * CPR;
-  static constexpr int A_OPS = A_CHUNKS / (64 * NWAVES);  // wave-wide copies per wave per step
-  static constexpr int B_OPS = B_CHUNKS / (64 * NWAVES);
-  static constexpr int LPS = A_OPS + B_OPS;        // loads per lane per step
-  static_assert(A_OPS >= 1 && B_OPS >= 1 && A_OPS * 64 * NWAVES == A_CHUNKS && B_OPS * 64 * NWAVES == B_CHUNKS, "");
-  static_assert(FM >= 1 && FN >= 1 && (!GATEUP || FN % 2 == 0), "a wave needs gate/up fragment pairs");
-  static_assert(STAGES >= 2 && (STAGES - 2) * LPS <= 63, "vmcnt range");
-  static constexpr int THREADS = 64 * NWAVES;
-  static constexpr int LDS_VEC = STAGES * (A_CHUNKS + B_CHUNKS);  // 16-byte units
-  typedef f32x16_t Acc[FM][FN];
-
-  // acc += A[rows of the tile, k range] * W[columns of the tile, k range]^T for the k_steps steps of BKT
-  // that start at step k_begin.  On return every copy into LDS has landed.
-  static __device__ __forceinline__ void mainloop(const TiledCtx& c, const bf16_t* __restrict__ in, const TileLoc& loc,
-                                                  int k_begin, int k_steps, u32x4* lds, Acc& acc) {
-    const int e = loc.e, row_first = loc.row_first, m_rows = loc.m_rows, mt = loc.mt, nt = loc.nt;
-    const int K = GATEUP ? c.hidden : c.ffn;
-    const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;  // packed 32-row groups of W
-    const int kt16 = K / TILE_K;
-    const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
-    const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
-    const int group0 = nt * (BN / TILE_N);
-    const int m0 = mt * BM;  // first row of the tile within the expert
-
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
-    const int wm = wave / WN, wn = wave % WN;
-    const int half = lane / 32, col = lane % 32;
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;  // LDS byte address of the ring
-
-    // ---- per-lane source addresses of the copies this wave issues every step ------------------
-    const u32x4* a_src[A_OPS];
-#pragma unroll
-    for (int i = 0; i < A_OPS; ++i) {
-      const int ci = (i * NWAVES + wave) * 64 + lane;      // LDS chunk this lane fills
-      const int r = ci / CPR, s = ci % CPR;
-      const int chunk = s ^ ((r / RP) % CPR);
-      const int row = m0 + r < m_rows ? m0 + r : m_rows - 1;  // clamp: never stored
-      const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row_first + row) : row_first + row;
-      a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk + (size_t)k_begin * CPR;
-    }
-    const u32x4* b_src[B_OPS];
-#pragma unroll
-    for (int i = 0; i < B_OPS; ++i) {
-      const int ci = (i * NWAVES + wave) * 64 + lane;
-      const int g = ci / (KK * 64), within = ci % (KK * 64);  // KK tiles of one group per step
-      const int grp = group0 + g < n_groups ? group0 + g : 0;
-      b_src[i] = w + ((size_t)grp * kt16) * 64 + within + (size_t)k_begin * (KK * 64);
-    }
-    // The LPS copies of one K step are issued in KK pieces, one piece in front of each MFMA group, so
-    // that the vector-memory queue never holds more than a couple of copies per wave.
-    auto issue_piece = [&](int stage, int kstep, int piece) {
-      const uint32_t base = lds0 + (uint32_t)stage * (A_CHUNKS + B_CHUNKS) * 16;
-#pragma unroll
-      for (int op = 0; op < LPS; ++op) {
-        if (op < piece * LPS / KK || op >= (piece + 1) * LPS / KK) continue;
-        if (op < A_OPS) {
-          load_to_lds_16(a_src[op] + (size_t)kstep * CPR, base + (uint32_t)((op * NWAVES + wave) * 64) * 16);
-        } else {
-          const int i = op - A_OPS;
-          load_to_lds_16(b_src[i] + (size_t)kstep * (KK * 64),
-                         base + (uint32_t)(A_CHUNKS + (i * NWAVES + wave) * 64) * 16);
-        }
-      }
-    };
-    auto issue = [&](int stage, int kstep) {
-#pragma unroll
-      for (int p = 0; p < KK; ++p) issue_piece(stage, kstep, p);
-    };
-
-    static_assert(KK % 2 == 0, "fragment double buffering assumes an even number of k-substeps");
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-      if (s < k_steps) issue(s, s);
-
-    // Fragments are double buffered in registers: the LDS reads of substep kk+1 are issued before the
-    // MFMAs of substep kk, across K steps too (the barrier that opens step ks+1 sits before the last
-    // MFMA group of step ks).
-    // A wave whose rows all lie past the end of the expert (ragged last m-tile) neither reads
-    // fragments nor multiplies; it still takes part in the copies and barriers.
-    const bool live = m_rows - m0 - wm * WTM > 0;
-    u32x4 fa[2][FM], fb[2][FN];
-    auto read_frags = [&](int buf, int stage, int kk) {
-      const u32x4* sa = lds + stage * (A_CHUNKS + B_CHUNKS);
-      const u32x4* sb = sa + A_CHUNKS;
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const int r = wm * WTM + i * 32 + col;
-        if (live) fa[buf][i] = sa[r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
-      }
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-        if (live) fb[buf][j] = sb[((wn * FN + j) * KK + kk) * 64 + lane];
-    };
-    auto mfma_frags = [&](int buf) {
-      if (!live) return;
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j]);
-    };
-
-    // open step 0: its loads have landed once only the younger STAGES-2 groups are outstanding
-    if (STAGES - 1 <= k_steps) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
-    block_barrier();
-    if (STAGES - 1 < k_steps) issue(STAGES - 1, STAGES - 1);   // the last ring slot is still untouched
-    read_frags(0, 0, 0);
-
-    int stage = 0;
-    bool pending = false;   // a K step's copies are partly issued
-    int pend_stage = 0, pend_step = 0;
-    for (int ks = 0; ks < k_steps; ++ks) {
-#pragma unroll
-      for (int kk = 0; kk < KK - 1; ++kk) {
-        if (STAGES >= 3 && pending) issue_piece(pend_stage, pend_step, kk + 1);
-        read_frags((kk + 1) & 1, stage, kk + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_frags(kk & 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      const int next_stage = stage + 1 == STAGES ? 0 : stage + 1;
-      pending = false;
-      if (ks + 1 < k_steps) {
-        // open step ks+1.  Every wave has finished reading this step's buffer (its last fragments are
-        // in registers), so after the barrier that buffer takes the loads of step ks+STAGES.
-        if (ks + STAGES <= k_steps) wait_vmcnt<(STAGES - 2) * LPS>(); else wait_vmcnt<0>();
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragment reads are in registers
-        block_barrier();
-        pending = ks + STAGES < k_steps;
-        pend_stage = stage;
-        pend_step = ks + STAGES;
-        if (pending) {
-          if (STAGES >= 3) issue_piece(pend_stage, pend_step, 0);
-          else issue(pend_stage, pend_step);   // two stages: the data is needed one step from now
-        }
-        read_frags(0, next_stage, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      mfma_frags((KK - 1) & 1);
-      __builtin_amdgcn_sched_barrier(0);
-      stage = next_stage;
-    }
-
-  }
-
-  static __device__ __forceinline__ void epilogue(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
-                                                  const Acc& acc, u32x4*) {
-    const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
-    const int n_out = GATEUP ? c.ffn : c.hidden;
-    const int m0 = loc.mt * BM;
-    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-    const int wm = wave / WN, wn = wave % WN;
-    const int half = lane / 32, col = lane % 32;
-    // ---- epilogue -----------------------------------------------------------------------
-    // accumulator register r of lane (half, col): row 8*(r/4) + 4*half + r%4, column col
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * WTM + i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
-        if (m >= m_rows) continue;
-        bf16_t* orow = out + (size_t)(row_first + m) * n_out;
-        if (GATEUP) {
-#pragma unroll
-          for (int j = 0; j < FN; j += 2) {
-            const int f = nt * (BN / 2) + ((wn * FN + j) / 2) * 32 + col;
-            if (f < n_out) orow[f] = f32_to_bf16(silu_f32(acc[i][j][r]) * acc[i][j + 1][r]);
-          }
-        } else {
-#pragma unroll
-          for (int j = 0; j < FN; ++j) {
-            const int n = nt * BN + (wn * FN + j) * 32 + col;
-            if (n < n_out) orow[n] = f32_to_bf16(acc[i][j][r]);
-          }
-        }
-      }
-    }
-  }
-};
-
 // ---------------------------------------------------------------------------------------------
-// Second kernel family: the weights bypass LDS.
+// The tile.
 //
 // All NWV waves of a block span the whole BM rows; a wave owns 64 packed weight rows (one gate/up
-// pair, or 64 output columns of the down projection).  Activation tiles still go through the LDS ring
-// (every wave needs all of them); weight tiles are 1 KiB each in MFMA operand order, so each wave
+// pair, or 64 output columns of the down projection; 32 with FN = 1).  Activation tiles go through the
+// LDS ring (every wave needs all of them); weight tiles are 1 KiB each in MFMA operand order, so each wave
 // streams its own straight from global memory into a ring of DB register slots, DB k-substeps ahead.
-// Compared with the kernel above this removes the LDS fill and the LDS reads of the weight operand
-// (about 40 % of the LDS traffic of a 256x256 tile) and keeps DB KiB per matrix in flight per wave,
+// Compared with staging both operands in LDS this removes the LDS fill and the LDS reads of the weight
+// operand (about 40 % of the LDS traffic of a 256x256 tile) and keeps DB KiB per matrix in flight per wave,
 // which is what the weight-streaming shapes need.
 //
 // Every vector-memory operation is issued by hand in a fixed order per k-substep
@@ -327,7 +137,7 @@ struct StreamTile {
     const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
     const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
     const int m0 = mt * MSTRIDE;
-    const int tid = threadIdx.x % THREADS, wave = tid / 64, lane = tid % 64;  // a block may hold two groups of NWV waves
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
     const int half = lane / 32, col = lane % 32;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
 
@@ -461,7 +271,7 @@ struct StreamTile {
     const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
     const int n_out = c.ffn;
     const int m0 = loc.mt * MSTRIDE;
-    const int tid = threadIdx.x % THREADS, wave = tid / 64, lane = tid % 64;
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
     const int half = lane / 32, col = lane % 32;
     const bool up_wave = wave & 1;
     float* mine = (float*)lds + (size_t)wave * HALF * 1024;          // what this wave hands over
@@ -499,7 +309,7 @@ struct StreamTile {
     const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
     const int n_out = GATEUP ? c.ffn : c.hidden;
     const int m0 = loc.mt * MSTRIDE;
-    const int tid = threadIdx.x % THREADS, wave = tid / 64, lane = tid % 64;
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
     const int half = lane / 32, col = lane % 32;
     // ---- epilogue: accumulator register r of lane (half, col) is row 8*(r/4) + 4*half + r%4 ----
 #pragma unroll
@@ -527,7 +337,7 @@ struct StreamTile {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Kernels over a tile type (LdsRingTile or StreamTile).
+// Kernels over a tile type.
 
 template <class TILE>
 __device__ __forceinline__ void zero_acc(typename TILE::Acc& acc) {
@@ -544,16 +354,6 @@ __device__ __forceinline__ void run_tile(const TiledCtx& c, const bf16_t* __rest
   zero_acc<TILE>(acc);
   TILE::mainloop(c, in, loc, 0, (TILE::GATEUP ? c.hidden : c.ffn) / TILE::BKT, lds, acc);
   TILE::epilogue(c, out, loc, acc, lds);
-}
-
-// One block per tile, the whole K range.
-template <class TILE>
-__global__ __launch_bounds__(TILE::THREADS) void ffn_tile_kernel(TiledCtx c, const bf16_t* __restrict__ in,
-                                                                  bf16_t* __restrict__ out) {
-  __shared__ u32x4 lds[TILE::LDS_VEC];
-  TileLoc loc;
-  if (!locate_tile<TILE::BM>(c, loc)) return;  // uniform over the block
-  run_tile<TILE>(c, in, out, loc, lds);
 }
 
 // One block per tile, tile height fitted to the expert.  An expert of R rows has ceil(R / 128) m-tiles whatever
@@ -611,72 +411,6 @@ static void launch_tiles_fit256(TiledCtx c, int n_rows, const bf16_t* in, bf16_t
   hipLaunchKernelGGL((ffn_tile_fit256_kernel<GATEUP, NWV, NT>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in, out);
 }
 
-// One block per tile, two groups of TILE::THREADS threads: each group runs the tile's main loop over one
-// half of the K range with an activation ring of its own (the groups execute the same number of
-// barriers, so the block-wide barriers of the main loop line up), then the groups swap halves of their
-// accumulators through LDS and each finishes half of the tile's row fragments.  This doubles the waves
-// that stream weights per tile, for launches with fewer tiles than the chip has CUs.  The caller
-// guarantees an even number of K steps.
-template <class TILE>
-__global__ __launch_bounds__(2 * TILE::THREADS) void ffn_tile_k2_kernel(TiledCtx c, const bf16_t* __restrict__ in,
-                                                                         bf16_t* __restrict__ out) {
-  constexpr int HALF = TILE::FM / 2, QUADS = HALF * TILE::FN * 4, T = TILE::THREADS;
-  static_assert(TILE::FM % 2 == 0 && 2 * QUADS * T <= 2 * TILE::LDS_VEC, "the exchange reuses the activation rings");
-  __shared__ u32x4 lds[2 * TILE::LDS_VEC];
-  TileLoc loc;
-  if (!locate_tile<TILE::BM>(c, loc)) return;  // uniform over the block
-  const int group = __builtin_amdgcn_readfirstlane(threadIdx.x / T);
-  const int steps = (TILE::GATEUP ? c.hidden : c.ffn) / TILE::BKT / 2;
-  typename TILE::Acc acc;
-  zero_acc<TILE>(acc);
-  TILE::mainloop(c, in, loc, group * steps, steps, lds + group * TILE::LDS_VEC, acc);
-
-  // group g finishes row fragments [g * HALF, (g + 1) * HALF); the others go to the partner
-  f32x4_t* xch = (f32x4_t*)lds;
-  const int lt = threadIdx.x % T;
-  __syncthreads();  // every wave has read its last activation fragments
-#pragma unroll
-  for (int i = 0; i < TILE::FM; ++i) {
-    if (i / HALF == group) continue;
-#pragma unroll
-    for (int j = 0; j < TILE::FN; ++j)
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        xch[(group * QUADS + ((i % HALF) * TILE::FN + j) * 4 + q) * T + lt] =
-            f32x4_t{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-  }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < TILE::FM; ++i) {
-    if (i / HALF != group) continue;
-#pragma unroll
-    for (int j = 0; j < TILE::FN; ++j)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const f32x4_t v = xch[((1 - group) * QUADS + ((i % HALF) * TILE::FN + j) * 4 + q) * T + lt];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) acc[i][j][4 * q + u] += v[u];
-      }
-  }
-  TILE::epilogue_part(c, out, loc, acc, group * HALF, (group + 1) * HALF);
-}
-
-template <class TILE>
-static void launch_tiles(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
-  const int n_total = TILE::GATEUP ? 2 * c.ffn : c.hidden;
-  c.n_tiles_n = (n_total + TILE::BN - 1) / TILE::BN;
-  c.grid_padded = (int)((tiles_upper_bound(c, n_rows, TILE::BM) + 7) / 8 * 8);
-  hipLaunchKernelGGL((ffn_tile_kernel<TILE>), dim3((unsigned)c.grid_padded), dim3(TILE::THREADS), 0, s, c, in, out);
-}
-
-template <class TILE>
-static void launch_tiles_k2(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
-  const int n_total = TILE::GATEUP ? 2 * c.ffn : c.hidden;
-  c.n_tiles_n = (n_total + TILE::BN - 1) / TILE::BN;
-  c.grid_padded = (int)((tiles_upper_bound(c, n_rows, TILE::BM) + 7) / 8 * 8);
-  hipLaunchKernelGGL((ffn_tile_k2_kernel<TILE>), dim3((unsigned)c.grid_padded), dim3(2 * TILE::THREADS), 0, s, c, in, out);
-}
-
 // Tile shapes built into the library.  hmoe picks one from the average rows per expert; the
 // environment variable HMOE_TILED_VARIANT (an index into this table) overrides the choice for
 // tuning runs.
@@ -685,41 +419,24 @@ struct TiledVariant {
   const char* name;
   tiled_launch_fn gate_up, down;
 };
-#define HMOE_LDS_RING(BM, BN, BKT, ST, WM, WN) \
-  { #BM "x" #BN "x" #BKT " s" #ST " w" #WM "x" #WN, launch_tiles<LdsRingTile<true, BM, BN, BKT, ST, WM, WN>>, \
-    launch_tiles<LdsRingTile<false, BM, BN, BKT, ST, WM, WN>> }
-#define HMOE_STREAM(NAME, NWV, NT) \
-  { NAME, launch_tiles<StreamTile<true, 128, NWV, 4, NT>>, launch_tiles<StreamTile<false, 128, NWV, 4, NT>> }
 #define HMOE_STREAM_FIT(NAME, NWV, NT) { NAME, launch_tiles_fit<true, NWV, NT>, launch_tiles_fit<false, NWV, NT> }
 #define HMOE_STREAM_FIT256(NAME, NWV_GU, NWV_D, NT) \
   { NAME, launch_tiles_fit256<true, NWV_GU, NT>, launch_tiles_fit256<false, NWV_D, NT> }
-#define HMOE_STREAM_K2(NAME, NT) \
-  { NAME, launch_tiles_k2<StreamTile<true, 128, 4, 4, NT, 4>>, launch_tiles_k2<StreamTile<false, 128, 4, 4, NT, 4>> }
 enum {
-  V_LDS_RING = 0,       // 128x256x64 tiles through a 3-stage LDS ring, 8 waves of 64x64
-  V_STREAM4 = 1,        // weights bypass LDS, 128x256 tile, 4 waves
-  V_STREAM4_PLAIN = 2,  //   ... with plain instead of non-temporal weight loads
-  V_SPLIT_K = 3,        // V_STREAM4 with two wave groups that split K (needs an even number of K steps of 64)
-  V_SPLIT_K_PLAIN = 4,
-  V_FIT = 5,            // weights bypass LDS, 128x512 tile, 8 waves, tile height fitted to the expert
-  V_FIT_PLAIN = 6,
-  V_FIT256 = 7,         // tiles of up to 256 rows, one weight group per wave: 256x256 (gate/up, 8 waves), 256x128 (down, 4 waves)
-  V_FIT256_PLAIN = 8,
-  V_FIT4 = 9,           // V_FIT with 128x256 tiles, 4 waves and half the weight ring: two blocks per CU
-  V_FIT4_PLAIN = 10
+  V_FIT = 0,            // 128x512 tile, 8 waves, tile height fitted to the expert, non-temporal weight loads
+  V_FIT_PLAIN = 1,      //   ... with plain weight loads
+  V_FIT4 = 2,           // 128x256 tile, 4 waves, half the weight ring: two blocks per CU
+  V_FIT4_PLAIN = 3,
+  V_FIT256 = 4,         // tiles of up to 256 rows, one weight group per wave: 256x256 (gate/up, 8 waves), 256x128 (down, 4 waves)
+  V_FIT256_PLAIN = 5
 };
 static const TiledVariant kVariants[] = {
-    HMOE_LDS_RING(128, 256, 64, 3, 2, 4),
-    HMOE_STREAM("stream 128x256 s4", 4, true),
-    HMOE_STREAM("stream 128x256 s4 plain", 4, false),
-    HMOE_STREAM_K2("stream 128x256 s4 k2", true),
-    HMOE_STREAM_K2("stream 128x256 s4 k2 plain", false),
-    HMOE_STREAM_FIT("stream 128x512 s4 fit", 8, true),
-    HMOE_STREAM_FIT("stream 128x512 s4 fit plain", 8, false),
+    HMOE_STREAM_FIT("stream 128x512 fit", 8, true),
+    HMOE_STREAM_FIT("stream 128x512 fit plain", 8, false),
+    HMOE_STREAM_FIT("stream 128x256 fit, 4 waves", 4, true),
+    HMOE_STREAM_FIT("stream 128x256 fit, 4 waves, plain", 4, false),
     HMOE_STREAM_FIT256("stream 256x256/128 fit", 8, 4, true),
     HMOE_STREAM_FIT256("stream 256x256/128 fit plain", 8, 4, false),
-    HMOE_STREAM_FIT("stream 128x256 s4 fit4", 4, true),
-    HMOE_STREAM_FIT("stream 128x256 s4 fit4 plain", 4, false),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -732,24 +449,21 @@ int launch_ffn_tiled(const FfnArgs& a) {
   bf16_t* h = (bf16_t*)a.h;
   bf16_t* o = (bf16_t*)a.o_perm;
   // Kernel choice (measured on the workload shapes and on batch-size sweeps of them; the tile counts are the
-  // launch's upper bounds).  The weight-streaming family with 8 waves and a 128x512 tile (tile height fitted to
-  // each expert: 2-4 % over fixed 128 rows on every workload) is the default.  The exceptions are launches with
-  // too few tiles to fill the CUs, where the time of one tile is what counts:
-  //  * experts of fewer than 192 rows on average: tiles of up to 256 rows and 32 columns per wave, their height
-  //    fitted to the expert in steps of 64 rows -- each wave multiplies as little as the expert needs, and an
-  //    expert of up to 256 rows streams its weights once;
-  //  * experts of 192 rows or more (a shared expert at a prefill batch, few large routed experts): the 128x256
-  //    tiles, through the LDS ring for gate/up and with weights streamed by 4 waves for the down projection, or,
-  //    when those tiles cover at most half of the CUs, with two wave groups per tile that split K.
+  // launch's upper bounds).
+  //  * Experts of fewer than 192 rows on average stream each weight byte about once: 128x512 tiles with 8 waves,
+  //    the tile height fitted to the expert, non-temporal weight loads.  When such a launch has too few tiles to
+  //    fill the CUs, the time of one tile is what counts and it takes tiles of up to 256 rows and 32 columns per
+  //    wave: each wave multiplies as little as the expert needs, and an expert of up to 256 rows streams its
+  //    weights once.
+  //  * Experts of 192 rows or more (a shared expert at a prefill batch, large routed experts) have several
+  //    m-tiles that share their weight panel through L2: plain loads, and 128x256 tiles with 4 waves, two blocks
+  //    per CU, so that one block's ring fill and epilogue overlap the other's main loop (4-14 % over the 8-wave
+  //    tile on compute-bound launches).  The down projection keeps the 128x512 tile when its K range is short
+  //    and its tiles are plenty (F < 4096: the stress and Qwen2 shapes, 1-2 % either way).
   const long m_tiles = (long)a.n_rows / 128 + std::min(d.n_experts, a.n_rows);
-  const long tiles_gate_up = m_tiles * ((2 * d.ffn + 511) / 512);
   const long tiles_down = m_tiles * ((d.hidden + 511) / 512);
-  const bool few_gate_up = m_tiles * ((2 * d.ffn + 255) / 256) <= 128, few_down = m_tiles * ((d.hidden + 255) / 256) <= 128;
-  // Several m-tiles per expert (192 rows or more on average): the panel is shared through L2, plain loads.
+  const bool few_gate_up = m_tiles * ((2 * d.ffn + 255) / 256) <= 128;
   const bool shared_panels = a.n_rows / d.n_experts >= 192;
-  auto split_k_fits = [](int variant, int k) {
-    return (variant != V_SPLIT_K && variant != V_SPLIT_K_PLAIN) || (k / 64) % 2 == 0;
-  };
   int v_gate_up = V_FIT, v_down = V_FIT;
   if (shared_panels) {
     v_gate_up = V_FIT4_PLAIN;
@@ -763,8 +477,8 @@ int launch_ffn_tiled(const FfnArgs& a) {
     const int want_gate_up = atoi(env);
     const char* comma = strchr(env, ',');
     const int want_down = comma ? atoi(comma + 1) : want_gate_up;
-    if (want_gate_up >= 0 && want_gate_up < kNumVariants && split_k_fits(want_gate_up, d.hidden)) v_gate_up = want_gate_up;
-    if (want_down >= 0 && want_down < kNumVariants && split_k_fits(want_down, d.ffn)) v_down = want_down;
+    if (want_gate_up >= 0 && want_gate_up < kNumVariants) v_gate_up = want_gate_up;
+    if (want_down >= 0 && want_down < kNumVariants) v_down = want_down;
   }
   probe_before(a.stream);
   kVariants[v_gate_up].gate_up(c, a.n_rows, x, h, a.stream);

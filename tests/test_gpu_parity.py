@@ -203,31 +203,27 @@ def test_ffn_bf16_paths(hm, path, hidden, ffn, counts):
     assert np.abs(ref).max() > 1e-2
 
 
-@pytest.mark.parametrize("variant", range(11))
+@pytest.mark.parametrize("variant", range(6))
 def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
-    """The library's tuning override selects each built-in prefill kernel in turn (0 LDS-ring tiles, 1-2 weight-
-    streaming tiles with 4 waves, 3-4 the same with two wave groups that split K, 5-6 weight-streaming tiles with
-    8 waves whose height is fitted to the expert, 7-8 tiles of up to 256 rows with one 32-row weight group per wave,
-    whose gate and up halves meet through LDS); ragged groups spanning several m-tiles, partial n-tiles for
-    every tile width.  The split-K tiles apply to a projection whose K is an even number of 64-wide steps (the
-    other projection then runs the default kernel): the shapes give them 1, 2, 3 and 4 steps per wave group in
-    both projections.  The fitted tiles get m-tiles of every height they come in (1-4 fragments of 32 rows; 2, 4, 6
-    and 8 for the 256-row tiles), alone and several per expert."""
+    """The library's tuning override selects each built-in prefill kernel in turn (0-1 weight-streaming tiles of
+    128x512 with 8 waves, 2-3 of 128x256 with 4 waves, both with the height fitted to the expert; 4-5 tiles of up
+    to 256 rows with one 32-row weight group per wave, whose gate and up halves meet through LDS; the pairs differ
+    in non-temporal vs plain weight loads).  Ragged groups spanning several m-tiles, partial n-tiles for every tile
+    width, and m-tiles of every height the fitted tiles come in (1-4 fragments of 32 rows; 2, 4, 6 and 8 for the
+    256-row tiles), alone and several per expert."""
     say("ffn prefill variant", variant)
     monkeypatch.setenv("HMOE_TILED_VARIANT", str(variant))
     shape = wl.small_shape(dtype=wl.BF16, hidden=256, ffn=320, n_experts=8, top_k=2)
     got, ref = _ffn_case(hm, shape, [33, 1, 0, 0, 300, 5, 64, 129], 3, seed=variant)
     assert max_rel_err(got, ref) < TOL[wl.BF16]
-    if variant >= 5:
-        shape = wl.small_shape(dtype=wl.BF16, hidden=192, ffn=320, n_experts=8, top_k=2)
-        got, ref = _ffn_case(hm, shape, [257, 97, 96, 260, 1, 31, 32, 400], 3, seed=variant)
+    shape = wl.small_shape(dtype=wl.BF16, hidden=192, ffn=320, n_experts=8, top_k=2)
+    got, ref = _ffn_case(hm, shape, [257, 97, 96, 260, 1, 31, 32, 400], 3, seed=variant)
+    assert max_rel_err(got, ref) < TOL[wl.BF16]
+    for hidden, ffn in ((128, 384), (384, 128), (512, 512)):
+        say("ffn prefill variant", variant, "hidden", hidden, "ffn", ffn)
+        shape = wl.small_shape(dtype=wl.BF16, hidden=hidden, ffn=ffn, n_experts=4, top_k=2)
+        got, ref = _ffn_case(hm, shape, [130, 0, 7, 128], 3, seed=variant + hidden)
         assert max_rel_err(got, ref) < TOL[wl.BF16]
-    if variant in (3, 4):
-        for hidden, ffn in ((128, 384), (384, 128), (512, 512)):
-            say("ffn prefill variant", variant, "hidden", hidden, "ffn", ffn)
-            shape = wl.small_shape(dtype=wl.BF16, hidden=hidden, ffn=ffn, n_experts=4, top_k=2)
-            got, ref = _ffn_case(hm, shape, [130, 0, 7, 128], 3, seed=variant + hidden)
-            assert max_rel_err(got, ref) < TOL[wl.BF16]
 
 
 @pytest.mark.parametrize("shape_id", range(6))
