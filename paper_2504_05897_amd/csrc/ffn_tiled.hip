@@ -208,8 +208,6 @@ struct StreamTile {
           const int fill_stage = stage == 0 ? SA - 1 : stage - 1;  // held step tt-1, free since this step opened
 #pragma unroll
           for (int kk = 0; kk < KK; ++kk) {
-            constexpr int dummy = 0;
-            (void)dummy;
             if (kk == KK - 1) {
               // open step tt+1: its activation tile has landed once at most N_A younger operations are out
               wait_vmcnt<N_A>();
@@ -259,6 +257,8 @@ struct StreamTile {
   static __device__ __forceinline__ void epilogue(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
                                                   const Acc& acc, u32x4* lds) {
     if constexpr (GATEUP && FN == 1) epilogue_pairs(c, out, loc, acc, lds);
+    else if constexpr (GATEUP) epilogue_lines(c, out, loc, acc, lds);
+    else if constexpr (FN == 2) epilogue_lines_down(c, out, loc, acc, lds);
     else epilogue_part(c, out, loc, acc, 0, FM);
   }
   // Gate/up with one weight group per wave: wave 2p holds the gate half and wave 2p+1 the up half of pair p, for all
@@ -301,6 +301,78 @@ struct StreamTile {
           if (m < m_rows && f < n_out) out[(size_t)(row_first + m) * n_out + f] = f32_to_bf16(silu_f32(g) * u);
         }
       }
+    }
+  }
+  // Gate/up with two weight groups per wave: a wave's SwiGLU results are 32 columns wide, half a 128-byte line of h,
+  // and written as such they cost the launch 6-10 % (partial lines, the other half arriving from another wave at
+  // another time).  Waves 2p and 2p+1 own neighbouring columns: both put their results into one [rows][64] block in
+  // the idle activation ring, then each stores half of the rows as whole lines, 16 bytes per lane.
+  static __device__ __forceinline__ void epilogue_lines(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
+                                                        const Acc& acc, u32x4* lds) {
+    static_assert(NWV % 2 == 0 && (NWV / 2) * FM * 32 * 8 <= LDS_VEC, "the staging blocks must fit the activation ring");
+    const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
+    const int n_out = c.ffn;
+    const int m0 = loc.mt * MSTRIDE;
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int half = lane / 32, col = lane % 32;
+    bf16_t* block = (bf16_t*)(lds + (wave / 2) * FM * 32 * 8);  // [FM * 32 rows][64 columns]
+    block_barrier();  // every wave has read its last activation fragments
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
+        block[row * 64 + (wave % 2) * 32 + col] = f32_to_bf16(silu_f32(acc[i][0][r]) * acc[i][1][r]);
+      }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    block_barrier();
+    const int f = nt * (BN / 2) + (wave / 2) * 64 + (lane % 8) * 8;
+#pragma unroll
+    for (int k = 0; k < 2 * FM; ++k) {
+      const int row = (wave % 2) * FM * 16 + k * 8 + lane / 8;
+      const u32x4 v = *(const u32x4*)(block + row * 64 + (lane % 8) * 8);
+      const int m = m0 + row;
+      if (m < m_rows && f < n_out) *(u32x4*)(out + (size_t)(row_first + m) * n_out + f) = v;
+    }
+  }
+  // Down projection with two weight groups per wave: the wave's 64 columns are one 128-byte line per row.  The wave
+  // turns its accumulators into rows in a block of its own in the idle activation ring, two fragments (64 rows) at a
+  // time, and stores whole lines, 16 bytes per lane.  (LDS serves a wave's accesses in order: no barrier in between.)
+  static __device__ __forceinline__ void epilogue_lines_down(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
+                                                             const Acc& acc, u32x4* lds) {
+    static_assert(NWV * 64 * 8 <= LDS_VEC, "the staging blocks must fit the activation ring");
+    const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
+    const int n_out = c.hidden;
+    const int m0 = loc.mt * MSTRIDE;
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int half = lane / 32, col = lane % 32;
+    bf16_t* block = (bf16_t*)(lds + wave * 64 * 8);  // [64 rows][64 columns]
+    const int n = nt * BN + wave * 64 + (lane % 8) * 8;
+    block_barrier();  // every wave has read its last activation fragments
+#pragma unroll
+    for (int pass = 0; pass < (FM + 1) / 2; ++pass) {
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii) {
+        const int i = pass * 2 + ii;
+        if (i < FM) {
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              block[(ii * 32 + (r / 4) * 8 + half * 4 + (r % 4)) * 64 + j * 32 + col] = f32_to_bf16(acc[i][j][r]);
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int row = k * 8 + lane / 8;
+        if (pass * 2 + row / 32 < FM) {  // uniform per k: the second fragment of the last pass may not exist
+          const u32x4 v = *(const u32x4*)(block + row * 64 + (lane % 8) * 8);
+          const int m = m0 + pass * 64 + row;
+          if (m < m_rows && n < n_out) *(u32x4*)(out + (size_t)(row_first + m) * n_out + n) = v;
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // the rows are in registers before the next pass overwrites the block
     }
   }
   // stores the 32-row fragments i_first <= i < i_last of the tile
