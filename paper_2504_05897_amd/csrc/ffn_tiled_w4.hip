@@ -216,21 +216,37 @@ __global__ __launch_bounds__(64 * W4T_WAVES) void ffn_tile_w4_kernel(TiledCtx c,
   for (int i = 0; i < W4T_FM; ++i) fold(i, row_sums((n_groups - 1) & 1, i));
 
   // ---- epilogue: accumulator register r of lane (j, kblk) is row 16 i + 4 kblk + r, weight row j of the unit ----
-  if (unit0 >= units_total) return;  // gate/up and down both hold an even number of units: a wave's pair is all or nothing
+  // A wave's results are 16 (gate/up) or 32 (down) columns wide, a fraction of a 128-byte line.  The tile's results
+  // are collected as bf16 in the idle activation stages, [rows][OUTC columns], and stored as whole lines, 16 bytes per
+  // thread.  Units past the end (gate/up and down both hold an even number: a wave's pair is all or nothing) are
+  // neither collected nor stored.
+  constexpr int OUTC = GATEUP ? W4T_WAVES * 16 : W4T_WAVES * 32;
+  static_assert(W4T_BM * OUTC * 2 <= 2 * W4T_CHUNKS * 16, "the tile's results must fit the activation stages");
+  bf16_t* staged = (bf16_t*)&a_lds[0][0];
+  __syncthreads();  // every wave has read its last activation fragments
+  if (unit0 < units_total) {
 #pragma unroll
-  for (int i = 0; i < W4T_FM; ++i) {
+    for (int i = 0; i < W4T_FM; ++i) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int m = m0 + i * 16 + 4 * kblk + r;
-      if (m >= loc.m_rows) continue;
-      bf16_t* orow = out + (size_t)(loc.row_first + m) * n_out;
-      if (GATEUP) {
-        orow[(unit0 / 2) * 16 + j] = f32_to_bf16(silu_f32(acc[i][0][r]) * acc[i][1][r]);
-      } else {
-        orow[unit0 * 16 + j] = f32_to_bf16(acc[i][0][r]);
-        orow[unit0 * 16 + 16 + j] = f32_to_bf16(acc[i][1][r]);
+      for (int r = 0; r < 4; ++r) {
+        bf16_t* srow = staged + (i * 16 + 4 * kblk + r) * OUTC;
+        if (GATEUP) {
+          srow[wave * 16 + j] = f32_to_bf16(silu_f32(acc[i][0][r]) * acc[i][1][r]);
+        } else {
+          srow[wave * 32 + j] = f32_to_bf16(acc[i][0][r]);
+          srow[wave * 32 + 16 + j] = f32_to_bf16(acc[i][1][r]);
+        }
       }
     }
+  }
+  __syncthreads();
+  const int col0 = loc.nt * OUTC;
+#pragma unroll
+  for (int id = tid; id < W4T_BM * OUTC / 8; id += 64 * W4T_WAVES) {
+    const int row = id / (OUTC / 8), cc = (id % (OUTC / 8)) * 8;
+    const int m = m0 + row;
+    if (m < loc.m_rows && col0 + cc < n_out)
+      *(u32x4*)(out + (size_t)(loc.row_first + m) * n_out + col0 + cc) = *(const u32x4*)(staged + row * OUTC + cc);
   }
 }
 
