@@ -526,7 +526,10 @@ int launch_ffn_tiled(const FfnArgs& a) {
   //    the tile height fitted to the expert, non-temporal weight loads.  When such a launch has too few tiles to
   //    fill the CUs, the time of one tile is what counts and it takes tiles of up to 256 rows and 32 columns per
   //    wave: each wave multiplies as little as the expert needs, and an expert of up to 256 rows streams its
-  //    weights once.
+  //    weights once.  Gate/up over a short K range (hidden < 4096) with experts of at most 32 rows on average takes
+  //    the 128x256 tile with 4 waves, two blocks per CU: 2-10 % on the DeepSeek-style and Qwen2-style shapes up
+  //    to 256 tokens (with a long K range the deeper weight ring of the 8-wave tile is worth more; with larger
+  //    experts under skewed routing the non-temporal loads of several m-tiles per panel cost more than it gains).
   //  * Experts of 192 rows or more (a shared expert at a prefill batch, large routed experts) have several
   //    m-tiles that share their weight panel through L2: plain loads, and 128x256 tiles with 4 waves, two blocks
   //    per CU, so that one block's ring fill and epilogue overlap the other's main loop (4-14 % over the 8-wave
@@ -542,6 +545,7 @@ int launch_ffn_tiled(const FfnArgs& a) {
     v_down = tiles_down < 256 || d.ffn >= 4096 ? V_FIT4_PLAIN : V_FIT_PLAIN;
   } else {
     if (few_gate_up) v_gate_up = V_FIT256;
+    else if (d.hidden < 4096 && a.n_rows <= 32 * d.n_experts) v_gate_up = V_FIT4;
     if (tiles_down < 256) v_down = V_FIT256;
   }
   if (const char* env = getenv("HMOE_TILED_VARIANT")) {
