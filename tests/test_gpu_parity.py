@@ -226,6 +226,24 @@ def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
         assert max_rel_err(got, ref) < TOL[wl.BF16]
 
 
+@pytest.mark.parametrize("hidden,ffn,counts", [
+    (256, 512, [64]),                        # one small dense expert, few tiles: 256-row tiles for both projections
+    (256, 512, [300]),                       # one large expert: 4-wave tiles, plain loads
+    (256, 512, [20] * 32 + [0, 45] * 16),    # many small experts, short K: 4-wave gate/up, 256-row down
+    (128, 4096, [200, 390, 1, 250]),         # large experts, long K in the down projection: 4-wave tiles for both
+    (1536, 256, [100] * 60 + [0, 399, 1, 7]),  # 128x512 tiles, non-temporal loads, for both
+    (1024, 128, [200] * 63 + [333]),         # large experts, short K, many tiles: 4-wave gate/up, 128x512 down, plain loads
+])
+def test_ffn_prefill_choice_branches(hm, hidden, ffn, counts):
+    """The prefill path without a tuning override, on launches built to take each branch of the library's kernel
+    choice (tile-starved or not, experts below or above 192 rows on average, short or long K range)."""
+    say("ffn prefill choice", hidden, ffn, len(counts), sum(counts))
+    shape = wl.small_shape(dtype=wl.BF16, hidden=hidden, ffn=ffn, n_experts=len(counts), top_k=1)
+    got, ref = _ffn_case(hm, shape, counts, 3, seed=hidden + len(counts))
+    assert max_rel_err(got, ref) < TOL[wl.BF16]
+    assert np.abs(ref).max() > 1e-3
+
+
 @pytest.mark.parametrize("shape_id", range(6))
 @pytest.mark.parametrize("gpb", [1, 2, 3])
 def test_ffn_every_decode_block_shape(hm, shape_id, gpb, monkeypatch):
