@@ -259,7 +259,7 @@ struct StreamTile {
     if constexpr (GATEUP && FN == 1) epilogue_pairs(c, out, loc, acc, lds);
     else if constexpr (GATEUP) epilogue_lines(c, out, loc, acc, lds);
     else if constexpr (FN == 2) epilogue_lines_down(c, out, loc, acc, lds);
-    else epilogue_part(c, out, loc, acc, 0, FM);
+    else epilogue_lines_block(c, out, loc, acc, lds);
   }
   // Gate/up with one weight group per wave: wave 2p holds the gate half and wave 2p+1 the up half of pair p, for all
   // rows.  The gate wave finishes the first HALF fragments and the up wave the others; each passes the partner the
@@ -375,35 +375,32 @@ struct StreamTile {
       __builtin_amdgcn_s_waitcnt(0xC07F);  // the rows are in registers before the next pass overwrites the block
     }
   }
-  // stores the 32-row fragments i_first <= i < i_last of the tile
-  static __device__ __forceinline__ void epilogue_part(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
-                                                       const Acc& acc, int i_first, int i_last) {
+  // Down projection with one weight group per wave: a wave's 32 columns are a quarter of a line.  The block collects
+  // the tile's bf16 results in the idle activation ring, [rows][32 * NWV columns], and every thread stores whole
+  // 16-byte pieces of whole lines.
+  static __device__ __forceinline__ void epilogue_lines_block(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
+                                                              const Acc& acc, u32x4* lds) {
+    static_assert(FM * 32 * BN * 2 <= LDS_VEC * 16, "the tile's results must fit the activation ring");
     const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
-    const int n_out = GATEUP ? c.ffn : c.hidden;
+    const int n_out = c.hidden;
     const int m0 = loc.mt * MSTRIDE;
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
     const int half = lane / 32, col = lane % 32;
-    // ---- epilogue: accumulator register r of lane (half, col) is row 8*(r/4) + 4*half + r%4 ----
+    bf16_t* staged = (bf16_t*)lds;
+    block_barrier();  // every wave has read its last activation fragments
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
-      if (i < i_first || i >= i_last) continue;  // uniform
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps the accumulator reads from piling up
-        const int m = m0 + i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
-        if (m >= m_rows) continue;
-        bf16_t* orow = out + (size_t)(row_first + m) * n_out;
-        if (GATEUP) {
-          const int f = nt * (BN / 2) + wave * 32 + col;
-          if (f < n_out) orow[f] = f32_to_bf16(silu_f32(acc[i][0][r]) * acc[i][1][r]);
-        } else {
+      for (int r = 0; r < 16; ++r)
+        staged[(i * 32 + (r / 4) * 8 + half * 4 + (r % 4)) * BN + wave * 32 + col] = f32_to_bf16(acc[i][0][r]);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    block_barrier();
 #pragma unroll
-          for (int j = 0; j < FN; ++j) {
-            const int n = nt * BN + (wave * FN + j) * 32 + col;
-            if (n < n_out) orow[n] = f32_to_bf16(acc[i][j][r]);
-          }
-        }
-      }
+    for (int id = tid; id < FM * 32 * BN / 8; id += THREADS) {
+      const int row = id / (BN / 8), cc = (id % (BN / 8)) * 8;
+      const int m = m0 + row, n = nt * BN + cc;
+      if (m < m_rows && n < n_out)
+        *(u32x4*)(out + (size_t)(row_first + m) * n_out + n) = *(const u32x4*)(staged + row * BN + cc);
     }
   }
 };
