@@ -431,10 +431,15 @@ __device__ __forceinline__ void run_tile(const TiledCtx& c, const bf16_t* __rest
 // that multiplies that many fragments.  The m-tiles of one weight panel stay equally long -- their blocks run
 // side by side and share the panel through L2, which uneven tiles would break -- and the padding rows that are
 // multiplied drop from up to 127 to at most 31 per m-tile.
+//
+// Two waves per SIMD either way (the second launch bound caps the kernel at 256 registers): one block of 8 waves, or
+// two blocks of 4 waves whose ring fill and epilogue overlap each other's main loop.  Left to itself the compiler
+// gives the 4-wave kernel 480 registers and the CU a single block.  With 256 registers the 4-wave tile has room for
+// a weight ring of one K step only.
 template <bool GATEUP, int NWV, bool NT>
 __global__ __launch_bounds__(64 * NWV, 2) void ffn_tile_fit_kernel(TiledCtx c, const bf16_t* __restrict__ in,
                                                                  bf16_t* __restrict__ out) {
-  constexpr int RING = NWV == 4 ? 4 : 8;  // two 4-wave blocks per CU: half the ring each
+  constexpr int RING = NWV == 4 ? 4 : 8;
   typedef StreamTile<GATEUP, 128, NWV, 4, NT, RING, 4> FULL;
   __shared__ u32x4 lds[FULL::LDS_VEC];
   TileLoc loc;
