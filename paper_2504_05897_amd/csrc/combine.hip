@@ -84,19 +84,22 @@ __global__ __launch_bounds__(256) void router_logits_f32_kernel(const float* __r
   if (lane == 0) logits[pair] = acc;
 }
 
-// bf16 layers: a block takes 32 tokens and all experts; both operands are K-contiguous rows, so
-// lanes load MFMA fragments straight from global memory (token or expert row = lane%32, 8 k values
-// at 8*(lane/32)).  The 4 waves split K and meet in LDS.  NF = ceil(E/32) expert fragments.
+// bf16 layers: a block takes tokens_per_block (at most 32) tokens and all experts; both operands are K-contiguous
+// rows, so lanes load MFMA fragments straight from global memory (token or expert row = lane%32, 8 k values
+// at 8*(lane/32)).  The 4 waves split K and meet in LDS.  NF = ceil(E/32) expert fragments.  The launch gives a
+// block fewer than 32 tokens when that is what it takes to have blocks for half of the CUs (the rows of the MFMA
+// that stay empty cost nothing; a token's sum runs in the same order whatever the block holds).
 template <int NF>
 __global__ __launch_bounds__(256) void router_logits_bf16_kernel(const bf16_t* __restrict__ x,
                                                                  const bf16_t* __restrict__ w_g, int n_tokens,
-                                                                 int n_experts, int hidden, float* __restrict__ logits) {
+                                                                 int n_experts, int hidden, float* __restrict__ logits,
+                                                                 int tokens_per_block) {
   __shared__ float red[3 * NF * 16 * 64];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, half = lane / 32, col = lane % 32;
-  const long t0 = (long)blockIdx.x * 32;
+  const long t0 = (long)blockIdx.x * tokens_per_block;
   const int kt = hidden / 16, per_wave = (kt + 3) / 4;
   const int kb0 = min(wave * per_wave, kt), kb1 = min(kb0 + per_wave, kt);
-  const bool has_tok = t0 + col < n_tokens;
+  const bool has_tok = col < tokens_per_block && t0 + col < n_tokens;
   const u32x4* xp = (const u32x4*)(x + (t0 + (has_tok ? col : 0)) * hidden) + half;
   const u32x4* wp[NF];
   bool has_exp[NF];
@@ -149,8 +152,9 @@ __global__ __launch_bounds__(256) void router_logits_bf16_kernel(const bf16_t* _
       for (int r = 0; r < 16; ++r) {
         float v = acc[j][r];
         for (int w = 0; w < 3; ++w) v += red[((w * NF + j) * 16 + r) * 64 + lane];
-        const long t = t0 + (r / 4) * 8 + half * 4 + (r % 4);
-        if (t < n_tokens && e < n_experts) logits[t * n_experts + e] = v;
+        const int row = (r / 4) * 8 + half * 4 + (r % 4);
+        const long t = t0 + row;
+        if (row < tokens_per_block && t < n_tokens && e < n_experts) logits[t * n_experts + e] = v;
       }
     }
   }
@@ -201,7 +205,9 @@ extern "C" int32_t hmoe_router_logits(const hmoe_layer_desc* desc, const void* x
   if (desc->dtype != HMOE_F32) {
     if (H % 16 != 0) return HMOE_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(w_g)) return HMOE_ERR_INVALID_ARG;
-    const dim3 grid((unsigned)((T + 31) / 32)), block(256);
+    int tpb = 32;  // tokens per block: fewer while the grid would leave more than half of the CUs without a block
+    while (tpb > 4 && (T + tpb - 1) / tpb < 128) tpb /= 2;
+    const dim3 grid((unsigned)((T + tpb - 1) / tpb)), block(256);
     const bf16_t* xb = (const bf16_t*)x;
     const bf16_t* wb = (const bf16_t*)w_g;
     if (T <= ROUTER_SMALL_T) {
@@ -209,10 +215,10 @@ extern "C" int32_t hmoe_router_logits(const hmoe_layer_desc* desc, const void* x
       else if (E <= 64) hipLaunchKernelGGL((router_logits_small_kernel<2>), dim3(1), block, 0, s, xb, wb, T, E, H, logits);
       else if (E <= 128) hipLaunchKernelGGL((router_logits_small_kernel<4>), dim3(1), block, 0, s, xb, wb, T, E, H, logits);
       else hipLaunchKernelGGL((router_logits_small_kernel<8>), dim3(1), block, 0, s, xb, wb, T, E, H, logits);
-    } else if (E <= 32) hipLaunchKernelGGL((router_logits_bf16_kernel<1>), grid, block, 0, s, xb, wb, T, E, H, logits);
-    else if (E <= 64) hipLaunchKernelGGL((router_logits_bf16_kernel<2>), grid, block, 0, s, xb, wb, T, E, H, logits);
-    else if (E <= 128) hipLaunchKernelGGL((router_logits_bf16_kernel<4>), grid, block, 0, s, xb, wb, T, E, H, logits);
-    else hipLaunchKernelGGL((router_logits_bf16_kernel<8>), grid, block, 0, s, xb, wb, T, E, H, logits);
+    } else if (E <= 32) hipLaunchKernelGGL((router_logits_bf16_kernel<1>), grid, block, 0, s, xb, wb, T, E, H, logits, tpb);
+    else if (E <= 64) hipLaunchKernelGGL((router_logits_bf16_kernel<2>), grid, block, 0, s, xb, wb, T, E, H, logits, tpb);
+    else if (E <= 128) hipLaunchKernelGGL((router_logits_bf16_kernel<4>), grid, block, 0, s, xb, wb, T, E, H, logits, tpb);
+    else hipLaunchKernelGGL((router_logits_bf16_kernel<8>), grid, block, 0, s, xb, wb, T, E, H, logits, tpb);
   } else {
     const long pairs = (long)T * E;
     hipLaunchKernelGGL(router_logits_f32_kernel, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, s, (const float*)x,
