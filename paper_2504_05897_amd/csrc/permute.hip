@@ -279,6 +279,27 @@ __global__ __launch_bounds__(PB_THREADS) void front_small_kernel(const bf16_t* _
                           inv_perm);
 }
 
+// Larger bf16 batches: router logits and routing in one launch.  A block computes the logits of its tokens (global
+// memory, they are an output, and LDS) and routes them from LDS, lane groups as in hmoe_route; the permutation,
+// which needs every token's choice, stays a launch of its own.
+template <int G, int VPL, int NF>
+__global__ __launch_bounds__(PB_THREADS) void front_tokens_kernel(const bf16_t* __restrict__ x,
+                                                                  const bf16_t* __restrict__ w_g, int hidden,
+                                                                  float* __restrict__ logits, int n_tokens, int n_experts,
+                                                                  int top_k, int tokens_per_block, int32_t* topk_idx,
+                                                                  float* __restrict__ topk_w) {
+  __shared__ float lds_logits[32 * NF * 32];
+  router_logits_tokens<NF>(x, w_g, n_tokens, n_experts, hidden, logits, tokens_per_block, lds_logits);  // ends with a barrier
+  constexpr int TOKENS_PER_PASS = PB_THREADS / G;
+  const long t0 = (long)blockIdx.x * tokens_per_block;
+  for (int l0 = 0; l0 < tokens_per_block; l0 += TOKENS_PER_PASS) {
+    const int local = l0 + threadIdx.x / G;
+    const bool valid = local < tokens_per_block && t0 + local < n_tokens;
+    route_token<G, VPL>(lds_logits, n_experts, top_k, local, valid, threadIdx.x % G, topk_idx + t0 * top_k,
+                        topk_w + t0 * top_k);
+  }
+}
+
 // x_perm[p, :] = x[perm[p] / K, :], rows of row_bytes (multiple of 16)
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ perm,
                                                           int top_k, int row_vec, int n_assign,
@@ -393,6 +414,27 @@ extern "C" int32_t hmoe_router_route_permute(const hmoe_layer_desc* desc, const 
   if (rc != HMOE_OK) return rc;
   if (T < 0 || !expert_offsets) return HMOE_ERR_INVALID_ARG;
   const long A = (long)T * desc->top_k;
+  if (T > ROUTER_SMALL_T && desc->dtype != HMOE_F32 && desc->hidden % 16 == 0 && x && w_g && logits && topk_idx &&
+      topk_w && aligned16(x) && aligned16(w_g)) {
+    // logits and routing in one launch, then the permutation
+    const int E = desc->n_experts, K = desc->top_k;
+    int tpb = 32;  // tokens per block: fewer while the grid would leave more than half of the CUs without a block
+    while (tpb > 4 && (T + tpb - 1) / tpb < 128) tpb /= 2;
+    const dim3 grid((unsigned)((T + tpb - 1) / tpb));
+#define HMOE_LAUNCH_FRONT_TOKENS(G, VPL, NF)                                                                        \
+  hipLaunchKernelGGL((front_tokens_kernel<G, VPL, NF>), grid, dim3(PB_THREADS), 0, (hipStream_t)stream,             \
+                     (const bf16_t*)x, (const bf16_t*)w_g, desc->hidden, logits, (int)T, E, K, tpb, topk_idx, topk_w)
+    if (E <= 8) HMOE_LAUNCH_FRONT_TOKENS(8, 1, 1);
+    else if (E <= 16) HMOE_LAUNCH_FRONT_TOKENS(16, 1, 1);
+    else if (E <= 32) HMOE_LAUNCH_FRONT_TOKENS(32, 1, 1);
+    else if (E <= 64) HMOE_LAUNCH_FRONT_TOKENS(64, 1, 2);
+    else if (E <= 128) HMOE_LAUNCH_FRONT_TOKENS(64, 2, 4);
+    else HMOE_LAUNCH_FRONT_TOKENS(64, 4, 8);
+#undef HMOE_LAUNCH_FRONT_TOKENS
+    HMOE_HIP(hipGetLastError());
+    return hmoe_permute(desc, topk_idx, T, nullptr, nullptr, expert_offsets, perm, inv_perm, h_counts_pinned, workspace,
+                        workspace_bytes, stream);
+  }
   if (T == 0 || T > ROUTER_SMALL_T || A > PB_CHUNK || desc->dtype == HMOE_F32) {  // the separate calls
     rc = hmoe_router_logits(desc, x, w_g, T, logits, stream);
     if (rc != HMOE_OK) return rc;
