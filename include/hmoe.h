@@ -152,8 +152,8 @@ int32_t hmoe_route_permute(const hmoe_layer_desc* desc, const float* logits, int
 /*
  * hmoe_router_logits followed by hmoe_route_permute as one call: the whole front end of Eq. (1)
  * (x . W_g, Softmax(TopK(.)), permutation).  For decode batches (bf16, T <= 8) it is a single
- * one-block launch; larger bf16 batches compute the logits and route in one launch and permute in a
- * second; anything else runs the two calls above.  `logits` [T, E] is an output (the same bits
+ * one-block launch; bf16 batches of up to 2048 tokens compute the logits and route in one launch and
+ * permute in a second; anything else runs the two calls above.  `logits` [T, E] is an output (the same bits
  * hmoe_router_logits writes); the other arguments and results as in those calls.
  */
 int32_t hmoe_router_route_permute(const hmoe_layer_desc* desc, const void* x, const void* w_g, int32_t T,

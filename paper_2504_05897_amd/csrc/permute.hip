@@ -414,9 +414,10 @@ extern "C" int32_t hmoe_router_route_permute(const hmoe_layer_desc* desc, const 
   if (rc != HMOE_OK) return rc;
   if (T < 0 || !expert_offsets) return HMOE_ERR_INVALID_ARG;
   const long A = (long)T * desc->top_k;
-  if (T > ROUTER_SMALL_T && desc->dtype != HMOE_F32 && desc->hidden % 16 == 0 && x && w_g && logits && topk_idx &&
-      topk_w && aligned16(x) && aligned16(w_g)) {
-    // logits and routing in one launch, then the permutation
+  if (T > ROUTER_SMALL_T && T <= 2048 && desc->dtype != HMOE_F32 && desc->hidden % 16 == 0 && x && w_g && logits &&
+      topk_idx && topk_w && aligned16(x) && aligned16(w_g)) {
+    // logits and routing in one launch, then the permutation (a launch saved; beyond a few thousand tokens the
+    // separate routing kernel, with a block per few tokens, is the faster one)
     const int E = desc->n_experts, K = desc->top_k;
     int tpb = 32;  // tokens per block: fewer while the grid would leave more than half of the CUs without a block
     while (tpb > 4 && (T + tpb - 1) / tpb < 128) tpb /= 2;
