@@ -50,8 +50,3 @@ def dequantize_w4(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
     n, k = codes.shape
     v = (codes.astype(np.float64) - 8.0).reshape(n, k // GROUP, GROUP) * scales.astype(np.float64)[:, :, None]
     return v.reshape(n, k)
-
-
-def quantized_expert(w_gate: np.ndarray, w_up: np.ndarray, w_down: np.ndarray):
-    """The three matrices of an expert as float64 arrays holding the values their 4-bit codes stand for."""
-    return tuple(dequantize_w4(*quantize_w4(m)) for m in (w_gate, w_up, w_down))

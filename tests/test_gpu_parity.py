@@ -375,6 +375,44 @@ def test_cache_slot_maps_and_outputs_follow_the_oracle_over_decode_steps(hm):
     layer.close()
 
 
+def test_cache_evict_follows_the_oracle(hm):
+    """hmoe_cache_evict between layer calls: host mirror, device table, the plans of the following calls (a freed
+    slot is taken first, lowest first) and the outputs equal the oracle's cache model after every step."""
+    say("cache evictions")
+    shape = wl.small_shape(dtype=wl.BF16, hidden=64, ffn=64, n_experts=8, top_k=2, n_slots=4, x_mode="rmsnorm")
+    lay0 = wl.make_layer(shape, 3, 8)
+    layer = build_layer(hm, lay0, max_tokens=8)
+    model = orc.ExpertCacheModel(8, 4)
+    script = [("serve", 1), ("evict", 0), ("evict", 6), ("serve", 8), ("evict", 3), ("evict", 2), ("evict", 2), ("serve", 2),
+              ("serve", 8), ("evict", 1), ("evict", 5), ("evict", 7), ("evict", 4), ("evict", 0), ("serve", 3), ("serve", 8)]
+    for i, (what, arg) in enumerate(script):
+        if what == "evict":
+            hm.hmoe_cache_evict(layer.cache, arg)
+            model.evict(arg)
+            torch.cuda.synchronize()
+        else:
+            T = arg
+            lay = wl.make_layer(shape, 500 + i, T, with_weights=False)
+            lay.experts, lay.w_router = lay0.experts, lay0.w_router
+            x = to_device(lay.x)
+            hm.hmoe_router_logits(layer.desc, x, layer.w_router, T, layer.logits)
+            logits = layer.logits[:T].cpu().numpy()
+            y = layer.forward(x, layer.logits[:T].contiguous())
+            torch.cuda.synchronize()
+            ridx, _ = orc.route(logits, 2)
+            plan = model.serve(np.unique(ridx).tolist())
+            wave, slot, victim, n_waves = layer.last_plan
+            for (e, s, w, v) in plan:
+                assert wave[e] == w and slot[e] == s and victim[e] == v, (i, plan)
+            err = max_rel_err(to_host_f32(y), oracle_layer(lay, logits))
+            say("  step", i, "T", T, "waves", n_waves, "err", err)
+            assert err < TOL[wl.BF16]
+        assert layer.slot_map() == model.slot_of, (i, what, arg)
+        assert np.array_equal(layer.slot_of.cpu().numpy(), np.array(model.slot_of, np.int32))
+        assert [hm.hmoe_cache_occupant(layer.cache, s) for s in range(4)] == model.expert_in
+    layer.close()
+
+
 def test_cache_stage_errors_and_pinning(hm):
     say("cache errors")
     shape = wl.small_shape(dtype=wl.BF16, hidden=64, ffn=64, n_experts=4, top_k=2, n_slots=2)
@@ -437,7 +475,8 @@ def test_route_permute_fused_equals_the_two_calls(hm, T, E, K):
 
 @pytest.mark.parametrize("T,E,K,H", [(1, 8, 2, 4096), (8, 8, 2, 256), (1, 64, 6, 2048), (4, 64, 8, 3584), (7, 60, 4, 128),
                                      (8, 128, 8, 64), (2, 200, 9, 192), (8, 256, 32, 64), (9, 64, 6, 128), (40, 8, 2, 64),
-                                     (0, 8, 2, 64)])
+                                     (0, 8, 2, 64), (40, 128, 8, 64), (100, 256, 32, 64), (300, 200, 9, 192),
+                                     (1024, 64, 6, 2048), (2048, 64, 8, 3584), (2049, 64, 8, 128)])
 def test_front_end_fused_equals_the_separate_calls(hm, T, E, K, H):
     """hmoe_router_route_permute (one launch for bf16, T <= 8; the separate calls otherwise) writes the same
     bits as hmoe_router_logits + hmoe_route + hmoe_permute, and the integers the oracle derives from them."""

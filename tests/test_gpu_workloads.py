@@ -1,11 +1,14 @@
 """Parity at the full sizes of the five workloads, in the launch configuration the benchmark
-times (AUTO kernel choice, real cache sizes with staging from pinned host memory).
+times (AUTO kernel choice, fused front end, real cache sizes with staging from pinned host memory).
 
 Integer results (top-k ids, offsets, permutation, slot map) are compared in full and bit for bit.
-The layer output is compared on every token for small batches and on a seeded sample of tokens
-for prefill batches (tokens are independent in Eq. (1), so the oracle evaluates the sampled ones
-one by one); the measure is max|y - y_ref| / max|y_ref| over the compared tokens, 2e-2 for bf16
-and 1e-4 for fp32."""
+The layer output is compared on every token for small batches and on a stratified sample of at least
+256 tokens for prefill batches (tokens are independent in Eq. (1), so the oracle evaluates the sampled
+ones one by one): for every expert with rows, the tokens behind the first and the last sorted row of its
+first and of its last 128-row tile, then seeded random tokens up to the sample size.  The measure is
+max|y - y_ref| / max|y_ref| over the compared tokens, 2e-2 for bf16 and 1e-4 for fp32.  Workloads whose
+logits come from x . W_g run through the fused front end (forward(x, None)), as the benchmark does, and
+once through the separate calls."""
 import sys
 
 import numpy as np
@@ -30,17 +33,39 @@ def say(*a):
     sys.stdout.flush()
 
 
-def run_and_check(hm, layer, base, shape, seed, T, n_sample, model=None):
+def stratified_tokens(offsets, perm, top_k, n_tokens, n_sample, seed, tile=128):
+    """Tokens behind the first and last sorted row of the first and of the last `tile`-row tile of every expert
+    with rows, plus seeded random tokens until there are at least n_sample (all tokens if n_sample >= n_tokens)."""
+    if n_sample >= n_tokens:
+        return np.arange(n_tokens)
+    rows = []
+    for e in range(len(offsets) - 1):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi > lo:
+            last_tile = lo + (hi - 1 - lo) // tile * tile
+            rows += [lo, min(lo + tile, hi) - 1, last_tile, hi - 1]
+    picked = set(int(perm[p]) // top_k for p in rows)
+    for t in np.random.default_rng(seed).permutation(n_tokens):
+        if len(picked) >= n_sample:
+            break
+        picked.add(int(t))
+    return np.array(sorted(picked))
+
+
+def run_and_check(hm, layer, base, shape, seed, T, n_sample, model=None, fused_front=True):
     """One forward of `layer` on fresh seeded activations; returns the error on the sample."""
     lay = wl.make_layer(shape, seed, T, with_weights=False)
     lay.experts, lay.shared, lay.w_router = base.experts, base.shared, base.w_router
     x = to_device(lay.x)
     if lay.logits is None:
-        hm.hmoe_router_logits(layer.desc, x, layer.w_router, T, layer.logits)
-        logits = layer.logits[:T].cpu().numpy()
         ref_lg = orc.router_logits(wl.as_f64(lay.x), wl.as_f64(lay.w_router))
+        if fused_front:      # router logits, routing and permutation through hmoe_router_route_permute, as benchmarked
+            y = layer.forward(x, None)
+        else:
+            hm.hmoe_router_logits(layer.desc, x, layer.w_router, T, layer.logits)
+            y = layer.forward(x, layer.logits[:T])
+        logits = layer.logits[:T].cpu().numpy()
         assert np.abs(logits - ref_lg).max() <= 1e-5 * np.abs(ref_lg).max()
-        y = layer.forward(x, layer.logits[:T])
     else:
         logits = lay.logits
         y = layer.forward(x, to_device(logits))
@@ -60,10 +85,8 @@ def run_and_check(hm, layer, base, shape, seed, T, n_sample, model=None):
         wave = layer.last_plan[0]
         for (e, s, w, v) in plan:
             assert wave[e] == w
-    if n_sample >= T:
-        sub = np.arange(T)
-    else:
-        sub = np.sort(np.random.default_rng(seed).choice(T, n_sample, replace=False))
+    sub = stratified_tokens(ro, rp, K, T, n_sample, seed)
+    assert len(sub) >= min(T, n_sample)
     y_ref = oracle_layer(lay, logits, token_subset=sub)
     return max_rel_err(to_host_f32(y)[sub], y_ref)
 
@@ -84,8 +107,8 @@ def test_workload2_mixtral(hm):
     base = wl.make_layer(shape, 1, 1, threads=16)
     layer = build_layer(hm, base, max_tokens=512)
     model = orc.ExpertCacheModel(shape.n_experts, shape.n_slots)
-    for i, (T, n_sample) in enumerate([(1, 1), (1, 1), (8, 8), (1, 1), (512, 24), (8, 8)]):
-        err = run_and_check(hm, layer, base, shape, 200 + i, T, n_sample, model)
+    for i, (T, n_sample) in enumerate([(1, 1), (1, 1), (8, 8), (1, 1), (512, 256), (8, 8)]):
+        err = run_and_check(hm, layer, base, shape, 200 + i, T, n_sample, model, fused_front=i != 1)
         say("  T", T, "waves", layer.last_plan[3], "err", err)
         assert err < TOL[wl.BF16]
     layer.close()
@@ -97,7 +120,7 @@ def test_workload3_dsv2lite(hm):
     base = wl.make_layer(shape, 2, 1, threads=16)
     layer = build_layer(hm, base, max_tokens=1024)
     model = orc.ExpertCacheModel(shape.n_experts, shape.n_slots)
-    for i, (T, n_sample) in enumerate([(1, 1), (1, 1), (1024, 96), (1, 1)]):
+    for i, (T, n_sample) in enumerate([(1, 1), (1, 1), (1024, 256), (1, 1)]):
         err = run_and_check(hm, layer, base, shape, 300 + i, T, n_sample, model)
         say("  T", T, "waves", layer.last_plan[3], "err", err)
         assert err < TOL[wl.BF16]
@@ -110,7 +133,7 @@ def test_workload4_qwen2moe(hm):
     base = wl.make_layer(shape, 3, 1, threads=16)
     layer = build_layer(hm, base, max_tokens=2048)
     model = orc.ExpertCacheModel(shape.n_experts, shape.n_slots)
-    for i, (T, n_sample) in enumerate([(4, 4), (2048, 64), (4, 4)]):
+    for i, (T, n_sample) in enumerate([(4, 4), (2048, 256), (4, 4)]):
         err = run_and_check(hm, layer, base, shape, 400 + i, T, n_sample, model)
         say("  T", T, "waves", layer.last_plan[3], "err", err)
         assert err < TOL[wl.BF16]
@@ -118,15 +141,21 @@ def test_workload4_qwen2moe(hm):
 
 
 def test_workload5_stress_layers(hm):
-    say("workload 5: 16384 tokens, all experts resident, two of the stacked layers")
+    say("workload 5: 16384 tokens, all experts resident, every one of the 27 stacked layers")
+    from concurrent.futures import ThreadPoolExecutor
     shape = wl.STRESS
-    for li in (0, 26):
-        base = wl.make_layer(shape, 5000 + li, 1, threads=16)
-        layer = build_layer(hm, base, max_tokens=16384)
-        err = run_and_check(hm, layer, base, shape, 5000 + li, 16384, 64)
-        say("  layer", li, "err", err)
-        layer.close()
-        assert err < TOL[wl.BF16]
+    with ThreadPoolExecutor(max_workers=1) as pool:      # the next layer's weights are drawn while this one is checked
+        nxt = pool.submit(wl.make_layer, shape, 5000, 1, threads=12)
+        for li in range(27):
+            base = nxt.result()
+            if li + 1 < 27:
+                nxt = pool.submit(wl.make_layer, shape, 5000 + li + 1, 1, threads=12)
+            layer = build_layer(hm, base, max_tokens=16384)
+            err = run_and_check(hm, layer, base, shape, 5000 + li, 16384, 256, fused_front=li != 1)
+            say("  layer", li, "err", err)
+            layer.close()
+            del layer, base
+            assert err < TOL[wl.BF16]
 
 
 def test_bench_line_contract():

@@ -268,6 +268,49 @@ def test_cache_multi_expert_calls_every_needed_expert_served_once():
                 assert w == waves[v] + 1                       # never overwrite before the victim ran
 
 
+def test_cache_evict_hand_trace():
+    """Dropping an expert frees its slot; the next miss takes the lowest-numbered free slot before any
+    occupant is replaced, and an expert that is not resident is dropped without effect (traced by hand)."""
+    c = orc.ExpertCacheModel(n_experts=4, n_slots=2)
+    c.serve([0])                                   # tick[0] = 1
+    c.serve([1])                                   # tick[1] = 2
+    c.evict(0)
+    assert c.slot_of == [-1, 1, -1, -1] and c.expert_in == [-1, 1]
+    c.evict(3)                                     # not resident: nothing changes
+    assert c.slot_of == [-1, 1, -1, -1] and c.expert_in == [-1, 1]
+    assert c.serve([2]) == [(2, 0, 1, -1)]         # the free slot, nobody replaced; tick[2] = 4
+    assert c.serve([3]) == [(3, 1, 1, 1)]          # no free slot: expert 1 (tick 2) is older than expert 2 (tick 4)
+    c.evict(3)
+    c.evict(2)
+    assert c.slot_of == [-1, -1, -1, -1] and c.expert_in == [-1, -1]
+    assert c.serve([1, 0]) == [(0, 0, 1, -1), (1, 1, 1, -1)]   # misses in ascending id, lowest free slot each
+    assert c.slot_of == [0, 1, -1, -1]
+
+
+def test_cache_evict_keeps_the_maps_inverse():
+    rng = np.random.default_rng(11)
+    c = orc.ExpertCacheModel(10, 4)
+    for _ in range(300):
+        if rng.random() < 0.3:
+            e = int(rng.integers(10))
+            was = c.slot_of[e]
+            c.evict(e)
+            assert c.slot_of[e] == -1 and (was < 0 or c.expert_in[was] == -1)
+        else:
+            need = rng.choice(10, size=int(rng.integers(1, 5)), replace=False).tolist()
+            free_before = [s for s in range(4) if c.expert_in[s] < 0]
+            plan = c.serve(need)
+            misses = [p for p in plan if p[2] > 0]
+            for (e, s, w, v), want in zip(misses, free_before):   # free slots go first, lowest first, nobody replaced
+                assert s == want and v == -1
+        for ex in range(10):
+            if c.slot_of[ex] >= 0:
+                assert c.expert_in[c.slot_of[ex]] == ex
+        for s in range(4):
+            if c.expert_in[s] >= 0:
+                assert c.slot_of[c.expert_in[s]] == s
+
+
 # ----------------------------------------------------------------------------- input recipe
 def test_bf16_rounding_is_nearest_even():
     a = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.0e-5], dtype=np.float32)
