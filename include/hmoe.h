@@ -341,11 +341,12 @@ int32_t hmoe_schedule_plan(int32_t n_experts, const int32_t* h_load, const int32
                            double* h_transfer_start, double* makespan, int32_t* rules_out);
 
 /* ------------------------------------------------------------------------------------
- * Timing probe for benchmarks: while armed, every hmoe_expert_ffn_grouped call brackets
- * its first (gate/up) kernel launch with a pair of HIP events on the call's stream.
+ * Timing probe for benchmarks: while armed, every grouped-FFN call brackets each of its two
+ * kernel launches with a pair of HIP events on the call's stream: first the gate/up launch
+ * (h = silu(x W_gate^T) * (x W_up^T)), then the down projection, so a call records two pairs.
  * hmoe_probe_arm(max_pairs) creates the events; hmoe_probe_read synchronises them and
  * writes the elapsed milliseconds of each recorded pair to h_ms (up to max), returns the
- * count in *n, and disarms.
+ * count in *n, and disarms.  Not for use under stream capture.
  */
 int32_t hmoe_probe_arm(int32_t max_pairs);
 int32_t hmoe_probe_read(float* h_ms, int32_t max, int32_t* n);

@@ -19,6 +19,11 @@ int set_hip_error(hipError_t err, const char* what) {
   return HMOE_ERR_HIP;
 }
 
+int set_error_text(int status, const char* text) {
+  g_last_error = text;
+  return status;
+}
+
 int check_desc(const hmoe_layer_desc* d) {
   if (!d) return HMOE_ERR_INVALID_ARG;
   if (d->hidden <= 0 || d->ffn <= 0 || d->n_experts <= 0 || d->top_k <= 0 || d->n_slots <= 0)

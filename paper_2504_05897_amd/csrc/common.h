@@ -71,6 +71,7 @@ __host__ __device__ inline size_t packed_index(int n, int k, int k_tiles) {
 }
 
 int set_hip_error(hipError_t err, const char* what);
+int set_error_text(int status, const char* text);  // text for hmoe_last_error; returns status
 int check_desc(const hmoe_layer_desc* d);
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

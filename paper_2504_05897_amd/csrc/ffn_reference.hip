@@ -171,12 +171,14 @@ int launch_ffn_reference(const FfnArgs& a) {
   else
     hipLaunchKernelGGL(ref_gateup_bf16, g1, dim3(256), 0, a.stream, c, (const bf16_t*)a.x_perm, (bf16_t*)a.h);
   probe_after(a.stream);
+  probe_before(a.stream);
   if (d.dtype == HMOE_F32)
     hipLaunchKernelGGL(ref_down_f32, g2, dim3(256), 0, a.stream, c, (const float*)a.h, (float*)a.o_perm);
   else if (d.dtype == HMOE_BF16_W4)
     hipLaunchKernelGGL(ref_down_w4, g2, dim3(256), 0, a.stream, c, (const bf16_t*)a.h, (bf16_t*)a.o_perm);
   else
     hipLaunchKernelGGL(ref_down_bf16, g2, dim3(256), 0, a.stream, c, (const bf16_t*)a.h, (bf16_t*)a.o_perm);
+  probe_after(a.stream);
   HMOE_HIP(hipGetLastError());
   return HMOE_OK;
 }

@@ -273,8 +273,10 @@ int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense) {
   probe_before(a.stream);
   launch_stage<true>(c, d.ffn / TILE_N, busy_max, max_rows, ffn_dense / TILE_N, (const bf16_t*)a.x_perm, (bf16_t*)a.h, a.stream);
   probe_after(a.stream);
+  probe_before(a.stream);
   launch_stage<false>(c, d.hidden / TILE_N, busy_max, max_rows, dense ? d.hidden / TILE_N : 0, (const bf16_t*)a.h,
                       (bf16_t*)a.o_perm, a.stream);
+  probe_after(a.stream);
   HMOE_HIP(hipGetLastError());
   return HMOE_OK;
 }
@@ -467,7 +469,9 @@ int launch_ffn_skinny_w4(const FfnArgs& a) {
   probe_before(a.stream);
   launch_stage_w4<true>(c, d.ffn, busy_max, (const bf16_t*)a.x_perm, (bf16_t*)a.h, a.stream);
   probe_after(a.stream);
+  probe_before(a.stream);
   launch_stage_w4<false>(c, d.hidden, busy_max, (const bf16_t*)a.h, (bf16_t*)a.o_perm, a.stream);
+  probe_after(a.stream);
   HMOE_HIP(hipGetLastError());
   return HMOE_OK;
 }

@@ -561,7 +561,9 @@ int launch_ffn_tiled(const FfnArgs& a) {
   probe_before(a.stream);
   kVariants[v_gate_up].gate_up(c, a.n_rows, x, h, a.stream);
   probe_after(a.stream);
+  probe_before(a.stream);
   kVariants[v_down].down(c, a.n_rows, h, o, a.stream);
+  probe_after(a.stream);
   HMOE_HIP(hipGetLastError());
   return HMOE_OK;
 }

@@ -266,7 +266,9 @@ int launch_ffn_tiled_w4(const FfnArgs& a) {
   probe_before(a.stream);
   launch_stage_tile_w4<true, 64, 4>(c, a.n_rows, (const bf16_t*)a.x_perm, (bf16_t*)a.h, a.stream);
   probe_after(a.stream);
+  probe_before(a.stream);
   launch_stage_tile_w4<false, 64, 4>(c, a.n_rows, (const bf16_t*)a.h, (bf16_t*)a.o_perm, a.stream);
+  probe_after(a.stream);
   HMOE_HIP(hipGetLastError());
   return HMOE_OK;
 }

@@ -160,14 +160,16 @@ def test_workload5_stress_layers(hm):
 
 def test_bench_line_contract():
     """bench.py prints one JSON line with the fields the harness reads: metric, value, timing, the roofline of the
-    dominant kernel and the CPU-oracle baseline; a GPU count above one is refused."""
+    dominant kernel and the CPU-oracle baseline; the default run covers every bf16 workload and reports the largest
+    (the MFMA-bound stress workload) as `value`; a GPU count above one is refused."""
     import json
     import os
     import subprocess
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     print("bench contract", flush=True)
-    run = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "3", "--warmup", "1"],
-                         capture_output=True, text=True, timeout=300, cwd=root)
+    # the default command with fewer stacked stress layers, so that the set-up stays short
+    run = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "2", "--warmup", "1", "--blocks", "3",
+                          "--layers", "2"], capture_output=True, text=True, timeout=600, cwd=root)
     assert run.returncode == 0, run.stderr[-2000:]
     lines = [l for l in run.stdout.splitlines() if l.startswith("{")]
     assert len(lines) == 1
@@ -175,13 +177,24 @@ def test_bench_line_contract():
     for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
                 "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
         assert key in out, key
-    assert out["n_gpus"] == 1 and out["steps"] == 3 and out["warmup"] == 1 and out["higher_is_better"] is True
-    assert out["value"] > 0 and out["ms_per_step"] > 0 and out["config"]["workload"] == "mixtral/prefill512"
+    assert out["n_gpus"] == 1 and out["steps"] == 2 and out["warmup"] == 1 and out["higher_is_better"] is True
+    assert out["value"] > 0 and out["ms_per_step"] > 0 and out["config"]["workload"] == "stress/prefill16384"
+    assert out["vs_baseline"] is None and out["dtype"] == "bf16"
     roof = out["roofline"]
-    assert roof["bound"] in ("hbm", "mfma") and roof["unit"] in ("GB/s", "TFLOP/s") and roof["peak"] in (8000.0, 2500.0)
+    assert roof["bound"] == "mfma" and roof["unit"] == "TFLOP/s" and roof["peak"] == 2500.0
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9 and 0 < roof["frac"] < 1
+    assert roof["traffic"] is None or roof["traffic"] > 0
     cpu = out["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["unit"] == out["unit"] and cpu["sample"]
+    want = ["mixtral/decode1", "mixtral/decode8", "mixtral/prefill512", "dsv2lite/decode1", "dsv2lite/prefill1024",
+            "qwen2moe/decode4", "qwen2moe/prefill2048", "stress/prefill16384"]
+    assert sorted(out["phases"]) == sorted(want)
+    for name in want:
+        ph = out["phases"][name]
+        assert ph["ms_per_step_p10"] <= ph["ms_per_step"] <= ph["ms_per_step_p90"] and ph["blocks"] == 3
+        for part in ("gate_up", "down", "layer"):
+            assert ph[part]["bound"] in ("hbm", "mfma") and 0 < ph[part]["frac"] < 1.2, (name, part, ph[part])
+    assert out["value"] == out["phases"]["stress/prefill16384"]["tokens_per_s"]
     refused = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                              timeout=120, cwd=root)
     assert refused.returncode != 0 and "ONE GPU" in (refused.stderr + refused.stdout)

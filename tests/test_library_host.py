@@ -107,3 +107,20 @@ def test_workload_shapes_fit_the_kernels(hm):
             assert s.hidden % 64 == 0 and s.ffn % 64 == 0
             for f in s.shared_ffn:
                 assert f % 64 == 0
+
+
+def test_traffic_table_names_kernels_that_exist():
+    """profiles/traffic.json (HBM bytes per launch from the counter runs, copied by bench.py into roofline.traffic)
+    must name kernels that the sources still define."""
+    import json
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    with open(os.path.join(root, "profiles", "traffic.json")) as fh:
+        table = json.load(fh)
+    csrc = os.path.join(root, "paper_2504_05897_amd", "csrc")
+    text = "".join(open(os.path.join(csrc, f)).read() for f in os.listdir(csrc))
+    assert table
+    for key, entry in table.items():
+        assert entry["bytes"] > 0 and re.fullmatch(r"\w+/\w+(\+w4)?", key), key
+        base = entry["kernel"].split("<")[0]
+        assert re.search(r"\b%s\b" % re.escape(base), text), "%s: kernel %s is gone; profile again" % (key, base)
