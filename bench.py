@@ -152,7 +152,7 @@ def main() -> int:
         for li in range(n_layers):
             seed = (5000 + li) if stacked else SEED0[name] + 100 * li
             lay = wl.make_layer(shape, seed, max_T, threads=threads)
-            layers.append(hm.MoELayer(desc, lay.experts, lay.shared, lay.w_router, max_tokens=max_T))
+            layers.append(hm.MoELayer(desc, lay.experts, lay.shared, lay.w_router, max_tokens=max_T, host_copies=False))
             if li:
                 lay.experts, lay.shared = [], []
             host_layers.append(lay)
@@ -301,6 +301,8 @@ def main() -> int:
         del layers, host_layers
         gc.collect()
         torch.cuda.empty_cache()
+        if hasattr(torch._C, "_host_emptyCache"):
+            torch._C._host_emptyCache()        # pinned host memory of the staging leg goes back as well
         return results, staging, setup_s, lay0, n_layers
 
     phases_out, staging_out, setup_out = {}, {}, {}

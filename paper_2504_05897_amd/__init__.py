@@ -384,7 +384,7 @@ class MoELayer:
 
     def __init__(self, desc: LayerDesc, experts: Sequence, shared: Sequence = (), w_router=None,
                  max_tokens: int = 1, device: str = "cuda:0", resident: Optional[Sequence[int]] = None,
-                 fused: bool = True):
+                 fused: bool = True, host_copies: bool = True):
         self.desc = desc
         self.fused = fused          # route+permute in one call, gather fused into the FFN
         self.overlap_shared = fused  # shared-expert FFN on a side stream, next to the routed path
@@ -393,21 +393,26 @@ class MoELayer:
         self.dt = torch_dtype(desc)
         E, S, K, H, F = desc.n_experts, desc.n_slots, desc.top_k, desc.hidden, desc.ffn
         self.slot_bytes = hmoe_slot_bytes(desc)
-        # pinned host copies of the packed experts
+        self.slots = torch.empty(S * self.slot_bytes, dtype=torch.uint8, device=self.dev)
+        self.slot_of = torch.empty(E, dtype=torch.int32, device=self.dev)
+        self.cache = hmoe_cache_create(desc, self.slots, self.slot_of)
+        # pinned host copies of the packed experts: what misses are staged from.  A layer whose cache holds every
+        # expert never stages; with host_copies=False it packs each expert once and writes it into its slot.
+        if not host_copies:
+            assert S == E and resident is None and len(experts) == E, "host_copies=False needs every expert resident"
         self.h_packed: List[torch.Tensor] = [torch.empty(self.slot_bytes, dtype=torch.uint8, pin_memory=True)
-                                             for _ in experts]
+                                             for _ in experts] if host_copies else []
 
         def pack_one(i):
             wg, wu, wd = experts[i]
-            hmoe_pack_expert(desc, np.ascontiguousarray(wg), np.ascontiguousarray(wu), np.ascontiguousarray(wd),
-                             self.h_packed[i])
+            out = self.h_packed[i] if host_copies else torch.empty(self.slot_bytes, dtype=torch.uint8)
+            hmoe_pack_expert(desc, np.ascontiguousarray(wg), np.ascontiguousarray(wu), np.ascontiguousarray(wd), out)
+            if not host_copies:
+                self.slots[i * self.slot_bytes:(i + 1) * self.slot_bytes].copy_(out)
 
         from concurrent.futures import ThreadPoolExecutor
         with ThreadPoolExecutor(max_workers=min(16, max(1, len(experts)))) as pool:   # packing is host-side memcpy work
             list(pool.map(pack_one, range(len(experts))))
-        self.slots = torch.empty(S * self.slot_bytes, dtype=torch.uint8, device=self.dev)
-        self.slot_of = torch.empty(E, dtype=torch.int32, device=self.dev)
-        self.cache = hmoe_cache_create(desc, self.slots, self.slot_of)
         self.copy_stream = torch.cuda.Stream(device=self.dev)
         self.side_stream = torch.cuda.Stream(device=self.dev)
         self.ev_fork = torch.cuda.Event()
@@ -431,7 +436,7 @@ class MoELayer:
             hmoe_cache_stage(self.shared_cache, 0, 0, None)
         self._alloc(max_tokens)
         for s, e in enumerate(range(S) if resident is None else resident):
-            hmoe_cache_stage(self.cache, int(e), s, self.h_packed[int(e)], None, self.copy_stream)
+            hmoe_cache_stage(self.cache, int(e), s, self.h_packed[int(e)] if host_copies else None, None, self.copy_stream)
         torch.cuda.synchronize(self.dev)
         self.last_plan = None
         self.staged_bytes = 0

@@ -14,6 +14,11 @@ store data, or as the source of a vector ALU instruction, e.g. a copy into anoth
 reported.  Reads by the matrix instructions are not checked: the sources tie those to the waits, and the
 compiler places some of them out of line, which a linear scan cannot follow.
 
+Two more findings come out of the same scan.  A vector-memory instruction that the compiler emitted itself
+(outside an inline-assembly block) while a hand-issued one is still queued is reported: it would be one of the
+"younger operations" that every hand-counted wait allows to stay in flight, and the wait would then cover one
+operation less than the source counted.  find_wait_count_errors (below) recounts the waits of the main loops.
+
 Control flow is followed only as far as this: a label that execution cannot fall into (the instruction before
 it is an unconditional branch or ends the program) starts from the queue of the branches seen so far that jump
 to it (the longest of them), or from an empty queue if none was seen -- the compiler lays the alternative code
@@ -38,7 +43,8 @@ def _vregs(operand: str) -> Set[int]:
 
 
 def _scan_kernel(name: str, lines: Iterable[Tuple[int, str]]) -> List[str]:
-    queue: List[Tuple[Set[int], int]] = []   # (destination registers of a hand-issued load or empty, line)
+    # (destination registers of a hand-issued load or empty, line, issued from inline assembly)
+    queue: List[Tuple[Set[int], int, bool]] = []
     found: List[str] = []
     in_asm = False
     jumps = {}            # label -> queues at the branches to it seen so far
@@ -88,7 +94,7 @@ def _scan_kernel(name: str, lines: Iterable[Tuple[int, str]]) -> List[str]:
             # matrix ones (a copy to another register file is the typical case)
             for o in (ops[1:] if has_dest else ops):
                 addresses |= _vregs(o)
-        for dest, issued in queue:
+        for dest, issued, _ in queue:
             if dest & writes:
                 found.append("%s: line %d: %s writes v%s while the load of line %d may be in flight"
                              % (name, no, op, sorted(dest & writes), issued))
@@ -96,7 +102,12 @@ def _scan_kernel(name: str, lines: Iterable[Tuple[int, str]]) -> List[str]:
                 found.append("%s: line %d: %s reads v%s while the load of line %d may be in flight"
                              % (name, no, op, sorted(dest & addresses), issued))
         if is_vmem:
-            queue.append((writes if (is_load and in_asm) else set(), no))
+            if not in_asm:
+                older = [line for _, line, hand in queue if hand]
+                if older:
+                    found.append("%s: line %d: %s was emitted by the compiler while the hand-issued operation of line %d may be in "
+                                 "flight: the hand-counted waits do not count it" % (name, no, op, older[0]))
+            queue.append((writes if (is_load and in_asm) else set(), no, in_asm))
     return found
 
 
@@ -111,6 +122,115 @@ def find_inflight_hazards(asm_text: str) -> List[str]:
         elif line.startswith(".Lfunc_end"):
             if name:
                 found += _scan_kernel(name, lines)
+            name, lines = None, []
+        elif name:
+            lines.append((no, line))
+    return found
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Recount of the hand-counted waits in the main loops.
+#
+# A main loop is the text from a label to the last branch back to it; branches out of it and forward branches
+# inside it are taken as not taken, which gives the steady-state path (every K step present).  The body is
+# walked several times with one queue of outstanding vector-memory operations, as the hardware keeps it, and from
+# the second walk on:
+#   * a matrix instruction may not read a register of a hand-issued load that a wait has not yet retired (the
+#     wait in front of it allowed too many younger operations), and
+#   * at a wait marked "opens an activation stage, ring of SA", every copy into LDS up to and including the stage
+#     that is SA - 3 stages before the one last marked "activation stage issued" must have been retired: with a
+#     ring of SA stages that is the stage the following barrier hands to the matrix instructions.
+def _loops(lines: List[Tuple[int, str]]) -> List[Tuple[int, int]]:
+    labels = {}
+    out = {}
+    for i, (_, raw) in enumerate(lines):
+        text = raw.split(";")[0].strip()
+        if text.endswith(":") and text.startswith(".L"):
+            labels[text[:-1]] = i
+            continue
+        op, _, rest = text.partition(" ")
+        if (op == "s_branch" or op.startswith("s_cbranch")) and rest.strip() in labels:
+            out[labels[rest.strip()]] = i            # the last backward branch to a label closes its loop
+    return sorted(out.items())
+
+
+def _scan_loop(name: str, body: List[Tuple[int, str]], walks: int = 5) -> List[str]:
+    found: List[str] = []
+    seen: Set[str] = set()
+    queue: List[dict] = []
+    stage = 0            # activation stages closed so far ("activation stage issued" marks seen)
+    for walk in range(walks):
+        in_asm = False
+        for no, raw in body:
+            text = raw.strip()
+            if text.startswith(";;#ASMSTART"):
+                in_asm = True
+                continue
+            if text.startswith(";;#ASMEND"):
+                in_asm = False
+                continue
+            if in_asm and "hmoe: activation stage issued" in text:
+                stage += 1
+                continue
+            code, _, comment = text.partition(";")
+            code = code.strip()
+            if not code or code.endswith(":") or code.startswith("."):
+                continue
+            op, _, rest = code.partition(" ")
+            ops = [o.strip() for o in _SPLIT.split(rest) if o.strip()] if rest else []
+            if op == "s_waitcnt":
+                m = re.search(r"vmcnt\((\d+)\)", rest)
+                if not m:
+                    continue
+                n = int(m.group(1))
+                if n < len(queue):
+                    queue = queue[len(queue) - n:] if n else []
+                m = re.search(r"opens an activation stage, ring of (\d+)", comment)
+                if m and walk >= 1:
+                    must_have_landed = stage - 1 - (int(m.group(1)) - 3)
+                    late = [q for q in queue if q["lds"] and q["stage"] <= must_have_landed]
+                    msg = ("%s: line %d: s_waitcnt vmcnt(%d) opens an activation stage while %d of its copies into LDS (first: "
+                           "line %d) may still be in flight" % (name, no, n, len(late), late[0]["line"] if late else 0))
+                    if late and msg not in seen:
+                        seen.add(msg)
+                        found.append(msg)
+                continue
+            if op.startswith("v_mfma") and walk >= 1:
+                reads: Set[int] = set()
+                for o in ops[1:]:
+                    reads |= _vregs(o)
+                for q in queue:
+                    if q["dest"] & reads:
+                        msg = ("%s: line %d: %s reads v%s before a wait has retired the hand-issued load of line %d"
+                               % (name, no, op, sorted(q["dest"] & reads), q["line"]))
+                        if msg not in seen:
+                            seen.add(msg)
+                            found.append(msg)
+                continue
+            if op.startswith(("global_", "flat_", "buffer_", "scratch_")):
+                is_lds = "_lds" in op
+                is_load = "_load" in op and not is_lds
+                queue.append({"dest": _vregs(ops[0]) if (is_load and in_asm and ops) else set(), "line": no,
+                              "lds": is_lds and in_asm, "stage": stage})
+    return found
+
+
+def find_wait_count_errors(asm_text: str) -> List[str]:
+    """Recounts the hand-counted waits of every main loop that issues loads from inline assembly; one message per
+    finding."""
+    found: List[str] = []
+    name, lines = None, []
+    for no, line in enumerate(asm_text.splitlines(), 1):
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            name, lines = m.group(1), []
+        elif line.startswith(".Lfunc_end"):
+            if name:
+                for first, last in _loops(lines):
+                    body = lines[first:last + 1]
+                    text = "\n".join(raw for _, raw in body)
+                    if "#ASMSTART" in text and "global_load" in text:
+                        found += _scan_loop(name, body)
             name, lines = None, []
         elif name:
             lines.append((no, line))

@@ -70,13 +70,17 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         logs = list(pool.map(compile_one, jobs))[len(listings):]
     # No register of a load issued from inline assembly may be written, or used as an address, before the wait
     # that covers the load (see asm_check.py).
+    # Nor may the compiler put a vector-memory instruction of its own between them, and the hand-counted waits of the
+    # main loops are recounted from the listing.
     hazards = []
     for path in listings:
         with open(path) as f:
-            hazards += asm_check.find_inflight_hazards(f.read())
+            text = f.read()
+        hazards += asm_check.find_inflight_hazards(text)
+        hazards += asm_check.find_wait_count_errors(text)
         os.remove(path)
     if hazards:
-        raise RuntimeError("registers reused while a hand-issued load is in flight:\n  " + "\n  ".join(hazards[:20]))
+        raise RuntimeError("hand-issued loads: the device assembly breaks the rules they rely on:\n  " + "\n  ".join(hazards[:20]))
     # No kernel of this library may spill registers.  The prefill kernels issue their loads by hand and count the
     # outstanding ones themselves; the compiler treats the destination of such a load as written at once, so under
     # register pressure it may spill and reuse that register before the data lands (observed: a late load then

@@ -39,11 +39,19 @@ __device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_ba
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(gptr), "s"(__builtin_amdgcn_readfirstlane(lds_base))
-               : "memory");
+               : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// The two marks below put no instruction into the kernel; they are comments in the device assembly that the
+// build's listing check (asm_check.py) reads to recount the hand-counted waits: where the copies of one activation
+// stage end, and which wait opens a stage of a ring of SA.
+__device__ __forceinline__ void mark_stage_issued() { asm volatile("; hmoe: activation stage issued" ::: "memory"); }
+template <int N, int SA>
+__device__ __forceinline__ void wait_vmcnt_opens_stage() {
+  asm volatile("s_waitcnt vmcnt(%0) ; hmoe: opens an activation stage, ring of %1" ::"n"(N), "n"(SA) : "memory");
 }
 // Workgroup barrier that the compiler may not move LDS accesses across.  (No fence instruction:
 // the waits that make the data visible are issued explicitly by the caller.)
@@ -165,6 +173,7 @@ struct StreamTile {
       for (int op = 0; op < A_OPS; ++op)
         if (op >= A_OPS * piece / KK && op < A_OPS * (piece + 1) / KK)
           load_to_lds_16(a_src[op] + koff, base + (uint32_t)((op * NWV + wave) * 64) * 16);
+      if (piece == KK - 1) mark_stage_issued();
     };
 
     u32x4 ring[DB][FN];
@@ -210,7 +219,7 @@ struct StreamTile {
           for (int kk = 0; kk < KK; ++kk) {
             if (kk == KK - 1) {
               // open step tt+1: its activation tile has landed once at most N_A younger operations are out
-              wait_vmcnt<N_A>();
+              wait_vmcnt_opens_stage<N_A, SA>();
               __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragments are in registers
               block_barrier();
               if constexpr (FN == 2) read_a((kk + 1) & 1, next_stage, 0);

@@ -46,9 +46,10 @@ def test_register_of_a_load_in_flight():
     # a copy of a destination into the accumulation registers before the wait: reported
     copy = listing(HAND + "\tv_accvgpr_write_b32 a4, v11\n\ts_waitcnt vmcnt(0)\n")
     assert len(check(copy)) == 1 and "v_accvgpr_write_b32 reads v[11]" in check(copy)[0]
-    # an LDS read landing in the destination, a store of it: reported
+    # an LDS read landing in the destination, a store of it: reported (the store also as a memory instruction of the
+    # compiler's own under a hand-issued load)
     lds = listing(HAND + "\tds_read_b128 v[12:15], v7\n\tglobal_store_dword v[4:5], v11, off\n")
-    assert len(check(lds)) == 2
+    assert len(check(lds)) == 3
 
 
 def test_labels_without_fall_through():
@@ -75,3 +76,67 @@ def test_private_memory_remarks():
                "a.hip:9:0: remark:     ScratchSize [bytes/lane]: 64 [-Rpass-analysis=kernel-resource-usage]\n")
     assert build.kernels_with_scratch(remarks) == ["_Z1bv"]
     assert build.kernels_with_scratch(remarks.replace(": 64", ": 0")) == []
+
+
+def test_compiler_emitted_memory_instruction_under_hand_issued_loads():
+    """A vector-memory instruction the compiler emitted itself while a hand-issued one is in flight would be one more
+    'younger operation' than the hand-counted waits allow for: reported.  Before the first hand-issued operation and
+    after the wait that retires the last one, the compiler's own loads and stores are fine."""
+    check = _load("asm_check").find_inflight_hazards
+    own = "\tglobal_load_dword v9, v[2:3], off\n"
+    assert check(listing(own + "\ts_waitcnt vmcnt(0)\n" + HAND + "\ts_waitcnt vmcnt(0)\n\tglobal_store_dwordx4 v[4:5], v[10:13], off\n")) == []
+    found = check(listing(HAND + own + "\ts_waitcnt vmcnt(0)\n"))
+    assert len(found) == 1 and "global_load_dword was emitted by the compiler" in found[0]
+    # a copy into LDS issued by hand counts as in flight too; a store under it is reported
+    lds = "\t;;#ASMSTART\n\ts_mov_b32 m0, s31\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v[128:129], off\n\t;;#ASMEND\n"
+    found = check(listing(lds + "\tglobal_store_dword v[4:5], v9, off\n\ts_waitcnt vmcnt(0)\n"))
+    assert len(found) == 1 and "global_store_dword was emitted by the compiler" in found[0]
+    # the compiler's load is older than the hand-issued one: every wait that covers the latter covers it as well
+    assert check(listing(own + HAND + "\ts_waitcnt vmcnt(0)\n")) == []
+
+
+def _loop(body):
+    return listing("\ts_mov_b32 s0, 0\n.LBB0_1:\n" + body + "\ts_cbranch_scc1 .LBB0_1\n\ts_endpgm\n")
+
+
+def _hand(text):
+    return "\t;;#ASMSTART\n\t" + text + "\n\t;;#ASMEND\n"
+
+
+def test_wait_recount_ring_of_weight_tiles():
+    """Main loop with a ring of two weight registers, each reloaded right after its use: the tile multiplied in a
+    substep was requested two substeps earlier, one younger load may stay in flight -> vmcnt(1).  vmcnt(2) lets
+    the matrix instruction read a register whose load may not have landed."""
+    check = _load("asm_check").find_wait_count_errors
+
+    def body(n):
+        return (_hand("s_waitcnt vmcnt(%d)" % n) + "\tv_mfma_f32_32x32x16_bf16 v[50:65], v[30:33], v[10:13], v[50:65]\n"
+                + _hand("global_load_dwordx4 v[10:13], v[2:3], off nt")
+                + _hand("s_waitcnt vmcnt(%d)" % n) + "\tv_mfma_f32_32x32x16_bf16 v[50:65], v[30:33], v[14:17], v[50:65]\n"
+                + _hand("global_load_dwordx4 v[14:17], v[4:5], off nt"))
+    assert check(_loop(body(1))) == []
+    assert check(_loop(body(0))) == []           # waits for more than needed: slow, not wrong
+    found = check(_loop(body(2)))
+    assert found and "reads v[10, 11, 12, 13] before a wait has retired the hand-issued load" in found[0]
+
+
+def test_wait_recount_activation_stages():
+    """Main loop of one K step per walk: a weight load, two copies into LDS that make up a stage (closed by the
+    'activation stage issued' mark), and the wait that opens a stage.  With a ring of 4 the stage to open was closed
+    two marks before the last one at that point: at the wait the youngest operations are the 3 of the previous step and
+    the weight load of this one, so vmcnt(4) is exact, vmcnt(5) leaves one of the stage's copies in flight; with a
+    ring of 3 the stage to open is the one closed last and vmcnt(1) is the most that is allowed."""
+    check = _load("asm_check").find_wait_count_errors
+    copy = _hand("s_mov_b32 m0, s31\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v[128:129], off")
+
+    def body(n, ring):
+        return (_hand("global_load_dwordx4 v[10:13], v[2:3], off nt")
+                + _hand("s_waitcnt vmcnt(%d) ; hmoe: opens an activation stage, ring of %d" % (n, ring)) + "\ts_barrier\n"
+                + copy + copy + _hand("; hmoe: activation stage issued"))
+    assert check(_loop(body(4, 4))) == []
+    found = check(_loop(body(5, 4)))
+    assert len(found) == 1 and "opens an activation stage while 1 of its copies into LDS" in found[0]
+    assert check(_loop(body(1, 3))) == []
+    assert check(_loop(body(2, 3))) != []
+    # a loop without hand-issued operations is not looked at
+    assert check(_loop("\tglobal_load_dword v9, v[2:3], off\n\ts_waitcnt vmcnt(0)\n")) == []
