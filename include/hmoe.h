@@ -141,6 +141,24 @@ int32_t hmoe_permute(const hmoe_layer_desc* desc, const int32_t* topk_idx, int32
                      int32_t* h_counts_pinned, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * hmoe_permute for callers that cannot allocate device memory and therefore have no workspace to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and the
+ * same results, bit for bit, but the scratch memory (per-block expert counts) is a static device array of
+ * HMOE_PERMUTE_STATIC_BYTES inside the library, which every GPU the library runs on holds until the process
+ * ends.  The call allocates and frees nothing (its first call on a device looks the array's address up).
+ *   Limit: hmoe_permute_workspace_bytes(desc, T) <= HMOE_PERMUTE_STATIC_BYTES, i.e. about
+ *   (T * K / 1024 + 2) * E * 4 bytes; beyond it -> HMOE_ERR_WORKSPACE (text via hmoe_last_error), nothing enqueued.
+ *   All calls on one GPU share the one array, which keeps the previous call's contents (nothing in it needs to
+ *   start at zero): calls that may run at the same time on one GPU -- different streams without an ordering
+ *   between them -- race and must use hmoe_permute with workspaces of their own.  The current device must be
+ *   the device of `stream`.
+ */
+#define HMOE_PERMUTE_STATIC_BYTES (1 << 20)
+int32_t hmoe_permute_static(const hmoe_layer_desc* desc, const int32_t* topk_idx, int32_t T, const void* x,
+                            void* x_perm, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
+                            int32_t* h_counts_pinned, void* stream);
+
+/*
  * hmoe_route followed by hmoe_permute (without the row gather; see hmoe_expert_ffn_grouped_gather)
  * as one call.  For small batches (T <= 64 and T*K <= 1024: every decode shape) both run in a single
  * one-block launch; larger batches run the two calls above.  Arguments and results as in those calls.

@@ -36,7 +36,7 @@ HMOE_FFN_AUTO, HMOE_FFN_REFERENCE, HMOE_FFN_SKINNY, HMOE_FFN_TILED = 0, 1, 2, 3
 # every symbol include/hmoe.h declares
 EXPORTS = [
     "hmoe_status_string", "hmoe_last_error", "hmoe_router_logits", "hmoe_route",
-    "hmoe_permute_workspace_bytes", "hmoe_permute", "hmoe_slot_bytes", "hmoe_pack_expert",
+    "hmoe_permute_workspace_bytes", "hmoe_permute", "hmoe_permute_static", "hmoe_slot_bytes", "hmoe_pack_expert",
     "hmoe_cache_create", "hmoe_cache_destroy", "hmoe_cache_lookup", "hmoe_cache_occupant",
     "hmoe_cache_evict", "hmoe_cache_pin_slot", "hmoe_cache_stage", "hmoe_cache_plan",
     "hmoe_ffn_workspace_bytes", "hmoe_expert_ffn_grouped", "hmoe_expert_ffn_grouped_gather", "hmoe_route_permute",
@@ -89,6 +89,7 @@ def _load() -> ctypes.CDLL:
     lib.hmoe_permute_workspace_bytes.restype = sz
     lib.hmoe_permute_workspace_bytes.argtypes = [dp, i32]
     lib.hmoe_permute.argtypes = [dp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.hmoe_permute_static.argtypes = [dp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.hmoe_slot_bytes.restype = sz
     lib.hmoe_slot_bytes.argtypes = [dp]
     lib.hmoe_pack_expert.argtypes = [dp, vp, vp, vp, vp]
@@ -185,6 +186,18 @@ def hmoe_permute(desc, topk_idx, T, x, x_perm, expert_offsets, perm, inv_perm, h
     _check(_lib.hmoe_permute(ctypes.byref(desc), _ptr(topk_idx), T, _ptr(x), _ptr(x_perm), _ptr(expert_offsets),
                              _ptr(perm), _ptr(inv_perm), _ptr(h_counts_pinned), _ptr(workspace), workspace_bytes,
                              _stream(stream)), "hmoe_permute")
+
+
+HMOE_PERMUTE_STATIC_BYTES = 1 << 20
+
+
+def hmoe_permute_static(desc, topk_idx, T, x, x_perm, expert_offsets, perm, inv_perm, h_counts_pinned, stream=None):
+    """hmoe_permute without a caller workspace (the library's static scratch array); allocates nothing."""
+    status = _lib.hmoe_permute_static(ctypes.byref(desc), _ptr(topk_idx), T, _ptr(x), _ptr(x_perm), _ptr(expert_offsets),
+                                      _ptr(perm), _ptr(inv_perm), _ptr(h_counts_pinned), _stream(stream))
+    if status == HMOE_ERR_WORKSPACE:
+        raise HmoeError(status, "hmoe_permute_static: " + _lib.hmoe_last_error().decode())
+    _check(status, "hmoe_permute_static")
 
 
 def hmoe_slot_bytes(desc) -> int:

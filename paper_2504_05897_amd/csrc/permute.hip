@@ -10,6 +10,8 @@
 //                  ballots (same-key mask), waves and steps are ordered by per-wave LDS bases
 // For A <= 1024 (every decode shape) one block does all three in one launch.
 //   4. gather      x_perm[p] = x[perm[p] / K], 16 bytes per lane
+#include <mutex>
+
 #include "route_body.h"
 #include "router_body.h"
 
@@ -321,9 +323,10 @@ extern "C" size_t hmoe_permute_workspace_bytes(const hmoe_layer_desc* desc, int3
   return ((size_t)hmoe::n_chunks(A) + 1) * desc->n_experts * sizeof(int32_t) + 256;
 }
 
-extern "C" int32_t hmoe_permute(const hmoe_layer_desc* desc, const int32_t* topk_idx, int32_t T, const void* x,
-                                void* x_perm, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
-                                int32_t* h_counts_pinned, void* workspace, size_t workspace_bytes, void* stream) {
+// hmoe_permute and hmoe_permute_static share this body; they differ in where the scratch memory comes from.
+static int32_t permute_with_workspace(const hmoe_layer_desc* desc, const int32_t* topk_idx, int32_t T, const void* x,
+                                      void* x_perm, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
+                                      int32_t* h_counts_pinned, void* workspace, size_t workspace_bytes, void* stream) {
   using namespace hmoe;
   int rc = check_desc(desc);
   if (rc != HMOE_OK) return rc;
@@ -365,6 +368,61 @@ extern "C" int32_t hmoe_permute(const hmoe_layer_desc* desc, const int32_t* topk
     HMOE_HIP(hipGetLastError());
   }
   return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_permute(const hmoe_layer_desc* desc, const int32_t* topk_idx, int32_t T, const void* x,
+                                void* x_perm, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
+                                int32_t* h_counts_pinned, void* workspace, size_t workspace_bytes, void* stream) {
+  return permute_with_workspace(desc, topk_idx, T, x, x_perm, expert_offsets, perm, inv_perm, h_counts_pinned, workspace,
+                                workspace_bytes, stream);
+}
+
+// ---- hmoe_permute without a workspace from the caller ------------------------------------------------------
+// The per-block counts live in a file-scope device array instead.  In host code the array's name is only a
+// stand-in: the address the kernels can use comes from hipGetSymbolAddress, once per device (each GPU holds its
+// own copy of the array at its own address), and that pointer is what every launch and copy below is given.
+static __device__ __align__(256) unsigned char scratch[HMOE_PERMUTE_STATIC_BYTES];
+
+namespace hmoe {
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device, nullptr = not looked up yet
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+static int32_t static_scratch(void** out) {
+  int dev = -1;
+  HMOE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return set_error_text(HMOE_ERR_UNSUPPORTED, "hmoe_permute_static: device index out of range");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    HMOE_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return set_error_text(HMOE_ERR_HIP, "hmoe_permute_static: hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return HMOE_OK;
+}
+}  // namespace hmoe
+
+extern "C" int32_t hmoe_permute_static(const hmoe_layer_desc* desc, const int32_t* topk_idx, int32_t T, const void* x,
+                                       void* x_perm, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
+                                       int32_t* h_counts_pinned, void* stream) {
+  using namespace hmoe;
+  int rc = check_desc(desc);
+  if (rc != HMOE_OK) return rc;
+  if (T < 0) return HMOE_ERR_INVALID_ARG;
+  const size_t need = hmoe_permute_workspace_bytes(desc, T);
+  if (need == 0 || need > (size_t)HMOE_PERMUTE_STATIC_BYTES)
+    return set_error_text(HMOE_ERR_WORKSPACE, "hmoe_permute_static: T * top_k assignments over n_experts experts need more than the "
+                                              "library's static scratch array (HMOE_PERMUTE_STATIC_BYTES); use hmoe_permute");
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != HMOE_OK) return rc;
+  // Nothing in the scratch memory has to start at zero: the histogram kernel writes every per-block count before
+  // the scan reads it, and the row of per-expert totals is written in full by the scan (or the one-block kernel).
+  return permute_with_workspace(desc, topk_idx, T, x, x_perm, expert_offsets, perm, inv_perm, h_counts_pinned, ws,
+                                (size_t)HMOE_PERMUTE_STATIC_BYTES, stream);
 }
 
 extern "C" int32_t hmoe_route_permute(const hmoe_layer_desc* desc, const float* logits, int32_t T, int32_t* topk_idx,
