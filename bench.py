@@ -199,15 +199,16 @@ def main() -> int:
             # that each pair times one kernel alone (routed call first, then the shared experts' call)
             probe_steps = min(args.steps, 20)
             pairs_per_step = (n_layers if stacked else 1) * (4 if Fs else 2)
+            saved = [(l.overlap_shared, l.merge_shared, l.merge_combine) for l in layers]
             for l in layers:
-                l.overlap_shared = l.merge_shared = False
+                l.overlap_shared = l.merge_shared = l.merge_combine = False
             hm.hmoe_probe_arm(probe_steps * pairs_per_step)
             for i in range(probe_steps):
                 one_step(i)
             torch.cuda.synchronize()
             ms = hm.hmoe_probe_read(probe_steps * pairs_per_step)
-            for l in layers:
-                l.overlap_shared = l.merge_shared = l.fused
+            for l, keep in zip(layers, saved):
+                l.overlap_shared, l.merge_shared, l.merge_combine = keep
             per_call = 4 if Fs else 2
             kern = {"gate_up": ms[0::per_call], "down": ms[1::per_call]}
             if Fs:

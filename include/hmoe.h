@@ -222,6 +222,9 @@ int32_t hmoe_cache_pin_slot(hmoe_cache* cache, int32_t slot, int32_t pinned);
  * h_packed_pinned must stay valid until the copy has completed.
  * h_packed_pinned == NULL marks the slot's current device contents as expert_id without
  * copying (for weights written into slot storage by the caller).
+ * HIP graphs: hmoe_cache_stage itself must not be called on a capturing stream.  Once an FFN call over this cache
+ * has been captured, the library cannot know when a replay reads a slot; every later copy into a slot therefore
+ * waits for all work enqueued on compute_stream so far (replays included) instead of for the slot's last reader.
  */
 int32_t hmoe_cache_stage(hmoe_cache* cache, int32_t expert_id, int32_t slot,
                          const void* h_packed_pinned, void* compute_stream, void* copy_stream);
@@ -326,6 +329,50 @@ int32_t hmoe_expert_ffn_grouped_with_shared(
  */
 int32_t hmoe_combine(const hmoe_layer_desc* desc, const void* o_perm, const int32_t* inv_perm,
                      const float* topk_w, const void* o_shared, int32_t T, void* y, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Grouped expert FFN over a cache that holds fewer experts than the call needs (on-demand loading of the missing
+ * experts over PCIe, Section I; transfer and compute overlapped on two streams, Section V): one call plans the
+ * replacement (hmoe_cache_plan on h_counts_pinned), and then, wave by wave, stages the wave's missing experts
+ * (hmoe_cache_stage from h_packed_pinned[e], on copy_stream) and runs the FFN of the wave's experts
+ * (hmoe_expert_ffn_grouped_gather when perm is given, else hmoe_expert_ffn_grouped with x as x_perm) on
+ * compute_stream.  A copy waits only for the last FFN call that read its slot, so the copies of wave w + 1 run under
+ * the FFN of wave w wherever they do not replace an expert that wave computes.
+ *   h_counts_pinned [E] HOST: per-expert rows as delivered by hmoe_permute / hmoe_route_permute on compute_stream;
+ *       the call SYNCHRONISES compute_stream once before it reads them.
+ *   h_packed_pinned [E] HOST array of HOST pointers: expert e's packed blob in pinned memory (may be NULL for
+ *       experts that never have to be staged; a missing expert without a blob -> HMOE_ERR_INVALID_ARG).
+ *   h_wave, h_slot, h_victim [E], n_waves: the plan, as written by hmoe_cache_plan.  staged_bytes (or NULL): bytes copied.
+ * Other arguments, results and errors as in the calls named above.
+ */
+int32_t hmoe_expert_ffn_staged(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x, const int32_t* perm,
+                               const int32_t* expert_offsets, int32_t A, const int32_t* h_counts_pinned,
+                               const void* const* h_packed_pinned, void* o_perm, void* workspace, size_t workspace_bytes,
+                               int32_t path, void* compute_stream, void* copy_stream, int32_t* h_wave, int32_t* h_slot,
+                               int32_t* h_victim, int32_t* n_waves, uint64_t* staged_bytes);
+
+/* ------------------------------------------------------------------------------------
+ * Expert FFN and the sum of Eq. (1) as one call, for layers whose kernels take a few microseconds each:
+ *     hmoe_expert_ffn_grouped_with_shared(desc, cache, x, perm, expert_offsets, T * K, NULL, 0, o_perm, ...,
+ *                                         shared_desc, shared_cache, shared_offsets, T, o_shared, ...)
+ *       (hmoe_expert_ffn_grouped_gather when shared_desc is NULL: a layer without shared experts)
+ *     hmoe_combine(desc, o_perm, inv_perm, topk_w, o_shared, T, y)
+ * with the same bits in o_perm, o_shared and y as those calls.  When the FFN runs as the decode kernel pair (bf16,
+ * path resolves to HMOE_FFN_SKINNY for both parts) and every routed expert is resident, the sum is computed inside
+ * the down projection's launch: a block that has stored its piece of o_perm / o_shared draws a ticket from the
+ * counter of its column block in `sync`, and the block that draws the last ticket adds up those columns for every
+ * token, in the order of hmoe_combine.  No block waits for another, and the result does not depend on which block is
+ * last.  Otherwise the calls above run one after the other.
+ *   sync: hmoe_ffn_combine_sync_bytes(desc) bytes of device memory that the CALLER ZEROES ONCE (before the first call
+ *         that uses it); every call leaves it zero.  Calls that may run at the same time need buffers of their own.
+ * Errors as in the calls above; nothing is enqueued when an argument is rejected.
+ */
+size_t hmoe_ffn_combine_sync_bytes(const hmoe_layer_desc* desc);
+int32_t hmoe_expert_ffn_combine(
+    const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x, const int32_t* perm, const int32_t* inv_perm,
+    const float* topk_w, const int32_t* expert_offsets, int32_t T, void* o_perm, void* workspace, size_t workspace_bytes,
+    const hmoe_layer_desc* shared_desc, hmoe_cache* shared_cache, const int32_t* shared_offsets, void* o_shared,
+    void* shared_workspace, size_t shared_workspace_bytes, void* y, void* sync, size_t sync_bytes, int32_t path, void* stream);
 
 /* ------------------------------------------------------------------------------------
  * Hybrid CPU-GPU scheduling simulation (Section IV-B).  HOST ONLY: no device work, no stream.

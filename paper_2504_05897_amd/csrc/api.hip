@@ -231,6 +231,7 @@ extern "C" int32_t hmoe_cache_create(const hmoe_layer_desc* desc, void* slot_sto
   c->pinned.assign(desc->n_slots, 0);
   c->use_seq = 0;
   c->track_reads = desc->n_slots < desc->n_experts;
+  c->reads_in_graphs = false;
   c->slot_last_read.assign(desc->n_slots, 0);
   c->ready_ev.assign(desc->n_slots, nullptr);
   for (auto& e : c->use_ev) e = nullptr;
@@ -311,8 +312,9 @@ extern "C" int32_t hmoe_cache_stage(hmoe_cache* c, int32_t expert_id, int32_t sl
   const int e_old = c->expert_in[slot] == expert_id ? -1 : c->expert_in[slot];
   if (h_packed_pinned) {
     // the copy may overwrite the slot only after the last FFN call that could read it
-    if (!c->track_reads) {
-      // reads were not tracked so far: order the copy after everything enqueued on compute
+    if (!c->track_reads || c->reads_in_graphs) {
+      // reads were not tracked so far, or some of them sit in captured graphs whose replays are not tracked: order the
+      // copy after everything enqueued on compute
       HMOE_HIP(hipEventRecord(c->fence_ev, comp));
       HMOE_HIP(hipStreamWaitEvent(copy, c->fence_ev, 0));
       c->track_reads = true;
@@ -482,6 +484,14 @@ static int32_t ffn_launch(const FfnArgs& a, int32_t path) {
 // remembers, per slot, the last call that read it, so that a later copy into the slot can wait for it
 static int32_t ffn_record_reads(hmoe_cache* cache, const FfnArgs& a) {
   if (!cache->track_reads) return HMOE_OK;
+  // Under stream capture an event record becomes a node of the graph: it says nothing about when a replay reads the
+  // slots.  From then on a copy into a slot is ordered after everything enqueued on the compute stream instead.
+  hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+  HMOE_HIP(hipStreamIsCapturing(a.stream, &capturing));
+  if (capturing != hipStreamCaptureStatusNone) {
+    cache->reads_in_graphs = true;
+    return HMOE_OK;
+  }
   const uint64_t seq = ++cache->use_seq;
   HMOE_HIP(hipEventRecord(cache->use_ev[seq % hmoe_cache::RING], a.stream));
   for (int e = 0; e < cache->desc.n_experts; ++e)
@@ -550,5 +560,106 @@ extern "C" int32_t hmoe_expert_ffn_grouped_with_shared(
   }
   if (!skip_routed && (rc = ffn_record_reads(cache, routed)) != HMOE_OK) return rc;
   if (!skip_dense && (rc = ffn_record_reads(shared_cache, dense)) != HMOE_OK) return rc;
+  return HMOE_OK;
+}
+
+extern "C" size_t hmoe_ffn_combine_sync_bytes(const hmoe_layer_desc* desc) {
+  if (check_desc(desc) != HMOE_OK) return 0;
+  return (((size_t)desc->hidden / TILE_N + 1) * sizeof(unsigned int) + 255) & ~(size_t)255;
+}
+
+extern "C" int32_t hmoe_expert_ffn_combine(
+    const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x, const int32_t* perm, const int32_t* inv_perm,
+    const float* topk_w, const int32_t* expert_offsets, int32_t T, void* o_perm, void* workspace, size_t workspace_bytes,
+    const hmoe_layer_desc* shared_desc, hmoe_cache* shared_cache, const int32_t* shared_offsets, void* o_shared,
+    void* shared_workspace, size_t shared_workspace_bytes, void* y, void* sync, size_t sync_bytes, int32_t path, void* stream) {
+  int rc = check_desc(desc);
+  if (rc != HMOE_OK) return rc;
+  if (T < 0) return HMOE_ERR_INVALID_ARG;
+  if (T == 0) return HMOE_OK;
+  const int32_t A = T * desc->top_k;
+  if (!perm || !inv_perm || !topk_w || !y || !aligned16(y)) return HMOE_ERR_INVALID_ARG;
+  if (shared_desc && (shared_desc->n_experts != 1 || shared_desc->n_slots != 1 || shared_desc->top_k != 1 ||
+                      shared_desc->hidden != desc->hidden || shared_desc->dtype != desc->dtype || !o_shared))
+    return HMOE_ERR_INVALID_ARG;
+  if (!sync || sync_bytes < hmoe_ffn_combine_sync_bytes(desc) || (reinterpret_cast<uintptr_t>(sync) & 3u)) return HMOE_ERR_WORKSPACE;
+  FfnArgs routed, dense;
+  bool skip_routed = false, skip_dense = true;
+  int32_t path_routed = path, path_dense = path;
+  rc = ffn_prepare(desc, cache, x, perm, expert_offsets, A, nullptr, 0, o_perm, workspace, workspace_bytes, &path_routed, stream,
+                   &routed, &skip_routed);
+  if (rc != HMOE_OK) return rc;
+  if (shared_desc) {
+    rc = ffn_prepare(shared_desc, shared_cache, x, nullptr, shared_offsets, T, nullptr, 0, o_shared, shared_workspace,
+                     shared_workspace_bytes, &path_dense, stream, &dense, &skip_dense);
+    if (rc != HMOE_OK) return rc;
+    if (shared_cache->slot_of[0] < 0) return HMOE_ERR_NOT_RESIDENT;
+  }
+  // The sum runs inside the down projection's launch when the FFN is the decode kernel pair and every routed expert
+  // is resident (each expert with rows then stores its rows in this call, and at least one block draws every ticket).
+  bool all_resident = true;
+  for (int e = 0; e < desc->n_experts; ++e) all_resident = all_resident && cache->slot_of[e] >= 0;
+  const bool fused = desc->dtype == HMOE_BF16 && path_routed == HMOE_FFN_SKINNY && (!shared_desc || path_dense == HMOE_FFN_SKINNY) &&
+                     all_resident && desc->hidden % 8 == 0;
+  if (!fused) {
+    if ((rc = ffn_launch(routed, path_routed)) != HMOE_OK) return rc;
+    if (shared_desc && (rc = ffn_launch(dense, path_dense)) != HMOE_OK) return rc;
+    if ((rc = ffn_record_reads(cache, routed)) != HMOE_OK) return rc;
+    if (shared_desc && (rc = ffn_record_reads(shared_cache, dense)) != HMOE_OK) return rc;
+    return hmoe_combine(desc, o_perm, inv_perm, topk_w, shared_desc ? o_shared : nullptr, T, y, stream);
+  }
+  CombineArgs cb;
+  cb.inv_perm = inv_perm;
+  cb.topk_w = topk_w;
+  cb.y = y;
+  cb.tickets = (unsigned int*)sync;
+  cb.n_tokens = T;
+  if (shared_desc) dense.slots = shared_cache->slots + (size_t)shared_cache->slot_of[0] * shared_cache->slot_bytes;
+  rc = launch_ffn_skinny(routed, shared_desc ? &dense : nullptr, &cb);
+  if (rc != HMOE_OK) return rc;
+  if ((rc = ffn_record_reads(cache, routed)) != HMOE_OK) return rc;
+  if (shared_desc && (rc = ffn_record_reads(shared_cache, dense)) != HMOE_OK) return rc;
+  return HMOE_OK;
+}
+
+extern "C" int32_t hmoe_expert_ffn_staged(const hmoe_layer_desc* desc, hmoe_cache* cache, const void* x, const int32_t* perm,
+                                          const int32_t* expert_offsets, int32_t A, const int32_t* h_counts_pinned,
+                                          const void* const* h_packed_pinned, void* o_perm, void* workspace,
+                                          size_t workspace_bytes, int32_t path, void* compute_stream, void* copy_stream,
+                                          int32_t* h_wave, int32_t* h_slot, int32_t* h_victim, int32_t* n_waves,
+                                          uint64_t* staged_bytes) {
+  int rc = check_ffn_shape(desc);
+  if (rc != HMOE_OK) return rc;
+  if (!cache || !h_counts_pinned || !h_packed_pinned || !h_wave || !h_slot || !h_victim || !n_waves) return HMOE_ERR_INVALID_ARG;
+  if (memcmp(desc, &cache->desc, sizeof(*desc)) != 0 || A < 0) return HMOE_ERR_INVALID_ARG;
+  // the plan needs the per-expert loads on the host: wait for whatever delivers them
+  HMOE_HIP(hipStreamSynchronize((hipStream_t)compute_stream));
+  rc = hmoe_cache_plan(cache, h_counts_pinned, h_wave, h_slot, h_victim, n_waves);
+  if (rc != HMOE_OK) return rc;
+  const int E = desc->n_experts;
+  for (int e = 0; e < E; ++e)
+    if (h_wave[e] > 0 && !h_packed_pinned[e]) return HMOE_ERR_INVALID_ARG;
+  std::vector<int32_t> members;
+  uint64_t staged = 0;
+  for (int w = 0; w < *n_waves; ++w) {
+    members.clear();
+    for (int e = 0; e < E; ++e)
+      if (h_wave[e] == w) members.push_back(e);
+    if (w > 0) {
+      // the copies of a wave go out before its FFN call: each waits on the copy stream for the last call that read its
+      // slot only, so it runs under the FFN of earlier waves wherever the slot is not one they read
+      for (int e : members) {
+        rc = hmoe_cache_stage(cache, e, h_slot[e], h_packed_pinned[e], compute_stream, copy_stream);
+        if (rc != HMOE_OK) return rc;
+        staged += cache->slot_bytes;
+      }
+    }
+    if (!members.empty()) {
+      rc = ffn_grouped(desc, cache, x, perm, expert_offsets, A, members.data(), (int32_t)members.size(), o_perm, workspace,
+                       workspace_bytes, path, compute_stream);
+      if (rc != HMOE_OK) return rc;
+    }
+  }
+  if (staged_bytes) *staged_bytes = staged;
   return HMOE_OK;
 }

@@ -134,8 +134,16 @@ struct FfnArgs {
   void* h = nullptr;                  // workspace [A, F]
   hipStream_t stream = nullptr;
 };
+// the sum of Eq. (1) computed inside the down projection's launch (decode batches)
+struct CombineArgs {
+  const int32_t* inv_perm = nullptr;
+  const float* topk_w = nullptr;
+  void* y = nullptr;
+  unsigned int* tickets = nullptr;   // device counters, zero before and after the call
+  int32_t n_tokens = 0;
+};
 int launch_ffn_reference(const FfnArgs& a);
-int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense = nullptr);
+int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense = nullptr, const CombineArgs* combine = nullptr);
 int launch_ffn_tiled(const FfnArgs& a);
 int launch_ffn_skinny_w4(const FfnArgs& a);
 int launch_ffn_tiled_w4(const FfnArgs& a);
@@ -163,6 +171,7 @@ struct hmoe_cache {
   hipEvent_t use_ev[RING];
   uint64_t use_seq;
   bool track_reads;
+  bool reads_in_graphs;                  // an FFN call over this cache was captured into a HIP graph
   std::vector<uint64_t> slot_last_read;  // [S], 0 = never
   std::vector<hipEvent_t> ready_ev;      // [S]
   hipEvent_t fence_ev;

@@ -38,6 +38,22 @@ struct SkinnyShared {
   int ffn, rows, grid_rows;
 };
 
+// The weighted sum of Eq. (1) inside the down projection's launch (decode batches).  Every block that has stored
+// its piece of o_perm / o_shared (device-scope stores) draws a ticket from the counter of its column block; the block
+// that draws the last one finds all pieces of those columns complete and adds them up, for every token, in the order of hmoe_combine
+// (j ascending, then the shared term; the bf16 values that were stored), so y has the bits of the separate call.
+// No block waits for another.  The counters are zero when the launch starts and the last block leaves them zero.
+// on == 0: none.
+struct SkinnyCombine {
+  const int32_t* inv_perm;
+  const float* topk_w;
+  const bf16_t* o_perm;     // [A, H], what the routed blocks store
+  const bf16_t* o_shared;   // [T, H] or NULL
+  bf16_t* y;                // [T, H]
+  unsigned int* tickets;    // one counter per column block
+  int n_tokens, top_k, on;
+};
+
 struct SkinnyCtx {
   const int32_t* offsets;
   const int32_t* slot_of;
@@ -49,7 +65,19 @@ struct SkinnyCtx {
   const int32_t* row_map;  // gate/up only: input row of sorted row p is row_map[p] / map_div
   int map_div;
   SkinnyShared shared;
+  SkinnyCombine combine;
 };
+
+// number of experts that are active, resident and have rows
+__device__ __forceinline__ int count_busy_experts(const SkinnyCtx& c, int lane) {
+  int seen = 0;
+  for (int base = 0; base < c.n_experts; base += 64) {
+    const int e = base + lane;
+    const bool busy = e < c.n_experts && c.active.test(e) && c.slot_of[e] >= 0 && c.offsets[e + 1] > c.offsets[e];
+    seen += __popcll(__ballot(busy));
+  }
+  return seen;
+}
 
 // id of the `want`-th expert (ascending) that is active, resident and has rows; -1 if fewer
 __device__ __forceinline__ int nth_busy_expert(const SkinnyCtx& c, int want, int lane) {
@@ -173,7 +201,11 @@ __global__ __launch_bounds__(64 * NW) void ffn_skinny_kernel(SkinnyCtx c, const 
             const int m = (r / 4) * 8 + half * 4 + (r % 4);
             if (m < rows) {
               const float v = GATEUP ? silu_f32(g) * u : g;
-              out[(size_t)(row0 + m) * n_out + cur_g * TILE_N + col] = f32_to_bf16(v);
+              bf16_t* dst = out + (size_t)(row0 + m) * n_out + cur_g * TILE_N + col;
+              if (!GATEUP && c.combine.on)  // read by another block of this launch: a store that is visible device-wide
+                __hip_atomic_store(dst, f32_to_bf16(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              else
+                *dst = f32_to_bf16(v);
             }
           }
         }
@@ -192,6 +224,68 @@ __global__ __launch_bounds__(64 * NW) void ffn_skinny_kernel(SkinnyCtx c, const 
       if (b + 1 < n_batches) compute_batch(1);
     }
     if (NW > 1) __syncthreads();  // the reduction areas are reused by the next row pass
+  }
+
+  if constexpr (!GATEUP) {
+    if (c.combine.on) {  // uniform over the launch
+      // Wave 0 stored this block's results with device-scope stores (they go through to memory instead of staying in
+      // this die's L2) and waits until all of them have been performed before it draws the ticket; the block that draws
+      // the last ticket reads the others' results with device-scope loads.  (Fences would do the same for ordinary
+      // stores and loads, but a device-scope fence writes back and invalidates the whole L2 of the die, in every block:
+      // measured, that made the decode layers 15-55 % slower than the separate combine launch.)
+      // Only wave 0 stays for this: the other waves are done, and the wave slots they free let the CU's next block
+      // start while this one waits for its ticket.
+      if (wave != 0) return;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      const int expected = count_busy_experts(c, lane) + (c.shared.grid_rows > 0 ? 1 : 0);
+      int ticket = 0;
+      if (lane == 0)
+        ticket = (int)__hip_atomic_fetch_add(&c.combine.tickets[block_in_matrix], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (__shfl(ticket, 0) == expected - 1) {
+        const SkinnyCombine& cb = c.combine;
+        auto load16 = [](const uint4* p) {  // 16 bytes as two device-scope 8-byte loads
+          const unsigned long long* q = (const unsigned long long*)p;
+          const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+        };
+        const int chunks = (g_end - g_begin) * (TILE_N / 8);  // 16-byte pieces of a row that this column block owns
+        const int row_vec = c.hidden / 8;
+        const uint4* o_perm = (const uint4*)cb.o_perm;
+        const uint4* o_shared = (const uint4*)cb.o_shared;
+        for (int id = lane; id < cb.n_tokens * chunks; id += 64) {
+          const int t = id / chunks, cv = g_begin * (TILE_N / 8) + id % chunks;
+          float acc[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+          for (int j = 0; j < cb.top_k; ++j) {
+            const uint4 v = load16(o_perm + (long)cb.inv_perm[t * cb.top_k + j] * row_vec + cv);
+            const float w = cb.topk_w[t * cb.top_k + j];
+            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              acc[2 * i] += w * __uint_as_float(u[i] << 16);
+              acc[2 * i + 1] += w * __uint_as_float(u[i] & 0xffff0000u);
+            }
+          }
+          if (o_shared) {
+            const uint4 v = load16(o_shared + (long)t * row_vec + cv);
+            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              acc[2 * i] += __uint_as_float(u[i] << 16);
+              acc[2 * i + 1] += __uint_as_float(u[i] & 0xffff0000u);
+            }
+          }
+          uint32_t o[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[i] = (uint32_t)f32_to_bf16(acc[2 * i]) | ((uint32_t)f32_to_bf16(acc[2 * i + 1]) << 16);
+          ((uint4*)cb.y)[(long)t * row_vec + cv] = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+        if (lane == 0)  // zero again for the next launch
+          __hip_atomic_exchange(&c.combine.tickets[block_in_matrix], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
   }
 }
 
@@ -254,13 +348,13 @@ static void launch_stage(SkinnyCtx c, int n_groups, int busy_max, int max_rows, 
 
 // dense (or NULL): a dense FFN of the same hidden size over dense->n_rows rows (one resident expert: weights
 // at dense->slots, offsets {0, n_rows} implied), computed by extra blocks of the same two launches.
-int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense) {
+int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense, const CombineArgs* combine) {
   const hmoe_layer_desc& d = *a.desc;
   if (d.dtype != HMOE_BF16) return HMOE_ERR_UNSUPPORTED;
   if (dense && (dense->desc->dtype != HMOE_BF16 || dense->desc->hidden != d.hidden)) return HMOE_ERR_UNSUPPORTED;
   if (dense && dense->n_rows == 0) dense = nullptr;
   if (a.n_rows == 0 && !dense) return HMOE_OK;
-  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div, {}};
+  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div, {}, {}};
   int ffn_dense = 0;
   if (dense) {
     ffn_dense = dense->desc->ffn;
@@ -274,6 +368,11 @@ int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense) {
   launch_stage<true>(c, d.ffn / TILE_N, busy_max, max_rows, ffn_dense / TILE_N, (const bf16_t*)a.x_perm, (bf16_t*)a.h, a.stream);
   probe_after(a.stream);
   probe_before(a.stream);
+  if (combine) {
+    if (a.n_rows == 0) return HMOE_ERR_INVALID_ARG;  // without routed rows nothing would draw the tickets
+    c.combine = SkinnyCombine{combine->inv_perm, combine->topk_w, (const bf16_t*)a.o_perm, dense ? (const bf16_t*)dense->o_perm : nullptr,
+                              (bf16_t*)combine->y, combine->tickets, combine->n_tokens, d.top_k, 1};
+  }
   launch_stage<false>(c, d.hidden / TILE_N, busy_max, max_rows, dense ? d.hidden / TILE_N : 0, (const bf16_t*)a.h,
                       (bf16_t*)a.o_perm, a.stream);
   probe_after(a.stream);
@@ -464,7 +563,7 @@ int launch_ffn_skinny_w4(const FfnArgs& a) {
   const hmoe_layer_desc& d = *a.desc;
   if (d.dtype != HMOE_BF16_W4) return HMOE_ERR_UNSUPPORTED;
   if (a.n_rows == 0) return HMOE_OK;
-  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div, {}};
+  SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div, {}, {}};
   const int busy_max = std::min(d.n_experts, a.n_rows);  // every busy expert has at least one row
   probe_before(a.stream);
   launch_stage_w4<true>(c, d.ffn, busy_max, (const bf16_t*)a.x_perm, (bf16_t*)a.h, a.stream);

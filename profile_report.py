@@ -74,8 +74,10 @@ def main() -> int:
     ap.add_argument("--traffic", action="append", default=[], help="KEY=KERNEL_SUBSTRING[@GRID]")
     ap.add_argument("--report-only", action="store_true")
     ap.add_argument("--limit", type=int, default=280, help="seconds per pass")
-    ap.add_argument("bench_args", nargs="*")
-    args = ap.parse_args()
+    argv = sys.argv[1:]
+    cut = argv.index("--") if "--" in argv else len(argv)
+    args = ap.parse_args(argv[:cut])
+    args.bench_args = argv[cut + 1:]
     out_dir = os.path.join(ROOT, "gpurun_out", "prof_" + args.name)
     os.makedirs(out_dir, exist_ok=True)
     bench = ["python3", "bench.py"] + args.bench_args
@@ -85,6 +87,12 @@ def main() -> int:
     if args.sq:
         passes.append(("sq", ["--pmc"] + SQ_COUNTERS, bench + ["--no-graph"]))
     commands = []
+    digest_file = os.path.join(out_dir, "kernel_sources.txt")   # digest of the kernel sources that the passes ran with
+    if not args.report_only:
+        sys.path.insert(0, ROOT)
+        from bench import kernel_sources_digest
+        with open(digest_file, "w") as fh:
+            fh.write(kernel_sources_digest() + "\n")
     for tag, opts, cmd in passes:
         full = ["rocprofv3"] + opts + ["--output-format", "csv", "-d", "gpurun_out/prof_" + args.name, "-o", tag, "--"] + cmd
         commands.append(" ".join(full))
@@ -165,8 +173,8 @@ def main() -> int:
     print("profile_report: wrote profiles/%s.md" % args.name)
 
     if args.traffic:
-        sys.path.insert(0, ROOT)
-        from bench import kernel_sources_digest
+        with open(digest_file) as fh:
+            digest = fh.read().strip()
         path = os.path.join(ROOT, "profiles", "traffic.json")
         table = {}
         if os.path.exists(path):
@@ -179,7 +187,7 @@ def main() -> int:
             if not cands:
                 raise SystemExit("profile_report: no dispatch of a kernel matching %r" % what)
             k = max(cands, key=lambda c: c[1])
-            table[key] = {"bytes": int(scaled[k]), "kernel": k[0], "grid": k[1], "sources": kernel_sources_digest(),
+            table[key] = {"bytes": int(scaled[k]), "kernel": k[0], "grid": k[1], "sources": digest,
                           "profile": "profiles/%s.md" % args.name}
         with open(path, "w") as fh:
             json.dump(table, fh, indent=1, sort_keys=True)

@@ -537,14 +537,16 @@ def test_fused_and_unfused_layers_agree(hm, T):
     assert np.array_equal(outs[0][0], outs[1][0])      # same kernels on the same rows: bit-identical outputs
 
 
+@pytest.mark.parametrize("fused_sum", [False, True])
 @pytest.mark.parametrize("T,shared_ffn,logits_mode", [(4, (), "router"), (2, (64,), "zipf"), (70, (64,), "zipf"),
                                                       (200, (), "router")])
-def test_graph_replay_equals_eager(hm, T, shared_ffn, logits_mode):
+def test_graph_replay_equals_eager(hm, T, shared_ffn, logits_mode, fused_sum):
     """The layer captured in a HIP graph (what the benchmark times) and replayed on fresh inputs, with eager work
     and synchronisations between the replays, gives the bits of the eager calls every time, and matches the oracle.
     Covers the decode front end in one launch, the shared expert inside the routed launches (T <= 32) and on its
-    side stream (T > 32), and the prefill kernels."""
-    say("graph replay", T, shared_ffn, logits_mode)
+    side stream (T > 32), and the prefill kernels; with fused_sum also the sum of Eq. (1) inside the down projection's
+    launch (decode batches), whose eager reference is the layer with the separate combine launch."""
+    say("graph replay", T, shared_ffn, logits_mode, fused_sum)
     shape = wl.small_shape(dtype=wl.BF16, hidden=128, ffn=192, n_experts=8, top_k=2, shared_ffn=shared_ffn,
                            x_mode="rmsnorm", logits_mode=logits_mode)
     lays = [wl.make_layer(shape, 50, T)] + [wl.make_layer(shape, 51 + i, T, with_weights=False) for i in range(3)]
@@ -558,11 +560,13 @@ def test_graph_replay_equals_eager(hm, T, shared_ffn, logits_mode):
             lg_in.copy_(to_device(lay.logits))
 
     feed(lays[0])
+    layer.merge_combine = fused_sum
     layer.forward(x_in, lg_in)                      # warm-up outside the capture
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         y_graph = layer.forward(x_in, lg_in)
+    layer.merge_combine = False                     # the eager reference sums in the separate launch
     for lay in lays[1:] + lays[:1]:
         feed(lay)
         graph.replay()
@@ -644,4 +648,112 @@ def test_ffn_with_shared_equals_the_two_calls(hm, T, hidden, ffn, shared_ffn, dt
                                                layer.ffn_ws_bytes, layer.shared_desc, layer.shared_cache,
                                                layer.shared_offsets, T, s_a, layer.shared_ws, 0)
     assert ei.value.status == hm.HMOE_ERR_WORKSPACE
+    layer.close()
+
+
+@pytest.mark.parametrize("E,K,hidden,ffn,shared_ffn", [(8, 2, 256, 128, (64, 64)), (64, 6, 512, 192, (128,)), (8, 2, 128, 256, ()),
+                                                       (16, 4, 2048, 64, (192,))])
+def test_ffn_combine_equals_the_separate_calls(hm, E, K, hidden, ffn, shared_ffn):
+    """hmoe_expert_ffn_combine (FFN of routed and shared experts and the sum of Eq. (1); for decode batches the sum runs
+    inside the down projection's launch, done by the last block of each column block) writes the same bits into o_perm,
+    o_shared and y as the separate calls, call after call through the same counters, for batches of several sizes
+    (one and several row passes), and matches the oracle."""
+    say("ffn_combine", E, K, hidden, ffn, shared_ffn)
+    shape = wl.small_shape(dtype=wl.BF16, hidden=hidden, ffn=ffn, n_experts=E, top_k=K, shared_ffn=shared_ffn, x_mode="rmsnorm")
+    base = wl.make_layer(shape, 77, 1)
+    layer = build_layer(hm, base, max_tokens=40)
+    d = layer.desc
+    sd = layer.shared_desc
+    for rep, T in enumerate([1, 8, 3, 32, 1, 9, 40]):       # 40 tokens: not a decode batch, the separate calls inside
+        lay = wl.make_layer(shape, 900 + rep, T, with_weights=False)
+        lay.experts, lay.shared, lay.w_router = base.experts, base.shared, base.w_router
+        A = T * K
+        x = to_device(lay.x)
+        lg = orc.router_logits(wl.as_f64(lay.x), wl.as_f64(lay.w_router)).astype(np.float32)
+        hm.hmoe_route_permute(d, to_device(lg), T, layer.topk_idx, layer.topk_w, layer.offsets, layer.perm, layer.inv_perm, None,
+                              layer.perm_ws, layer.perm_ws_bytes)
+        if sd is not None:
+            layer.shared_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
+        o_a, y_a = torch.full_like(layer.o_perm, 5.0), torch.full_like(layer.y, 5.0)
+        o_b, y_b = torch.full_like(layer.o_perm, 6.0), torch.full_like(layer.y, 6.0)
+        s_a = torch.full_like(layer.o_shared, 5.0) if sd is not None else None
+        s_b = torch.full_like(layer.o_shared, 6.0) if sd is not None else None
+        hm.hmoe_expert_ffn_combine(d, layer.cache, x, layer.perm, layer.inv_perm, layer.topk_w, layer.offsets, T, o_a, layer.ffn_ws,
+                                   layer.ffn_ws_bytes, sd, None if sd is None else layer.shared_cache,
+                                   None if sd is None else layer.shared_offsets, s_a, None if sd is None else layer.shared_ws,
+                                   0 if sd is None else layer.shared_ws_bytes, y_a, layer.sync, layer.sync_bytes)
+        torch.cuda.synchronize()
+        assert int(layer.sync.max()) == 0, "the ticket counters must be left zero"
+        hm.hmoe_expert_ffn_grouped_gather(d, layer.cache, x, layer.perm, layer.offsets, A, None, o_b, layer.ffn_ws,
+                                          layer.ffn_ws_bytes)
+        if sd is not None:
+            hm.hmoe_expert_ffn_grouped(sd, layer.shared_cache, x, layer.shared_offsets, T, None, s_b, layer.shared_ws,
+                                       layer.shared_ws_bytes)
+        hm.hmoe_combine(d, o_b, layer.inv_perm, layer.topk_w, s_b, T, y_b)
+        torch.cuda.synchronize()
+        assert torch.equal(o_a[:A].cpu(), o_b[:A].cpu()), T
+        assert sd is None or torch.equal(s_a[:T].cpu(), s_b[:T].cpu()), T
+        assert torch.equal(y_a[:T].cpu(), y_b[:T].cpu()), T
+        assert max_rel_err(to_host_f32(y_a[:T]), oracle_layer(lay, lg)) < TOL[wl.BF16]
+    # argument checks: a counter buffer that is too small, a shared layer of another hidden size
+    with pytest.raises(hm.HmoeError) as ei:
+        hm.hmoe_expert_ffn_combine(d, layer.cache, x, layer.perm, layer.inv_perm, layer.topk_w, layer.offsets, T, o_a, layer.ffn_ws,
+                                   layer.ffn_ws_bytes, None, None, None, None, None, 0, y_a, layer.sync, 4)
+    assert ei.value.status == hm.HMOE_ERR_WORKSPACE
+    if sd is not None:
+        bad = hm.make_desc(hidden * 2, shared_ffn[0], 1, 1, 1, d.dtype)
+        with pytest.raises(hm.HmoeError) as ei:
+            hm.hmoe_expert_ffn_combine(d, layer.cache, x, layer.perm, layer.inv_perm, layer.topk_w, layer.offsets, T, o_a,
+                                       layer.ffn_ws, layer.ffn_ws_bytes, bad, layer.shared_cache, layer.shared_offsets, s_a,
+                                       layer.shared_ws, layer.shared_ws_bytes, y_a, layer.sync, layer.sync_bytes)
+        assert ei.value.status == hm.HMOE_ERR_INVALID_ARG
+    layer.close()
+
+
+def test_stage_after_captured_ffn_calls(hm):
+    """An FFN call over a partial cache captured in a HIP graph, replayed, then an expert staged into a slot the graph
+    reads, and the graph replayed again on the new slot contents: every result is the one of the weights that were in
+    the slot when the call ran (the copy is ordered after the replays enqueued before it)."""
+    say("stage after graph capture")
+    shape = wl.small_shape(dtype=wl.BF16, hidden=128, ffn=192, n_experts=4, top_k=1, n_slots=2, x_mode="rmsnorm")
+    lay = wl.make_layer(shape, 9, 1)
+    layer = build_layer(hm, lay, max_tokens=64)
+    d = layer.desc
+    T = 48
+    rng = np.random.default_rng(3)
+    xb = wl.store(rng.standard_normal((T, 128)).astype(np.float32), wl.BF16)
+    x = to_device(xb)
+    offs = to_device(np.array([0, 20, 48, 48, 48], np.int32))      # rows 0..19 -> expert 0, rows 20..47 -> expert 1
+
+    def ref(e, rows):
+        wg, wu, wd = lay.experts[e]
+        return orc.expert_ffn(wl.as_f64(xb[rows]), wl.as_f64(wg), wl.as_f64(wu), wl.as_f64(wd))
+
+    o = torch.zeros(T, 128, dtype=torch.bfloat16, device=DEV)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        hm.hmoe_expert_ffn_grouped(d, layer.cache, x, offs, T, None, o, layer.ffn_ws, layer.ffn_ws_bytes)   # warm-up
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            hm.hmoe_expert_ffn_grouped(d, layer.cache, x, offs, T, None, o, layer.ffn_ws, layer.ffn_ws_bytes)
+        for _ in range(3):
+            graph.replay()
+        # expert 2 into slot 0 (evicts expert 0): the copy must wait for the replays above
+        hm.hmoe_cache_stage(layer.cache, 2, 0, layer.h_packed[2], side, layer.copy_stream)
+        side.synchronize()
+        got = to_host_f32(o).copy()
+        assert max_rel_err(got[:20], ref(0, slice(0, 20))) < TOL[wl.BF16] and max_rel_err(got[20:], ref(1, slice(20, 48))) < TOL[wl.BF16]
+        assert layer.slot_map() == [-1, 1, 0, -1]
+        # the same graph now finds expert 0 gone (its rows stay untouched) and expert 1 still there
+        o.fill_(7.0)
+        graph.replay()
+        offs2 = to_device(np.array([0, 0, 20, 48, 48], np.int32))  # eager: rows 0..19 -> expert 1, rows 20..47 -> expert 2
+        o2 = torch.zeros(T, 128, dtype=torch.bfloat16, device=DEV)
+        hm.hmoe_expert_ffn_grouped(d, layer.cache, x, offs2, T, None, o2, layer.ffn_ws, layer.ffn_ws_bytes)
+        side.synchronize()
+    got = to_host_f32(o)
+    assert np.all(got[:20] == 7.0) and max_rel_err(got[20:], ref(1, slice(20, 48))) < TOL[wl.BF16]
+    got2 = to_host_f32(o2)
+    assert max_rel_err(got2[:20], ref(1, slice(0, 20))) < TOL[wl.BF16] and max_rel_err(got2[20:], ref(2, slice(20, 48))) < TOL[wl.BF16]
     layer.close()

@@ -124,3 +124,26 @@ def test_traffic_table_names_kernels_that_exist():
         assert entry["bytes"] > 0 and re.fullmatch(r"\w+/\w+(\+w4)?", key), key
         base = entry["kernel"].split("<")[0]
         assert re.search(r"\b%s\b" % re.escape(base), text), "%s: kernel %s is gone; profile again" % (key, base)
+
+
+def test_new_entry_points_reject_bad_arguments_on_the_host(hm):
+    """hmoe_permute_static, hmoe_expert_ffn_combine and hmoe_expert_ffn_staged check what the host can check before
+    they touch the device."""
+    ok = hm.make_desc(64, 64, 8, 2, 8, 1)
+    big = hm.make_desc(64, 64, 256, 32, 256, 1)
+    lib = hm._lib
+    assert lib.hmoe_permute_static(ctypes.byref(ok), None, -1, None, None, None, None, None, None, None) == hm.HMOE_ERR_INVALID_ARG
+    assert lib.hmoe_permute_static(ctypes.byref(big), None, 40000, None, None, None, None, None, None, None) == hm.HMOE_ERR_WORKSPACE
+    assert b"HMOE_PERMUTE_STATIC_BYTES" in lib.hmoe_last_error()
+    assert hm.hmoe_permute_workspace_bytes(big, 40000) > hm.HMOE_PERMUTE_STATIC_BYTES
+    assert hm.hmoe_ffn_combine_sync_bytes(ok) >= (64 // 32) * 4 and hm.hmoe_ffn_combine_sync_bytes(ok) % 256 == 0
+    args = [None] * 22
+    args[0] = ctypes.byref(ok)
+    args[7], args[10], args[16], args[19], args[20] = 4, 0, 0, 0, 0
+    assert lib.hmoe_expert_ffn_combine(*args) == hm.HMOE_ERR_INVALID_ARG          # no perm / inv_perm / weights / y
+    args[7] = 0
+    assert lib.hmoe_expert_ffn_combine(*args) == hm.HMOE_OK                       # T = 0: no-op
+    sargs = [None] * 19
+    sargs[0] = ctypes.byref(ok)
+    sargs[5], sargs[10], sargs[11] = 0, 0, 0
+    assert lib.hmoe_expert_ffn_staged(*sargs) == hm.HMOE_ERR_INVALID_ARG          # no cache, no counts, no plan arrays
