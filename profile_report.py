@@ -67,12 +67,69 @@ def mean(v):
     return sum(v) / max(1, len(v))
 
 
+def copies_report(args, out_dir, bench) -> int:
+    """Transfer / compute overlap of the staging leg: kernel trace and memory-copy trace of one run."""
+    full = ["rocprofv3", "--kernel-trace", "--memory-copy-trace", "--output-format", "csv", "-d", "gpurun_out/prof_" + args.name,
+            "-o", "stg", "--"] + bench
+    if not args.report_only:
+        run(full, os.path.join(out_dir, "stg.log"), args.limit)
+        for f in os.listdir(out_dir):
+            if f.endswith(".db"):
+                os.remove(os.path.join(out_dir, f))
+    with open(os.path.join(out_dir, "stg_memory_copy_trace.csv")) as fh:
+        copies = [(int(r["Start_Timestamp"]), int(r["End_Timestamp"])) for r in csv.DictReader(fh)
+                  if "HOST_TO_DEVICE" in r["Direction"] and int(r["End_Timestamp"]) - int(r["Start_Timestamp"]) > 1000000]
+    with open(os.path.join(out_dir, "stg_kernel_trace.csv")) as fh:
+        kernels = [(int(r["Start_Timestamp"]), int(r["End_Timestamp"]), short(r["Kernel_Name"])) for r in csv.DictReader(fh)
+                   if "ffn_" in r["Kernel_Name"]]
+    copies.sort()
+    total = under = hit = 0
+    examples = []
+    for k in kernels:
+        total += k[1] - k[0]
+        for c in copies:
+            lo, hi = max(k[0], c[0]), min(k[1], c[1])
+            if hi > lo:
+                under += hi - lo
+                hit += 1
+                if len(examples) < 8:
+                    examples.append((c, k))
+                break
+    md = ["# rocprofv3 summary: %s (staging copies against FFN kernels)" % args.name, "",
+          "Written by `python3 profile_report.py %s --copies -- %s`, which runs" % (args.name, " ".join(args.bench_args)), "",
+          "```", " ".join(full), "```", "",
+          "Host-to-device copies longer than 1 ms (the staged experts): %d, %.2f ms on average, %.1f ms in total."
+          % (len(copies), mean([c[1] - c[0] for c in copies]) / 1e6, sum(c[1] - c[0] for c in copies) / 1e6),
+          "FFN kernel dispatches: %d, %.1f ms in total; %d of them ran while such a copy was in flight (%.2f ms of kernel time under "
+          "a copy).  A copy waits for the last FFN call that read its slot and for nothing else, so it starts under the FFN of the "
+          "experts that were resident (the slot it overwrites is not one they read) and the wave that needs it starts when it has "
+          "landed; copies themselves run one after the other on the copy stream." % (len(kernels), total / 1e6, hit, under / 1e6), "",
+          "Examples (ms from the start of the first listed copy):", "", "| copy | kernel | kernel runs |", "|---|---|---|"]
+    t0 = examples[0][0][0] if examples else 0
+    for c, k in examples:
+        md.append("| %.3f .. %.3f | `%s` | %.3f .. %.3f |" % ((c[0] - t0) / 1e6, (c[1] - t0) / 1e6, k[2], (k[0] - t0) / 1e6, (k[1] - t0) / 1e6))
+    if copies:
+        first = copies[len(copies) // 2][0]
+        ev = [(c[0], c[1], "copy host to device") for c in copies if first <= c[0] < first + 60_000_000]
+        ev += [(k[0], k[1], "`%s`" % k[2]) for k in kernels if first - 1_000_000 <= k[0] < first + 60_000_000]
+        md += ["", "A stretch of the timeline (ms):", "", "| start | end | what |", "|---|---|---|"]
+        for e in sorted(ev)[:40]:
+            md.append("| %.3f | %.3f | %s |" % ((e[0] - first) / 1e6, (e[1] - first) / 1e6, e[2]))
+    with open(os.path.join(ROOT, "profiles", args.name + ".md"), "w") as fh:
+        fh.write("\n".join(md) + "\n")
+    print("profile_report: wrote profiles/%s.md" % args.name)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("name")
     ap.add_argument("--sq", action="store_true", help="also collect the matrix-core / sequencer counters")
     ap.add_argument("--traffic", action="append", default=[], help="KEY=KERNEL_SUBSTRING[@GRID]")
     ap.add_argument("--report-only", action="store_true")
+    ap.add_argument("--copies", action="store_true",
+                    help="a single pass with --kernel-trace --memory-copy-trace instead: which FFN kernels ran while a staging "
+                         "copy (host to device, longer than 1 ms) was in flight")
     ap.add_argument("--limit", type=int, default=280, help="seconds per pass")
     argv = sys.argv[1:]
     cut = argv.index("--") if "--" in argv else len(argv)
@@ -81,6 +138,8 @@ def main() -> int:
     out_dir = os.path.join(ROOT, "gpurun_out", "prof_" + args.name)
     os.makedirs(out_dir, exist_ok=True)
     bench = ["python3", "bench.py"] + args.bench_args
+    if args.copies:
+        return copies_report(args, out_dir, bench)
     passes = [("trace", ["--kernel-trace", "--stats"], bench),
               ("fetch", ["--pmc", "FETCH_SIZE"], bench + ["--no-graph", "--copy-probe"]),
               ("write", ["--pmc", "WRITE_SIZE"], bench + ["--no-graph", "--copy-probe"])]
