@@ -315,6 +315,8 @@ def main() -> int:
         if staging:
             for pname, r in staging.items():
                 staging_out["%s/%s%s" % (name, pname, suffix)] = r
+                # next to the kernel-only rate: the same phase with the workload's real cache size, copies included
+                phases_out["%s/%s%s" % (name, pname, suffix)]["tokens_per_s_incl_pcie"] = r["tokens_per_s_incl_pcie"]
         setup_out[name] = setup_s
         head = (name, PHASES[name][-1] if not args.phase else [p for p in PHASES[name] if p[0] == args.phase][-1], lay0, n_layers)
         print("bench.py: %s done (setup %.1f s)" % (name, setup_s), file=sys.stderr, flush=True)
