@@ -35,8 +35,6 @@ namespace hmoe {
 
 // One 16-byte global -> LDS copy per lane; the wave's 64 chunks land at lds_base .. +1024 in lane
 // order.  lds_base must be wave-uniform.  Completion is tracked by vmcnt like any vector load.
-// m0 is on the clobber list so that the statement says what it overwrites (the compiler answers that m0 is
-// reserved: it keeps no value of its own there across statements).
 __device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
