@@ -757,3 +757,36 @@ def test_stage_after_captured_ffn_calls(hm):
     got2 = to_host_f32(o2)
     assert max_rel_err(got2[:20], ref(1, slice(0, 20))) < TOL[wl.BF16] and max_rel_err(got2[20:], ref(2, slice(20, 48))) < TOL[wl.BF16]
     layer.close()
+
+
+@pytest.mark.parametrize("shape_id,gpb", [(0, 1), (1, 3), (2, 2), (3, 1), (4, 3), (5, 2)])
+def test_ffn_combine_every_decode_block_shape(hm, shape_id, gpb, monkeypatch):
+    """The sum inside the down projection's launch with every block shape of the decode kernel and 1-3 column groups per
+    block (one ticket counter per column block, whatever its width): same bits as the separate calls."""
+    say("ffn_combine decode shape", shape_id, gpb)
+    monkeypatch.setenv("HMOE_SKINNY", "%d,%d" % (shape_id, gpb))
+    shape = wl.small_shape(dtype=wl.BF16, hidden=320, ffn=192, n_experts=6, top_k=3, shared_ffn=(128,), x_mode="rmsnorm")
+    base = wl.make_layer(shape, 5, 1)
+    layer = build_layer(hm, base, max_tokens=16)
+    d, sd, K = layer.desc, layer.shared_desc, 3
+    for rep, T in enumerate([2, 16, 5]):
+        lay = wl.make_layer(shape, 40 + rep, T, with_weights=False)
+        x = to_device(lay.x)
+        lg = orc.router_logits(wl.as_f64(lay.x), wl.as_f64(base.w_router)).astype(np.float32)
+        hm.hmoe_route_permute(d, to_device(lg), T, layer.topk_idx, layer.topk_w, layer.offsets, layer.perm, layer.inv_perm, None,
+                              layer.perm_ws, layer.perm_ws_bytes)
+        layer.shared_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
+        o_a, y_a, s_a = torch.full_like(layer.o_perm, 5.0), torch.full_like(layer.y, 5.0), torch.full_like(layer.o_shared, 5.0)
+        o_b, y_b, s_b = torch.full_like(layer.o_perm, 6.0), torch.full_like(layer.y, 6.0), torch.full_like(layer.o_shared, 6.0)
+        hm.hmoe_expert_ffn_combine(d, layer.cache, x, layer.perm, layer.inv_perm, layer.topk_w, layer.offsets, T, o_a, layer.ffn_ws,
+                                   layer.ffn_ws_bytes, sd, layer.shared_cache, layer.shared_offsets, s_a, layer.shared_ws,
+                                   layer.shared_ws_bytes, y_a, layer.sync, layer.sync_bytes)
+        hm.hmoe_expert_ffn_grouped_with_shared(d, layer.cache, x, layer.perm, layer.offsets, T * K, None, o_b, layer.ffn_ws,
+                                               layer.ffn_ws_bytes, sd, layer.shared_cache, layer.shared_offsets, T, s_b,
+                                               layer.shared_ws, layer.shared_ws_bytes)
+        hm.hmoe_combine(d, o_b, layer.inv_perm, layer.topk_w, s_b, T, y_b)
+        torch.cuda.synchronize()
+        assert int(layer.sync.max()) == 0
+        assert torch.equal(o_a[:T * K].cpu(), o_b[:T * K].cpu()) and torch.equal(s_a[:T].cpu(), s_b[:T].cpu())
+        assert torch.equal(y_a[:T].cpu(), y_b[:T].cpu()), (shape_id, gpb, T)
+    layer.close()
