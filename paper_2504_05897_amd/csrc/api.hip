@@ -601,11 +601,13 @@ extern "C" int32_t hmoe_expert_ffn_combine(
   for (int e = 0; e < desc->n_experts; ++e) all_resident = all_resident && cache->slot_of[e] >= 0;
   const bool fused = desc->dtype == HMOE_BF16 && path_routed == HMOE_FFN_SKINNY && (!shared_desc || path_dense == HMOE_FFN_SKINNY) &&
                      all_resident && desc->hidden % 8 == 0;
-  if (!fused) {
-    if ((rc = ffn_launch(routed, path_routed)) != HMOE_OK) return rc;
-    if (shared_desc && (rc = ffn_launch(dense, path_dense)) != HMOE_OK) return rc;
-    if ((rc = ffn_record_reads(cache, routed)) != HMOE_OK) return rc;
-    if (shared_desc && (rc = ffn_record_reads(shared_cache, dense)) != HMOE_OK) return rc;
+  if (!fused) {  // the calls this one stands for, one after the other
+    rc = shared_desc ? hmoe_expert_ffn_grouped_with_shared(desc, cache, x, perm, expert_offsets, A, nullptr, 0, o_perm, workspace,
+                                                           workspace_bytes, shared_desc, shared_cache, shared_offsets, T, o_shared,
+                                                           shared_workspace, shared_workspace_bytes, path, stream)
+                     : hmoe_expert_ffn_grouped_gather(desc, cache, x, perm, expert_offsets, A, nullptr, 0, o_perm, workspace,
+                                                      workspace_bytes, path, stream);
+    if (rc != HMOE_OK) return rc;
     return hmoe_combine(desc, o_perm, inv_perm, topk_w, shared_desc ? o_shared : nullptr, T, y, stream);
   }
   CombineArgs cb;
