@@ -27,6 +27,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 #include "tile_locate.h"
@@ -110,7 +111,7 @@ __device__ __forceinline__ void wait_vmcnt_regs(u32x4& a) {
 // twice in two blocks that must keep pace to share them through L2); the gate and the up half of a SwiGLU pair then
 // sit in neighbouring waves and meet through LDS in the epilogue.  Tiles higher than 128 rows copy only the rows
 // they multiply (rounded up to what one copy instruction per thread moves).
-template <bool GATEUP_, int BM_, int NWV, int SA, bool NT, int DB = 8, int FMC = 0, int FN_ = 2>
+template <bool GATEUP_, int BM_, int NWV, int SA, bool NT, int DB = 8, int FMC = 0, int FN_ = 2, bool ILV = false>
 struct StreamTile {
   static constexpr bool GATEUP = GATEUP_;
   static constexpr int BM = BM_;
@@ -129,7 +130,11 @@ struct StreamTile {
   static constexpr int OPS3 = A_OPS - A_OPS * 3 / KK;  // copies issued in the last substep of a step
   static constexpr int N_B = (DB - 1) * FN + (DB / KK) * A_OPS;
   static constexpr int N_A = (SA - 3) * (KK * FN + A_OPS) + 3 * FN + A_OPS - OPS3;
-  static_assert(N_B <= 63 && N_A <= 63, "vmcnt range");
+  static_assert(N_B <= 63 && N_A + FN - 1 <= 63, "vmcnt range");
+  // ILV (one wave per SIMD): the substep's work is issued between its matrix instructions, in the order [weight group
+  // 0] [copies] [weight group 1]; a wait for both groups of a ring slot then has one substep's copies fewer behind it.
+  // The count uses the largest piece of copies, so it is exact or one operation stricter.
+  static constexpr int N_B_ILV = N_B - (A_OPS + KK - 1) / KK;
   static constexpr int THREADS = 64 * NWV;
   static constexpr int LDS_VEC = SA * A_CHUNKS;  // 16-byte units
   typedef f32x16_t Acc[FM][FN];
@@ -145,7 +150,8 @@ struct StreamTile {
     const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
     const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
     const int m0 = mt * MSTRIDE;
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);  // uniform: LDS bases and weight groups stay scalar
     const int half = lane / 32, col = lane % 32;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
 
@@ -166,6 +172,11 @@ struct StreamTile {
       b_src[j] = w + ((size_t)(g < n_groups ? g : 0) * kt16 + (size_t)k_begin * KK) * 64 + lane;
     }
     const int n_sub = k_steps * KK;
+    auto issue_a_op = [&](int stage, int kstep, int op) {
+      const uint32_t base = lds0 + (uint32_t)stage * A_CHUNKS * 16;
+      const size_t koff = (size_t)(kstep < k_steps ? kstep : k_steps - 1) * CPR;
+      load_to_lds_16(a_src[op] + koff, base + (uint32_t)((op * NWV + wave) * 64) * 16);
+    };
     auto issue_a_piece = [&](int stage, int kstep, int piece) {
       const uint32_t base = lds0 + (uint32_t)stage * A_CHUNKS * 16;
       const size_t koff = (size_t)(kstep < k_steps ? kstep : k_steps - 1) * CPR;
@@ -208,27 +219,53 @@ struct StreamTile {
     read_a(0, 0, 0);
 
     int stage = 0;  // ring stage of step tt
-    for (int t = 0; t < k_steps; t += DB / KK) {
-#pragma unroll
-      for (int h = 0; h < DB / KK; ++h) {
-        const int tt = t + h;
-        if (tt < k_steps) {
+    // one K step; hc carries h, the step's place in the weight ring (a compile-time constant: the ring is registers)
+    auto k_step = [&](int tt, auto hc) __attribute__((always_inline)) {
+        constexpr int h = decltype(hc)::value;
+        {
           const int next_stage = stage + 1 == SA ? 0 : stage + 1;
           const int fill_stage = stage == 0 ? SA - 1 : stage - 1;  // held step tt-1, free since this step opened
 #pragma unroll
           for (int kk = 0; kk < KK; ++kk) {
             if (kk == KK - 1) {
               // open step tt+1: its activation tile has landed once at most N_A younger operations are out
-              wait_vmcnt_opens_stage<N_A, SA>();
+              wait_vmcnt_opens_stage<ILV ? N_A + FN - 1 : N_A, SA>();
               __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this step's last fragments are in registers
               block_barrier();
-              if constexpr (FN == 2) read_a((kk + 1) & 1, next_stage, 0);
+              if constexpr (FN == 2 && !ILV) read_a((kk + 1) & 1, next_stage, 0);
             } else {
-              if constexpr (FN == 2) read_a((kk + 1) & 1, stage, kk + 1);
+              if constexpr (FN == 2 && !ILV) read_a((kk + 1) & 1, stage, kk + 1);
             }
             __builtin_amdgcn_sched_barrier(0);
             const int sl = h * KK + kk;  // ring slot of substep 4*tt + kk
-            if constexpr (FN == 2) {
+            if constexpr (FN == 2 && ILV) {
+              // One wave per SIMD: nothing else fills the matrix pipe while this wave issues anything else, so all
+              // other work of the substep sits between its matrix instructions, one piece behind each: the next
+              // substep's fragment reads behind the first FM, which multiply weight group 0; then the reload of
+              // group 0's ring slot, this substep's activation copies, and behind the last one the reload of
+              // group 1.  Vector-memory order per substep: [group 0] [copies] [group 1].
+              wait_vmcnt_regs<N_B_ILV>(ring[sl][0], ring[sl][1]);
+              const int s_next = tt * KK + kk + DB;
+              const size_t w_next = (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64;
+#pragma unroll
+              for (int m = 0; m < 2 * FM; ++m) {
+                const int i = m % FM, j = m / FM;
+                acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
+                if (m < FM) fa[(kk + 1) & 1][m] = kk == KK - 1 ? read_frag(next_stage, 0, m) : read_frag(stage, kk + 1, m);
+                if (m == FM) ring[sl][0] = load_stream_16<NT>(b_src[0] + w_next);
+#pragma unroll
+                for (int op = 0; op < A_OPS; ++op)
+                  if (op >= A_OPS * kk / KK && op < A_OPS * (kk + 1) / KK) {
+                    const int at = FM + 1 + (op - A_OPS * kk / KK);
+                    if (m == (at < 2 * FM - 1 ? at : 2 * FM - 1)) issue_a_op(fill_stage, tt + SA - 1, op);
+                  }
+                if (m == 2 * FM - 1) {
+                  if (kk == KK - 1) mark_stage_issued();
+                  ring[sl][1] = load_stream_16<NT>(b_src[1] + w_next);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+              }
+            } else if constexpr (FN == 2) {
               wait_vmcnt_regs<N_B>(ring[sl][0], ring[sl][1]);
 #pragma unroll
               for (int i = 0; i < FM; ++i)
@@ -243,14 +280,33 @@ struct StreamTile {
               }
             }
             __builtin_amdgcn_sched_barrier(0);
-            const int s_next = tt * KK + kk + DB;
+            if constexpr (!ILV) {
+              const int s_next = tt * KK + kk + DB;
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-              ring[sl][j] = load_stream_16<NT>(b_src[j] + (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64);
-            issue_a_piece(fill_stage, tt + SA - 1, kk);
+              for (int j = 0; j < FN; ++j)
+                ring[sl][j] = load_stream_16<NT>(b_src[j] + (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64);
+              issue_a_piece(fill_stage, tt + SA - 1, kk);
+            }
           }
           stage = next_stage;
         }
+    };
+    static_assert(DB / KK == 1 || DB / KK == 2, "the weight ring holds one or two K steps");
+    if constexpr (ILV && DB / KK == 2) {
+      // Pairs of steps without a condition inside the loop, then the odd step if there is one: accumulators that
+      // pass through a conditional block inside the loop are more than the register allocator handles when they
+      // fill the second register file.
+      int t = 0;
+      for (; t + 2 <= k_steps; t += 2) {
+        k_step(t, std::integral_constant<int, 0>{});
+        k_step(t + 1, std::integral_constant<int, 1>{});
+      }
+      if (t < k_steps) k_step(t, std::integral_constant<int, 0>{});
+    } else {
+      for (int t = 0; t < k_steps; t += DB / KK) {
+        k_step(t, std::integral_constant<int, 0>{});
+        if constexpr (DB / KK == 2)
+          if (t + 1 < k_steps) k_step(t + 1, std::integral_constant<int, 1>{});
       }
     }
     wait_vmcnt<0>();  // the clamped tail copies must not outlive the block's LDS
@@ -430,8 +486,18 @@ __device__ __forceinline__ void run_tile(const TiledCtx& c, const bf16_t* __rest
                                          const TileLoc& loc, u32x4* lds) {
   typename TILE::Acc acc;
   zero_acc<TILE>(acc);
+  // A 256-row tile with two weight groups per wave keeps its accumulators in the second half of the register file
+  // (one wave per SIMD, 512 registers).  A fitted instantiation needs fewer of them than the full tile, and the
+  // register allocator would park weight-ring values in the free ones -- copying a register whose hand-issued load
+  // has not landed.  Holding the unused accumulator registers over the tile leaves it nowhere to park.
+  constexpr int HELD = TILE::BM == 224 && TILE::FN == 2 ? 14 - TILE::FM * TILE::FN : 0;
+  f32x16_t held[HELD > 0 ? HELD : 1];
+#pragma unroll
+  for (int i = 0; i < HELD; ++i) asm volatile("" : "=a"(held[i]));
   TILE::mainloop(c, in, loc, 0, (TILE::GATEUP ? c.hidden : c.ffn) / TILE::BKT, lds, acc);
   TILE::epilogue(c, out, loc, acc, lds);
+#pragma unroll
+  for (int i = 0; i < HELD; ++i) asm volatile("" ::"a"(held[i]));
 }
 
 // One block per tile, tile height fitted to the expert.  An expert of R rows has ceil(R / 128) m-tiles whatever
@@ -494,6 +560,32 @@ static void launch_tiles_fit256(TiledCtx c, int n_rows, const bf16_t* in, bf16_t
   hipLaunchKernelGGL((ffn_tile_fit256_kernel<GATEUP, NWV, NT>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in, out);
 }
 
+// Tiles of up to 256 rows with TWO weight groups per wave: 256x256 with four waves, one wave per SIMD, the 256
+// accumulator registers of a wave in the second half of its register file.  A CU then pulls (256 + 256) * 2 bytes
+// per k for 256 x 256 products, two thirds of what two resident 128x256 blocks pull.
+template <bool GATEUP, bool NT>
+__global__ __launch_bounds__(256) void ffn_tile_fit256w_kernel(TiledCtx c, const bf16_t* __restrict__ in,
+                                                                bf16_t* __restrict__ out) {
+  typedef StreamTile<GATEUP, 224, 4, 4, NT, 8, 7, 2, true> FULL;
+  __shared__ u32x4 lds[FULL::LDS_VEC];
+  TileLoc loc;
+  if (!locate_tile<224>(c, loc)) return;  // uniform over the block
+  const int tiles = (loc.m_rows + 223) / 224;
+  const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;  // per m-tile, 1..8; uniform
+  if (fragments > 6) run_tile<FULL>(c, in, out, loc, lds);
+  else if (fragments > 5) run_tile<StreamTile<GATEUP, 224, 4, 4, NT, 8, 6, 2, true>>(c, in, out, loc, lds);
+  else if (fragments > 4) run_tile<StreamTile<GATEUP, 224, 4, 4, NT, 8, 5, 2, true>>(c, in, out, loc, lds);
+  else run_tile<StreamTile<GATEUP, 224, 4, 4, NT, 8, 4, 2, true>>(c, in, out, loc, lds);
+}
+
+template <bool GATEUP, bool NT>
+static void launch_tiles_fit256w(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
+  const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
+  c.n_tiles_n = (n_total + 255) / 256;
+  c.grid_padded = (int)((tiles_upper_bound(c, n_rows, 224) + 7) / 8 * 8);
+  hipLaunchKernelGGL((ffn_tile_fit256w_kernel<GATEUP, NT>), dim3((unsigned)c.grid_padded), dim3(256), 0, s, c, in, out);
+}
+
 // Tile shapes built into the library.  hmoe picks one from the average rows per expert; the
 // environment variable HMOE_TILED_VARIANT (an index into this table) overrides the choice for
 // tuning runs.
@@ -511,7 +603,9 @@ enum {
   V_FIT4 = 2,           // 128x256 tile, 4 waves, half the weight ring: two blocks per CU
   V_FIT4_PLAIN = 3,
   V_FIT256 = 4,         // tiles of up to 256 rows, one weight group per wave: 256x256 (gate/up, 8 waves), 256x128 (down, 4 waves)
-  V_FIT256_PLAIN = 5
+  V_FIT256_PLAIN = 5,
+  V_FIT256W = 6,        // 256x256, 4 waves, two weight groups per wave, one wave per SIMD
+  V_FIT256W_PLAIN = 7
 };
 static const TiledVariant kVariants[] = {
     HMOE_STREAM_FIT("stream 128x512 fit", 8, true),
@@ -520,6 +614,8 @@ static const TiledVariant kVariants[] = {
     HMOE_STREAM_FIT("stream 128x256 fit, 4 waves, plain", 4, false),
     HMOE_STREAM_FIT256("stream 256x256/128 fit", 8, 4, true),
     HMOE_STREAM_FIT256("stream 256x256/128 fit plain", 8, 4, false),
+    {"stream 224x256, 4 waves", launch_tiles_fit256w<true, true>, launch_tiles_fit<false, 8, true>},
+    {"stream 224x256, 4 waves, plain", launch_tiles_fit256w<true, false>, launch_tiles_fit<false, 8, false>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 

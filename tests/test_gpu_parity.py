@@ -203,7 +203,7 @@ def test_ffn_bf16_paths(hm, path, hidden, ffn, counts):
     assert np.abs(ref).max() > 1e-2
 
 
-@pytest.mark.parametrize("variant", range(6))
+@pytest.mark.parametrize("variant", range(8))
 def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
     """The library's tuning override selects each built-in prefill kernel in turn (0-1 weight-streaming tiles of
     128x512 with 8 waves, 2-3 of 128x256 with 4 waves, both with the height fitted to the expert; 4-5 tiles of up
