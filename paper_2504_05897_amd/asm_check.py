@@ -42,13 +42,46 @@ def _vregs(operand: str) -> Set[int]:
     return {int(m.group(1))} if m else set()
 
 
+def _waits_for_all(lines: List[Tuple[int, str]], label: str) -> bool:
+    """Whether the text at a label waits for every vector-memory operation before it does anything else (restoring
+    the execution mask and other waits aside): the shared tail of several code paths that ends their loads' time in flight."""
+    at = None
+    for i, (_, raw) in enumerate(lines):
+        if raw.split(";")[0].strip() == label + ":":
+            at = i
+            break
+    if at is None:
+        return False
+    for _, raw in lines[at + 1:]:
+        text = raw.strip()
+        if text.startswith(";;#ASM"):
+            continue
+        text = text.split(";")[0].strip()
+        if not text:
+            continue
+        op, _, rest = text.partition(" ")
+        if op in ("s_or_b64", "s_mov_b64") and rest.strip().startswith("exec"):
+            continue
+        if op == "s_waitcnt" and "vmcnt" not in rest:   # a wait for LDS or scalar loads
+            continue
+        return op == "s_waitcnt" and "vmcnt(0)" in rest
+    return False
+
+
 def _scan_kernel(name: str, lines: Iterable[Tuple[int, str]]) -> List[str]:
+    lines = list(lines)
     # (destination registers of a hand-issued load or empty, line, issued from inline assembly)
     queue: List[Tuple[Set[int], int, bool]] = []
     found: List[str] = []
     in_asm = False
-    jumps = {}            # label -> queues at the branches to it seen so far
+    jumps = {}            # label -> queue at each branch to it seen so far (by the branch's line)
     no_fall_through = False
+    seen_labels = {}      # label -> lines of the hand-issued register loads that were queued when it was scanned
+    # the closing branches of the main loops: the only backward branches a load may be in flight across (what
+    # happens there is recounted by find_wait_count_errors)
+    loops = _loops(lines)
+    closing = {lines[b][0] for a, b in loops
+               if not any((x, y) != (a, b) and a <= x and y <= b for x, y in loops) and _falls_through(lines[a:b + 1])}
     for no, raw in lines:
         text = raw.strip()
         if text.startswith(";;#ASMSTART"):
@@ -61,16 +94,37 @@ def _scan_kernel(name: str, lines: Iterable[Tuple[int, str]]) -> List[str]:
         if text.endswith(":") and not text.startswith(".L") or not text:
             continue
         if text.endswith(":"):
-            if no_fall_through:
-                queue = list(max(jumps.get(text[:-1], [[]]), key=len))
+            # What may be in flight here.  Without a path from above (or with one that has no hand-issued register load
+            # in flight): the longest queue of the branches to the label seen so far.  Otherwise: the queue from above, and behind it (as if youngest: only a wait for everything retires
+            # them) the hand-issued register loads that are in flight at such a branch and not on the path from above.
+            arriving = list(jumps.get(text[:-1], {}).values())
+            if no_fall_through or not any(hand and dest for dest, _, hand in queue):
+                # (a path from above with no such load in flight adds nothing to what the branches bring)
+                queue = list(max(arriving + ([] if no_fall_through else [queue]), key=len, default=[]))
                 no_fall_through = False
+            else:
+                have = {line for _, line, _ in queue}
+                for other in arriving:
+                    for entry in other:
+                        if entry[2] and entry[0] and entry[1] not in have:
+                            queue.append(entry)
+                            have.add(entry[1])
+            seen_labels[text[:-1]] = {line for dest, line, hand in queue if hand and dest}
             continue
         if text.startswith("."):
             continue
         op, _, rest = text.partition(" ")
         if op in ("s_branch", "s_endpgm", "s_setpc_b64") or op.startswith("s_cbranch"):
             if op.startswith(("s_branch", "s_cbranch")):
-                jumps.setdefault(rest.strip(), []).append(list(queue))
+                jumps.setdefault(rest.strip(), {})[no] = list(queue)
+                if rest.strip() in seen_labels and no not in closing:
+                    # A backward branch: if its target was scanned without a load that is in flight here, nothing
+                    # has checked that text against it -- and where paths merge the compiler may copy or reuse
+                    # registers.
+                    loads = [line for dest, line, hand in queue if hand and dest and line not in seen_labels[rest.strip()]]
+                    if loads and not _waits_for_all(lines, rest.strip()):
+                        found.append("%s: line %d: %s goes back to %s while the hand-issued load of line %d may be in flight"
+                                     % (name, no, op, rest.strip(), loads[0]))
             no_fall_through = not op.startswith("s_cbranch")
             continue
         no_fall_through = False
@@ -131,8 +185,9 @@ def find_inflight_hazards(asm_text: str) -> List[str]:
 # ---------------------------------------------------------------------------------------------------------------
 # Recount of the hand-counted waits in the main loops.
 #
-# A main loop is the text from a label to the last branch back to it; branches out of it and forward branches
-# inside it are taken as not taken, which gives the steady-state path (every K step present).  The body is
+# A main loop is the text from a label to the last branch back to it, if it holds no other such stretch and no
+# unconditional branch before its end; branches out of it and forward branches inside it are taken as not taken,
+# which gives the steady-state path (every K step present).  The body is
 # walked several times with one queue of outstanding vector-memory operations, as the hardware keeps it, and from
 # the second walk on:
 #   * a matrix instruction may not read a register of a hand-issued load that a wait has not yet retired (the
@@ -152,6 +207,18 @@ def _loops(lines: List[Tuple[int, str]]) -> List[Tuple[int, int]]:
         if (op == "s_branch" or op.startswith("s_cbranch")) and rest.strip() in labels:
             out[labels[rest.strip()]] = i            # the last backward branch to a label closes its loop
     return sorted(out.items())
+
+
+def _falls_through(body: List[Tuple[int, str]]) -> bool:
+    """Whether execution that enters at the first line reaches the last one with every conditional branch not
+    taken.  A label with a later branch back to it is not always a loop: the compiler also lays a block out in
+    front of code that jumps back to it once (the block then leaves through an unconditional branch before the
+    text reaches that jump)."""
+    for _, raw in body[:-1]:
+        op = raw.split(";")[0].strip().partition(" ")[0]
+        if op in ("s_branch", "s_endpgm", "s_setpc_b64"):
+            return False
+    return True
 
 
 def _scan_loop(name: str, body: List[Tuple[int, str]], walks: int = 5) -> List[str]:
@@ -226,8 +293,15 @@ def find_wait_count_errors(asm_text: str) -> List[str]:
             name, lines = m.group(1), []
         elif line.startswith(".Lfunc_end"):
             if name:
-                for first, last in _loops(lines):
+                loops = _loops(lines)
+                for first, last in loops:
+                    # Only an innermost loop is one straight-line body that repeats; a loop around other loops (a
+                    # block that works through several tiles) is walked through its inner loops.
+                    if any((a, b) != (first, last) and first <= a and b <= last for a, b in loops):
+                        continue
                     body = lines[first:last + 1]
+                    if not _falls_through(body):
+                        continue
                     text = "\n".join(raw for _, raw in body)
                     if "#ASMSTART" in text and "global_load" in text:
                         found += _scan_loop(name, body)

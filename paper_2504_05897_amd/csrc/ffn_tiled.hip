@@ -42,6 +42,11 @@ __device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_ba
                : "v"(gptr), "s"(__builtin_amdgcn_readfirstlane(lds_base))
                : "memory", "m0");
 }
+// 16-byte global store issued by hand (a kernel that keeps hand-issued loads in flight across its epilogue issues
+// every vector-memory operation itself, so that the compiler never waits for, or counts, any of them)
+__device__ __forceinline__ void store_16(void* gptr, const u32x4& v) {
+  asm volatile("global_store_dwordx4 %0, %1, off" ::"v"(gptr), "v"(v) : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -139,55 +144,89 @@ struct StreamTile {
   static constexpr int LDS_VEC = SA * A_CHUNKS;  // 16-byte units
   typedef f32x16_t Acc[FM][FN];
 
+  // Where a thread's copies and weight loads start: a_src[i] is the 16-byte chunk of the activation tile that copy i
+  // of this thread moves (rows past the expert's end clamped to its last row), b_src[j] the thread's piece of the
+  // first weight tile of the wave's group j (groups past N clamped to group 0).  m0 is the tile's first row within
+  // the expert.  NA may exceed A_OPS (a caller that serves tile types of several heights with one set of pointers).
+  template <int NA>
+  static __device__ __forceinline__ void set_sources(const TiledCtx& c, const bf16_t* __restrict__ in, const TileLoc& loc,
+                                                     int m0, int k_begin, int wave, int lane, const u32x4* (&a_src)[NA],
+                                                     const u32x4* (&b_src)[FN]) {
+    const int K = GATEUP ? c.hidden : c.ffn;
+    const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;
+    const int kt16 = K / TILE_K;
+    const char* slot = c.slots + (size_t)c.slot_of[loc.e] * c.slot_bytes;
+    const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+      const int ci = (i * NWV + wave) * 64 + lane;
+      const int r = ci / CPR, sl = ci % CPR;
+      const int chunk = sl ^ ((r / RP) % CPR);
+      const int row = m0 + r < loc.m_rows ? m0 + r : loc.m_rows - 1;
+      const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, loc.row_first + row) : loc.row_first + row;
+      a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk + (size_t)k_begin * CPR;
+    }
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int g = loc.nt * (BN / TILE_N) + wave * FN + j;
+      b_src[j] = w + ((size_t)(g < n_groups ? g : 0) * kt16 + (size_t)k_begin * KK) * 64 + lane;
+    }
+  }
+  // copy `op` of this thread for K step `kstep` (clamped to the last step) into ring stage `stage`
+  template <int NA>
+  static __device__ __forceinline__ void issue_a_op(const u32x4* (&a_src)[NA], uint32_t lds0, int wave, int k_steps,
+                                                    int stage, int kstep, int op) {
+    const uint32_t base = lds0 + (uint32_t)stage * A_CHUNKS * 16;
+    const size_t koff = (size_t)(kstep < k_steps ? kstep : k_steps - 1) * CPR;
+    load_to_lds_16(a_src[op] + koff, base + (uint32_t)((op * NWV + wave) * 64) * 16);
+  }
+  // piece `piece` (of KK) of the copies of one stage
+  template <int NA>
+  static __device__ __forceinline__ void issue_a_piece(const u32x4* (&a_src)[NA], uint32_t lds0, int wave, int k_steps,
+                                                       int stage, int kstep, int piece) {
+#pragma unroll
+    for (int op = 0; op < A_OPS; ++op)
+      if (op >= A_OPS * piece / KK && op < A_OPS * (piece + 1) / KK) issue_a_op(a_src, lds0, wave, k_steps, stage, kstep, op);
+    if (piece == KK - 1) mark_stage_issued();
+  }
+  // The start of a tile: fill the weight ring and SA-1 activation stages.  Nothing is waited for.
+  template <int NA>
+  static __device__ __forceinline__ void issue_prologue(const u32x4* (&a_src)[NA], const u32x4* (&b_src)[FN], uint32_t lds0,
+                                                        int wave, int k_steps, u32x4 (&ring)[DB][FN]) {
+    const int n_sub = k_steps * KK;
+#pragma unroll
+    for (int s = 0; s < DB; ++s)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) ring[s][j] = load_stream_16<NT>(b_src[j] + (size_t)(s < n_sub ? s : n_sub - 1) * 64);
+#pragma unroll
+    for (int st = 0; st < SA - 1; ++st)
+#pragma unroll
+      for (int p = 0; p < KK; ++p) issue_a_piece(a_src, lds0, wave, k_steps, st, st, p);
+  }
+
   // acc += A[rows of the tile, k range] * W[columns of the tile, k range]^T for the k_steps steps of BKT
   // that start at step k_begin.  On return every copy into LDS has landed.
   static __device__ __forceinline__ void mainloop(const TiledCtx& c, const bf16_t* __restrict__ in, const TileLoc& loc,
                                                   int k_begin, int k_steps, u32x4* lds, Acc& acc) {
-    const int e = loc.e, row_first = loc.row_first, m_rows = loc.m_rows, mt = loc.mt, nt = loc.nt;
-    const int K = GATEUP ? c.hidden : c.ffn;
-    const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;
-    const int kt16 = K / TILE_K;
-    const char* slot = c.slots + (size_t)c.slot_of[e] * c.slot_bytes;
-    const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
-    const int m0 = mt * MSTRIDE;
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);  // uniform: LDS bases and weight groups stay scalar
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
+    const u32x4* a_src[A_OPS];
+    const u32x4* b_src[FN];
+    set_sources(c, in, loc, loc.mt * MSTRIDE, k_begin, wave, lane, a_src, b_src);
+    u32x4 ring[DB][FN];
+    issue_prologue(a_src, b_src, lds0, wave, k_steps, ring);
+    steps(a_src, b_src, lds, wave, lane, k_steps, ring, acc);
+  }
+
+  // The K loop of a tile whose prologue has been issued (by this thread, into `ring` and the first SA-1 stages).
+  // On return every vector-memory operation of the thread has completed.
+  template <int NA>
+  static __device__ __forceinline__ void steps(const u32x4* (&a_src)[NA], const u32x4* (&b_src)[FN], u32x4* lds, int wave,
+                                               int lane, int k_steps, u32x4 (&ring)[DB][FN], Acc& acc) {
     const int half = lane / 32, col = lane % 32;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
-
-    const u32x4* a_src[A_OPS];
-#pragma unroll
-    for (int i = 0; i < A_OPS; ++i) {
-      const int ci = (i * NWV + wave) * 64 + lane;
-      const int r = ci / CPR, sl = ci % CPR;
-      const int chunk = sl ^ ((r / RP) % CPR);
-      const int row = m0 + r < m_rows ? m0 + r : m_rows - 1;
-      const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, row_first + row) : row_first + row;
-      a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk + (size_t)k_begin * CPR;
-    }
-    const u32x4* b_src[FN];
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int g = nt * (BN / TILE_N) + wave * FN + j;
-      b_src[j] = w + ((size_t)(g < n_groups ? g : 0) * kt16 + (size_t)k_begin * KK) * 64 + lane;
-    }
     const int n_sub = k_steps * KK;
-    auto issue_a_op = [&](int stage, int kstep, int op) {
-      const uint32_t base = lds0 + (uint32_t)stage * A_CHUNKS * 16;
-      const size_t koff = (size_t)(kstep < k_steps ? kstep : k_steps - 1) * CPR;
-      load_to_lds_16(a_src[op] + koff, base + (uint32_t)((op * NWV + wave) * 64) * 16);
-    };
-    auto issue_a_piece = [&](int stage, int kstep, int piece) {
-      const uint32_t base = lds0 + (uint32_t)stage * A_CHUNKS * 16;
-      const size_t koff = (size_t)(kstep < k_steps ? kstep : k_steps - 1) * CPR;
-#pragma unroll
-      for (int op = 0; op < A_OPS; ++op)
-        if (op >= A_OPS * piece / KK && op < A_OPS * (piece + 1) / KK)
-          load_to_lds_16(a_src[op] + koff, base + (uint32_t)((op * NWV + wave) * 64) * 16);
-      if (piece == KK - 1) mark_stage_issued();
-    };
-
-    u32x4 ring[DB][FN];
     // Activation fragments: two sets with two weight groups per wave (the next substep's set is read while this one
     // is multiplied); one set with one group, where a fragment feeds a single MFMA and is refilled right behind it.
     constexpr int FA_SETS = FN == 1 ? 1 : 2;
@@ -205,15 +244,7 @@ struct StreamTile {
       }
     };
 
-    // ---- prologue: fill the weight ring and SA-1 activation stages, then wait for all of it ----
-#pragma unroll
-    for (int s = 0; s < DB; ++s)
-#pragma unroll
-      for (int j = 0; j < FN; ++j) ring[s][j] = load_stream_16<NT>(b_src[j] + (size_t)(s < n_sub ? s : n_sub - 1) * 64);
-#pragma unroll
-    for (int st = 0; st < SA - 1; ++st)
-#pragma unroll
-      for (int p = 0; p < KK; ++p) issue_a_piece(st, st, p);
+    // ---- the prologue's loads and copies: wait for all of them ----
     wait_vmcnt<0>();
     block_barrier();
     read_a(0, 0, 0);
@@ -257,7 +288,8 @@ struct StreamTile {
                 for (int op = 0; op < A_OPS; ++op)
                   if (op >= A_OPS * kk / KK && op < A_OPS * (kk + 1) / KK) {
                     const int at = FM + 1 + (op - A_OPS * kk / KK);
-                    if (m == (at < 2 * FM - 1 ? at : 2 * FM - 1)) issue_a_op(fill_stage, tt + SA - 1, op);
+                    if (m == (at < 2 * FM - 1 ? at : 2 * FM - 1))
+                      issue_a_op(a_src, lds0, wave, k_steps, fill_stage, tt + SA - 1, op);
                   }
                 if (m == 2 * FM - 1) {
                   if (kk == KK - 1) mark_stage_issued();
@@ -285,7 +317,7 @@ struct StreamTile {
 #pragma unroll
               for (int j = 0; j < FN; ++j)
                 ring[sl][j] = load_stream_16<NT>(b_src[j] + (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64);
-              issue_a_piece(fill_stage, tt + SA - 1, kk);
+              issue_a_piece(a_src, lds0, wave, k_steps, fill_stage, tt + SA - 1, kk);
             }
           }
           stage = next_stage;
@@ -400,6 +432,45 @@ struct StreamTile {
       if (m < m_rows && f < n_out) *(u32x4*)(out + (size_t)(row_first + m) * n_out + f) = v;
     }
   }
+  // The same for a block that goes on to another tile: the staging blocks lie in a region of their own (`staging`, the
+  // activation ring is already being filled for the next tile) and the stores are issued by hand.  The previous tile's
+  // reads of the staging blocks are separated from these writes by that tile's whole K loop.
+  static __device__ __forceinline__ void epilogue_lines_walk(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
+                                                             Acc& acc, u32x4* staging, int wave, int lane) {
+    // The accumulators stay where they are until here: without this the compiler starts to copy them out of the
+    // second register file before the next tile's loads are issued, into registers it frees by moving others.
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
+    const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
+    const int n_out = c.ffn;
+    const int m0 = loc.mt * MSTRIDE;
+    const int half = lane / 32, col = lane % 32;
+    bf16_t* block = (bf16_t*)(staging + (wave / 2) * FM * 32 * 8);  // [FM * 32 rows][64 columns]
+    // (scheduling fences: left alone the scheduler spreads the whole tile's arithmetic over every register it can
+    // find, and the registers of the next tile's loads in flight would be moved out of its way)
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
+        block[row * 64 + (wave % 2) * 32 + col] = f32_to_bf16(silu_f32(acc[i][0][r]) * acc[i][1][r]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    block_barrier();
+    const int f = nt * (BN / 2) + (wave / 2) * 64 + (lane % 8) * 8;
+#pragma unroll
+    for (int k = 0; k < 2 * FM; ++k) {
+      const int row = (wave % 2) * FM * 16 + k * 8 + lane / 8;
+      const u32x4 v = *(const u32x4*)(block + row * 64 + (lane % 8) * 8);
+      const int m = m0 + row;
+      if (m < m_rows && f < n_out) store_16(out + (size_t)(row_first + m) * n_out + f, v);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
   // Down projection with two weight groups per wave: the wave's 64 columns are one 128-byte line per row.  The wave
   // turns its accumulators into rows in a block of its own in the idle activation ring, two fragments (64 rows) at a
   // time, and stores whole lines, 16 bytes per lane.  (LDS serves a wave's accesses in order: no barrier in between.)
@@ -438,6 +509,50 @@ struct StreamTile {
         }
       }
       __builtin_amdgcn_s_waitcnt(0xC07F);  // the rows are in registers before the next pass overwrites the block
+    }
+  }
+  // The same for a block that goes on to another tile (see epilogue_lines_walk): staging blocks in a region of their
+  // own, stores issued by hand.
+  static __device__ __forceinline__ void epilogue_lines_down_walk(const TiledCtx& c, bf16_t* __restrict__ out,
+                                                                  const TileLoc& loc, Acc& acc, u32x4* staging, int wave,
+                                                                  int lane) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
+    const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
+    const int n_out = c.hidden;
+    const int m0 = loc.mt * MSTRIDE;
+    const int half = lane / 32, col = lane % 32;
+    bf16_t* block = (bf16_t*)(staging + wave * 64 * 8);  // [64 rows][64 columns]
+    const int n = nt * BN + wave * 64 + (lane % 8) * 8;
+#pragma unroll
+    for (int pass = 0; pass < (FM + 1) / 2; ++pass) {
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii) {
+        const int i = pass * 2 + ii;
+        if (i < FM) {
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              block[(ii * 32 + (r / 4) * 8 + half * 4 + (r % 4)) * 64 + j * 32 + col] = f32_to_bf16(acc[i][j][r]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int row = k * 8 + lane / 8;
+        if (pass * 2 + row / 32 < FM) {  // uniform per k: the second fragment of the last pass may not exist
+          const u32x4 v = *(const u32x4*)(block + row * 64 + (lane % 8) * 8);
+          const int m = m0 + pass * 64 + row;
+          if (m < m_rows && n < n_out) store_16(out + (size_t)(row_first + m) * n_out + n, v);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // the rows are in registers before the next pass overwrites the block
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
   // Down projection with one weight group per wave: a wave's 32 columns are a quarter of a line.  The block collects
@@ -586,6 +701,132 @@ static void launch_tiles_fit256w(TiledCtx c, int n_rows, const bf16_t* in, bf16_
   hipLaunchKernelGGL((ffn_tile_fit256w_kernel<GATEUP, NT>), dim3((unsigned)c.grid_padded), dim3(256), 0, s, c, in, out);
 }
 
+// The 224x256 tile in a block that works through several tiles (one block per CU, every eighth of the tile list dealt
+// to the blocks of one XCD in turn): before a tile's epilogue the block issues the first loads and copies of its next
+// tile, so their latency passes under the epilogue's arithmetic instead of in front of the next K loop.  The
+// activation ring has three stages and the epilogue a staging region of its own.
+// first loads and copies of a 224-row tile of fm fragments (fm copies per thread and stage, stages of fm * 256 chunks)
+template <bool NT>
+__device__ __forceinline__ void walk_issue_prologue(const u32x4* (&a_src)[7], const u32x4* (&b_src)[2], uint32_t lds0, int wave,
+                                                    int k_steps, int fm, u32x4 (&ring)[8][2]) {
+  const int n_sub = k_steps * 4;
+#pragma unroll
+  for (int s = 0; s < 8; ++s)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) ring[s][j] = load_stream_16<NT>(b_src[j] + (size_t)(s < n_sub ? s : n_sub - 1) * 64);
+#pragma unroll
+  for (int st = 0; st < 2; ++st)
+#pragma unroll
+    for (int op = 0; op < 7; ++op)
+      if (op < fm)  // uniform
+        load_to_lds_16(a_src[op] + (size_t)(st < k_steps ? st : k_steps - 1) * 8,
+                       lds0 + (uint32_t)(st * fm * 256 + (op * 4 + wave) * 64) * 16);
+}
+// every vector-memory operation of the thread has completed; the operands tie the weight ring to the wait
+__device__ __forceinline__ void walk_wait_ring(u32x4 (&r)[8][2]) {
+  asm volatile("s_waitcnt vmcnt(0)"
+               : "+v"(r[0][0]), "+v"(r[0][1]), "+v"(r[1][0]), "+v"(r[1][1]), "+v"(r[2][0]), "+v"(r[2][1]), "+v"(r[3][0]),
+                 "+v"(r[3][1]), "+v"(r[4][0]), "+v"(r[4][1]), "+v"(r[5][0]), "+v"(r[5][1]), "+v"(r[6][0]), "+v"(r[6][1]),
+                 "+v"(r[7][0]), "+v"(r[7][1])
+               :
+               : "memory");
+}
+
+template <bool GATEUP, bool NT, int FM>
+__device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
+                                              const TileWalk<224>& walk, int xcd, int stride, int wave, int lane, int k_steps,
+                                              u32x4* lds, uint32_t lds0, TileLoc& loc, int& idx, int& fm, bool& more,
+                                              const u32x4* (&a_src)[7], const u32x4* (&b_src)[2], u32x4 (&ring)[8][2]) {
+  typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, FM, 2, true> TILE;
+  typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true> FULL;
+  typename TILE::Acc acc;
+  zero_acc<TILE>(acc);
+  constexpr int HELD = 14 - 2 * FM;  // see run_tile
+  f32x16_t held[HELD > 0 ? HELD : 1];
+#pragma unroll
+  for (int i = 0; i < HELD; ++i) asm volatile("" : "=a"(held[i]));
+  int lane_steps = lane;  // (opaque, like the two below: the fragment addresses of the four tile heights are not all kept)
+  asm volatile("" : "+v"(lane_steps));
+  TILE::steps(a_src, b_src, lds, wave, lane_steps, k_steps, ring, acc);
+  block_barrier();  // every wave is through with the activation stages
+  // The next tile's first loads and copies are issued here, without a condition, and waited for below, behind the
+  // epilogue: registers with a load in flight never cross a branch (the compiler may copy a value where control flow
+  // merges, and a copy of such a register reads what has not arrived).  A block at its last tile issues that tile's
+  // first loads once more, unused.
+  const TileLoc done = loc;
+  idx += stride;
+  more = walk.at(xcd, idx, loc);  // leaves loc as it is when there is no further tile
+  if (more) {
+    const int tiles = (loc.m_rows + 223) / 224;
+    const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;
+    fm = fragments < 4 ? 4 : fragments;
+  }
+  {
+    // (an opaque copy of the lane id: what is derived from it here is recomputed per tile instead of being kept in
+    // registers over the K loop, where registers are short)
+    int lane_here = lane;
+    asm volatile("" : "+v"(lane_here));
+    FULL::set_sources(c, in, loc, loc.mt * 32 * fm, 0, wave, lane_here, a_src, b_src);
+    walk_issue_prologue<NT>(a_src, b_src, lds0, wave, k_steps, fm, ring);
+  }
+  int lane_there = lane;
+  asm volatile("" : "+v"(lane_there));
+  if constexpr (GATEUP) TILE::epilogue_lines_walk(c, out, done, acc, lds + FULL::LDS_VEC, wave, lane_there);
+  else TILE::epilogue_lines_down_walk(c, out, done, acc, lds + FULL::LDS_VEC, wave, lane_there);
+  walk_wait_ring(ring);
+#pragma unroll
+  for (int i = 0; i < HELD; ++i) asm volatile("" ::"a"(held[i]));
+}
+
+template <bool GATEUP, bool NT>
+__global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf16_t* __restrict__ in,
+                                                             bf16_t* __restrict__ out) {
+  typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true> FULL;
+  constexpr int STAGING = 2 * 7 * 32 * 8;  // two [224][64] bf16 blocks, in 16-byte units
+  __shared__ u32x4 lds[FULL::LDS_VEC + STAGING];
+  __shared__ int walk_table[TileWalk<224>::TABLE_INTS];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+  TileWalk<224> walk;
+  walk.init(c, walk_table);
+  const int xcd = blockIdx.x % 8, stride = gridDim.x / 8;
+  int idx = blockIdx.x / 8;
+  TileLoc loc;
+  if (!walk.at(xcd, idx, loc)) return;  // uniform over the block
+  const int k_steps = (GATEUP ? c.hidden : c.ffn) / 64;
+  const u32x4* a_src[7];
+  const u32x4* b_src[2];
+  u32x4 ring[8][2];
+  const int tiles = (loc.m_rows + 223) / 224;
+  const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;
+  int fm = fragments < 4 ? 4 : fragments;
+  FULL::set_sources(c, in, loc, loc.mt * 32 * fm, 0, wave, lane, a_src, b_src);
+  walk_issue_prologue<NT>(a_src, b_src, lds0, wave, k_steps, fm, ring);
+  walk_wait_ring(ring);
+  bool more = true;
+  while (more) {
+    if (fm == 7) walk_one_tile<GATEUP, NT, 7>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring);
+    else if (fm == 6) walk_one_tile<GATEUP, NT, 6>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring);
+    else if (fm == 5) walk_one_tile<GATEUP, NT, 5>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring);
+    else walk_one_tile<GATEUP, NT, 4>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring);
+  }
+}
+
+template <bool GATEUP, bool NT>
+static void launch_tiles_walk(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
+  const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
+  c.n_tiles_n = (n_total + 255) / 256;
+  const long bound = (tiles_upper_bound(c, n_rows, 224) + 7) / 8 * 8;
+  long blocks = bound < 256 ? bound : 256;  // one per CU
+  if (const char* env = getenv("HMOE_WALK_BLOCKS")) {  // tuning and tests: fewer blocks, more tiles each
+    const long want = atol(env) / 8 * 8;
+    if (want >= 8 && want < blocks) blocks = want;
+  }
+  c.grid_padded = (int)blocks;
+  hipLaunchKernelGGL((ffn_tile_walk_kernel<GATEUP, NT>), dim3((unsigned)c.grid_padded), dim3(256), 0, s, c, in, out);
+}
+
 // Tile shapes built into the library.  hmoe picks one from the average rows per expert; the
 // environment variable HMOE_TILED_VARIANT (an index into this table) overrides the choice for
 // tuning runs.
@@ -605,7 +846,9 @@ enum {
   V_FIT256 = 4,         // tiles of up to 256 rows, one weight group per wave: 256x256 (gate/up, 8 waves), 256x128 (down, 4 waves)
   V_FIT256_PLAIN = 5,
   V_FIT256W = 6,        // 256x256, 4 waves, two weight groups per wave, one wave per SIMD
-  V_FIT256W_PLAIN = 7
+  V_FIT256W_PLAIN = 7,
+  V_WALK = 8,           // the same tile in blocks that work through several tiles each
+  V_WALK_PLAIN = 9
 };
 static const TiledVariant kVariants[] = {
     HMOE_STREAM_FIT("stream 128x512 fit", 8, true),
@@ -616,6 +859,8 @@ static const TiledVariant kVariants[] = {
     HMOE_STREAM_FIT256("stream 256x256/128 fit plain", 8, 4, false),
     {"stream 224x256, 4 waves", launch_tiles_fit256w<true, true>, launch_tiles_fit<false, 8, true>},
     {"stream 224x256, 4 waves, plain", launch_tiles_fit256w<true, false>, launch_tiles_fit<false, 8, false>},
+    {"stream 224x256, walking blocks", launch_tiles_walk<true, true>, launch_tiles_walk<false, true>},
+    {"stream 224x256, walking blocks, plain", launch_tiles_walk<true, false>, launch_tiles_walk<false, false>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -650,6 +895,13 @@ int launch_ffn_tiled(const FfnArgs& a) {
   if (shared_panels) {
     v_gate_up = V_FIT4_PLAIN;
     v_down = tiles_down < 256 || d.ffn >= 4096 ? V_FIT4_PLAIN : V_FIT_PLAIN;
+    // Launches of at least seven rounds of 224x256 tiles (the routed experts of a large batch) take that tile with one
+    // wave per SIMD, in blocks that walk through their tiles: measured per layer, stress shape -3 %, Qwen2 shape -3 %
+    // (down projection -6 %, gate/up -1 ... -4 %).  With fewer rounds the last, partly filled one costs more than
+    // the tile gains (a dense shared expert: 3-25 % slower).
+    const long m_tiles_224 = (long)a.n_rows / 224 + std::min(d.n_experts, a.n_rows);
+    if (m_tiles_224 * ((2 * d.ffn + 255) / 256) >= 7 * 256) v_gate_up = V_WALK_PLAIN;
+    if (m_tiles_224 * ((d.hidden + 255) / 256) >= 7 * 256) v_down = V_WALK_PLAIN;
   } else {
     if (few_gate_up) v_gate_up = V_FIT256;
     else if (d.hidden < 4096 && a.n_rows <= 32 * d.n_experts) v_gate_up = V_FIT4;

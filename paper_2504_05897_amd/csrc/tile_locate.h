@@ -77,6 +77,69 @@ __device__ __forceinline__ bool locate_tile(const TiledCtx& c, TileLoc& t) {
   return false;
 }
 
+// The same tile list for a block that works through several tiles: the per-expert prefix sums are computed once into
+// a table in LDS (3 * HMOE_MAX_EXPERTS ints: first row, rows, inclusive tile count), and entry idx of the xcd-th eighth
+// of the list is looked up on demand.  Every wave of the block computes and writes the same table.
+template <int BM>
+struct TileWalk {
+  static constexpr int CH = HMOE_MAX_EXPERTS / 64;
+  static constexpr int TABLE_INTS = 3 * HMOE_MAX_EXPERTS;
+  int total, per_xcd, n_tiles_n;
+  int* tab;
+  __device__ __forceinline__ void init(const TiledCtx& c, int* table) {
+    const int lane = threadIdx.x % 64;
+    tab = table;
+    n_tiles_n = c.n_tiles_n;
+    int sum = 0;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      int first = 0, rows = 0, incl = sum;
+      if (j * 64 < c.n_experts) {  // uniform
+        const int i = j * 64 + lane;
+        if (i < c.n_experts && ((c.active.w[j] >> lane) & 1ull) && c.slot_of[i] >= 0) {
+          first = c.offsets[i];
+          rows = c.offsets[i + 1] - first;
+        }
+        int v = (rows + BM - 1) / BM * c.n_tiles_n;
+#pragma unroll
+        for (int d = 1; d < 64; d *= 2) {
+          const int below = __shfl_up(v, d);
+          if (lane >= d) v += below;
+        }
+        incl = sum + v;
+        sum += __shfl(v, 63);
+      }
+      tab[j * 64 + lane] = first;
+      tab[HMOE_MAX_EXPERTS + j * 64 + lane] = rows;
+      tab[2 * HMOE_MAX_EXPERTS + j * 64 + lane] = incl;
+    }
+    total = __builtin_amdgcn_readfirstlane(sum);
+    per_xcd = (total + 7) / 8;
+    __syncthreads();
+  }
+  __device__ __forceinline__ bool at(int xcd, int idx, TileLoc& t) const {
+    const int lane = threadIdx.x % 64;
+    const int tile_id = xcd * per_xcd + idx;
+    if (idx >= per_xcd || tile_id >= total) return false;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const unsigned long long past = __ballot(tab[2 * HMOE_MAX_EXPERTS + j * 64 + lane] > tile_id);  // monotone
+      if (past) {
+        const int e = j * 64 + __ffsll((long long)past) - 1;
+        t.e = e;
+        t.row_first = __builtin_amdgcn_readfirstlane(tab[e]);
+        t.m_rows = __builtin_amdgcn_readfirstlane(tab[HMOE_MAX_EXPERTS + e]);
+        const int mts = (t.m_rows + BM - 1) / BM;
+        const int within = tile_id - (__builtin_amdgcn_readfirstlane(tab[2 * HMOE_MAX_EXPERTS + e]) - mts * n_tiles_n);
+        t.nt = within / mts;
+        t.mt = within % mts;
+        return true;
+      }
+    }
+    return false;
+  }
+};
+
 // upper bound of the tile count of a launch (sum over experts of ceil(rows / BM) is at most this)
 static inline long tiles_upper_bound(const TiledCtx& c, int n_rows, int bm) {
   return ((long)n_rows / bm + (c.n_experts < n_rows ? c.n_experts : n_rows)) * c.n_tiles_n;

@@ -140,3 +140,46 @@ def test_wait_recount_activation_stages():
     assert check(_loop(body(2, 3))) != []
     # a loop without hand-issued operations is not looked at
     assert check(_loop("\tglobal_load_dword v9, v[2:3], off\n\ts_waitcnt vmcnt(0)\n")) == []
+
+
+def test_load_in_flight_where_paths_merge():
+    """What faulted once: a block that issues its next tile's loads before its epilogue.  Where the path with the
+    loads in flight met one without, the compiler copied the ring registers and reused them for a store address."""
+    check = _load("asm_check").find_inflight_hazards
+    copy = "\tv_mov_b64_e32 v[20:21], v[10:11]\n\tv_lshl_add_u64 v[10:11], v[4:5], 0, s[2:3]\n\ts_waitcnt vmcnt(0)\n"
+    # a clean path falls into the label, a branch brings the load: the copy and the reuse behind the label are reported
+    merged = listing(HAND + "\ts_branch .LBB0_3\n.LBB0_2:\n\ts_nop 0\n.LBB0_3:\n" + copy)
+    found = check(merged)
+    assert len(found) == 2 and "v_mov_b64_e32 reads v[10, 11]" in found[0] and "writes v[10, 11]" in found[1]
+    # the same with the wait first: clean
+    assert check(listing(HAND + "\ts_branch .LBB0_3\n.LBB0_2:\n\ts_nop 0\n.LBB0_3:\n\ts_waitcnt vmcnt(0)\n" + copy)) == []
+    # a branch back to text that was scanned without the load: reported, whatever that text does ...
+    back = listing(".LBB0_1:\n\tv_mov_b32_e32 v30, 0\n\ts_branch .LBB0_3\n.LBB0_2:\n" + HAND + "\ts_branch .LBB0_1\n"
+                   ".LBB0_3:\n\ts_waitcnt vmcnt(0)\n")
+    found = check(back)
+    assert len(found) == 1 and "goes back to .LBB0_1" in found[0]
+    # ... unless that text starts by waiting for everything (the shared tail of several paths)
+    tail = listing(".LBB0_1:\n\ts_or_b64 exec, exec, s[0:1]\n\ts_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(0)\n\ts_branch .LBB0_3\n.LBB0_2:\n"
+                   + HAND + "\ts_branch .LBB0_1\n.LBB0_3:\n\ts_endpgm\n")
+    assert check(tail) == []
+    # the closing branch of a main loop is where loads are meant to be in flight
+    loop = listing(".LBB0_1:\n\ts_waitcnt vmcnt(0)\n\tv_mfma_f32_32x32x16_bf16 v[50:65], v[10:13], v[44:47], v[50:65]\n" + HAND
+                   + "\ts_cbranch_scc1 .LBB0_1\n\ts_waitcnt vmcnt(0)\n")
+    assert check(loop) == []
+
+
+def test_wait_recount_skips_what_is_not_a_loop():
+    """A stretch from a label to a later branch back to it is walked as a loop only if it holds no other such stretch
+    and no unconditional branch: a block that works through several tiles has its K loops inside a tile loop, and the
+    compiler lays single K steps out in front of code that jumps back to them once."""
+    check = _load("asm_check").find_wait_count_errors
+    step = ("\ts_waitcnt vmcnt(1)\n\tv_mfma_f32_32x32x16_bf16 v[50:65], v[10:13], v[44:47], v[50:65]\n" + HAND)
+    # one K step per walk with a ring of two would need vmcnt(1) to retire the load it reads: as a loop it is wrong ...
+    assert check(listing(".LBB0_1:\n" + step + "\ts_cbranch_scc1 .LBB0_1\n")) != []
+    # ... but not if the stretch leaves through an unconditional branch before its end (a step laid out on its own)
+    assert check(listing(".LBB0_1:\n" + step + "\ts_branch .LBB0_3\n.LBB0_2:\n\ts_nop 0\n\ts_cbranch_scc1 .LBB0_1\n.LBB0_3:\n")) == []
+    # ... and an outer loop around a correct inner one is not walked as one body
+    good = ("\ts_waitcnt vmcnt(0)\n\tv_mfma_f32_32x32x16_bf16 v[50:65], v[10:13], v[44:47], v[50:65]\n" + HAND)
+    nested = listing(".LBB0_0:\n" + HAND.replace("v[10:13]", "v[30:33]") + ".LBB0_1:\n" + good + "\ts_cbranch_scc1 .LBB0_1\n"
+                     "\tv_mfma_f32_32x32x16_bf16 v[50:65], v[30:33], v[44:47], v[50:65]\n\ts_cbranch_scc1 .LBB0_0\n")
+    assert check(nested) == []

@@ -203,7 +203,7 @@ def test_ffn_bf16_paths(hm, path, hidden, ffn, counts):
     assert np.abs(ref).max() > 1e-2
 
 
-@pytest.mark.parametrize("variant", range(8))
+@pytest.mark.parametrize("variant", range(10))
 def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
     """The library's tuning override selects each built-in prefill kernel in turn (0-1 weight-streaming tiles of
     128x512 with 8 waves, 2-3 of 128x256 with 4 waves, both with the height fitted to the expert; 4-5 tiles of up
@@ -226,6 +226,23 @@ def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
         assert max_rel_err(got, ref) < TOL[wl.BF16]
 
 
+@pytest.mark.parametrize("blocks", [8, 24])
+def test_ffn_blocks_that_walk_through_tiles(hm, blocks, monkeypatch):
+    """The 224x256 tile in blocks that take several tiles each (variants 8 and 9, the choice for large routed
+    launches): few blocks, so that every block walks through tiles of every height the tile comes in (4-7 fragments,
+    experts below 97 rows padded to 4), of several experts and n-tiles, with an odd and an even number of K steps,
+    and issues each next tile's first loads under the epilogue of the one before."""
+    say("ffn walking blocks", blocks)
+    monkeypatch.setenv("HMOE_WALK_BLOCKS", str(blocks))
+    counts = [225, 700, 31, 450, 0, 129, 224, 1, 600, 353, 161, 97, 900, 260, 0, 512]
+    for variant, hidden, ffn in ((9, 320, 384), (8, 512, 192), (9, 192, 640)):
+        monkeypatch.setenv("HMOE_TILED_VARIANT", str(variant))
+        shape = wl.small_shape(dtype=wl.BF16, hidden=hidden, ffn=ffn, n_experts=len(counts), top_k=2)
+        got, ref = _ffn_case(hm, shape, counts, 3, seed=blocks + hidden)
+        assert max_rel_err(got, ref) < TOL[wl.BF16]
+        assert np.abs(ref).max() > 1e-3
+
+
 @pytest.mark.parametrize("hidden,ffn,counts", [
     (256, 512, [64]),                        # one small dense expert, few tiles: 256-row tiles for both projections
     (256, 512, [300]),                       # one large expert: 4-wave tiles, plain loads
@@ -233,6 +250,8 @@ def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
     (128, 4096, [200, 390, 1, 250]),         # large experts, long K in the down projection: 4-wave tiles for both
     (1536, 256, [100] * 60 + [0, 399, 1, 7]),  # 128x512 tiles, non-temporal loads, for both
     (1024, 128, [200] * 63 + [333]),         # large experts, short K, many tiles: 4-wave gate/up, 128x512 down, plain loads
+    (2048, 128, [1200, 1400] * 17),          # seven rounds of 224x256 tiles in the down projection: walking blocks there
+    (128, 1024, [1300, 1250] * 17),          # ... and in gate/up
 ])
 def test_ffn_prefill_choice_branches(hm, hidden, ffn, counts):
     """The prefill path without a tuning override, on launches built to take each branch of the library's kernel
