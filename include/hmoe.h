@@ -244,6 +244,16 @@ int32_t hmoe_cache_plan(hmoe_cache* cache, const int32_t* h_counts, int32_t* h_w
                         int32_t* h_victim, int32_t* n_waves);
 
 /*
+ * Shared experts (Section II-A) run as a dense FFN of their own, usually next to the routed experts' FFN on a second
+ * stream.  hmoe_cache_set_layer tells the cache of such an FFN (one expert, one slot) which routed layer it belongs to
+ * (`routed`: same hidden size and dtype; copied; NULL forgets it): prefill launches over that cache then choose their
+ * kernels as the routed launches of a batch of the same tokens do, so that the two share the CUs well.  Host only;
+ * results do not depend on it.  HMOE_ERR_INVALID_ARG for a cache of more than one expert or a layer that does not
+ * match.
+ */
+int32_t hmoe_cache_set_layer(hmoe_cache* cache, const hmoe_layer_desc* routed);
+
+/*
  * Score-aware replacement (Section IV-D, Eq. (3)): the Minus Recent Score policy keeps a priority
  * estimate S per expert, S <- alpha * TopP(s) + (1 - alpha) * S, where s are the routing scores of the
  * current iteration and only the p largest are accumulated (the paper uses p = 2K); the victim is the

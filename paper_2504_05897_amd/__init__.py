@@ -43,7 +43,7 @@ EXPORTS = [
     "hmoe_router_route_permute", "hmoe_expert_ffn_grouped_with_shared", "hmoe_ffn_combine_sync_bytes", "hmoe_expert_ffn_combine",
     "hmoe_expert_ffn_staged",
     "hmoe_combine",
-    "hmoe_cache_set_policy", "hmoe_cache_update_scores", "hmoe_cache_get_scores",
+    "hmoe_cache_set_policy", "hmoe_cache_update_scores", "hmoe_cache_get_scores", "hmoe_cache_set_layer",
     "hmoe_route_scores_workspace_bytes", "hmoe_route_scores",
     "hmoe_schedule_simulate", "hmoe_schedule_plan",
     "hmoe_probe_arm", "hmoe_probe_read",
@@ -117,6 +117,7 @@ def _load() -> ctypes.CDLL:
     lib.hmoe_router_route_permute.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.hmoe_combine.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp]
     lib.hmoe_cache_set_policy.argtypes = [vp, i32, ctypes.c_float]
+    lib.hmoe_cache_set_layer.argtypes = [vp, dp]
     lib.hmoe_cache_update_scores.argtypes = [vp, vp, i32]
     lib.hmoe_cache_get_scores.argtypes = [vp, vp]
     lib.hmoe_route_scores_workspace_bytes.restype = sz
@@ -344,6 +345,10 @@ def hmoe_combine(desc, o_perm, inv_perm, topk_w, o_shared, T, y, stream=None):
                              _ptr(y), _stream(stream)), "hmoe_combine")
 
 
+def hmoe_cache_set_layer(cache, routed_desc):
+    _check(_lib.hmoe_cache_set_layer(cache, None if routed_desc is None else ctypes.byref(routed_desc)), "hmoe_cache_set_layer")
+
+
 def hmoe_cache_set_policy(cache, policy: int, alpha: float = 0.5):
     _check(_lib.hmoe_cache_set_policy(cache, policy, alpha), "hmoe_cache_set_policy")
 
@@ -485,6 +490,7 @@ class MoELayer:
             self.shared_slot_of = torch.empty(1, dtype=torch.int32, device=self.dev)
             self.shared_cache = hmoe_cache_create(self.shared_desc, self.shared_slots, self.shared_slot_of)
             hmoe_cache_stage(self.shared_cache, 0, 0, None)
+            hmoe_cache_set_layer(self.shared_cache, desc)
         self.h_packed_ptrs = (ctypes.c_void_p * E)(*[t.data_ptr() for t in self.h_packed]) if host_copies else None
         self._alloc(max_tokens)
         for s, e in enumerate(range(S) if resident is None else resident):

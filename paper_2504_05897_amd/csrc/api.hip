@@ -232,6 +232,7 @@ extern "C" int32_t hmoe_cache_create(const hmoe_layer_desc* desc, void* slot_sto
   c->use_seq = 0;
   c->track_reads = desc->n_slots < desc->n_experts;
   c->reads_in_graphs = false;
+  c->has_beside = false;
   c->slot_last_read.assign(desc->n_slots, 0);
   c->ready_ev.assign(desc->n_slots, nullptr);
   for (auto& e : c->use_ev) e = nullptr;
@@ -396,6 +397,20 @@ extern "C" int32_t hmoe_cache_set_policy(hmoe_cache* c, int32_t policy, float al
   return HMOE_OK;
 }
 
+extern "C" int32_t hmoe_cache_set_layer(hmoe_cache* c, const hmoe_layer_desc* routed) {
+  if (!c) return HMOE_ERR_INVALID_ARG;
+  if (!routed) {
+    c->has_beside = false;
+    return HMOE_OK;
+  }
+  int rc = check_desc(routed);
+  if (rc != HMOE_OK) return rc;
+  if (c->desc.n_experts != 1 || routed->hidden != c->desc.hidden || routed->dtype != c->desc.dtype) return HMOE_ERR_INVALID_ARG;
+  c->beside = *routed;
+  c->has_beside = true;
+  return HMOE_OK;
+}
+
 extern "C" int32_t hmoe_cache_update_scores(hmoe_cache* c, const float* h_scores, int32_t top_p) {
   if (!c || !h_scores || top_p < 1) return HMOE_ERR_INVALID_ARG;
   const int E = c->desc.n_experts;
@@ -454,6 +469,7 @@ static int32_t ffn_prepare(const hmoe_layer_desc* desc, hmoe_cache* cache, const
   a.o_perm = o_perm;
   a.h = workspace;
   a.stream = (hipStream_t)stream;
+  a.beside = cache->has_beside ? &cache->beside : nullptr;
   memset(&a.active, 0, sizeof(a.active));
   if (h_active) {
     for (int i = 0; i < n_active; ++i) {

@@ -135,6 +135,7 @@ struct FfnArgs {
   void* o_perm = nullptr;
   void* h = nullptr;                  // workspace [A, F]
   hipStream_t stream = nullptr;
+  const hmoe_layer_desc* beside = nullptr;  // a dense FFN over all tokens: the routed layer it runs next to, if known
 };
 // the sum of Eq. (1) computed inside the down projection's launch (decode batches)
 struct CombineArgs {
@@ -177,4 +178,6 @@ struct hmoe_cache {
   std::vector<uint64_t> slot_last_read;  // [S], 0 = never
   std::vector<hipEvent_t> ready_ev;      // [S]
   hipEvent_t fence_ev;
+  hmoe_layer_desc beside;                // hmoe_cache_set_layer: the routed layer these (shared) experts belong to
+  bool has_beside;
 };

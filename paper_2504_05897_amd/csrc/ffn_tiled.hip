@@ -895,13 +895,19 @@ int launch_ffn_tiled(const FfnArgs& a) {
   if (shared_panels) {
     v_gate_up = V_FIT4_PLAIN;
     v_down = tiles_down < 256 || d.ffn >= 4096 ? V_FIT4_PLAIN : V_FIT_PLAIN;
-    // Launches of at least seven rounds of 224x256 tiles (the routed experts of a large batch) take that tile with one
-    // wave per SIMD, in blocks that walk through their tiles: measured per layer, stress shape -3 %, Qwen2 shape -3 %
-    // (down projection -6 %, gate/up -1 ... -4 %).  With fewer rounds the last, partly filled one costs more than
-    // the tile gains (a dense shared expert: 3-25 % slower).
-    const long m_tiles_224 = (long)a.n_rows / 224 + std::min(d.n_experts, a.n_rows);
-    if (m_tiles_224 * ((2 * d.ffn + 255) / 256) >= 7 * 256) v_gate_up = V_WALK_PLAIN;
-    if (m_tiles_224 * ((d.hidden + 255) / 256) >= 7 * 256) v_down = V_WALK_PLAIN;
+    // A layer whose routed experts make at least seven rounds of 224x256 tiles (a large batch) takes that tile with
+    // one wave per SIMD, in blocks that walk through their tiles -- for both projections, and for the layer's shared
+    // experts too (hmoe_cache_set_layer tells their launches which layer they run beside): stress shape -3.5 % per
+    // layer, Qwen2 shape unchanged.  A block of these fills its CU, one of the other kernels half of one, and
+    // launches of both kinds next to each other on two streams keep each other waiting (+2 %); alone, a dense
+    // expert of a few rounds is 3-25 % slower with the large tile (its last, partly filled round).
+    const hmoe_layer_desc& lay = a.beside ? *a.beside : d;
+    const long lay_rows = a.beside ? (long)a.n_rows * lay.top_k : a.n_rows;
+    const long m_tiles_224 = lay_rows / 224 + std::min((long)lay.n_experts, lay_rows);
+    long min_rounds = 7;
+    if (const char* env = getenv("HMOE_WALK_MIN_ROUNDS")) min_rounds = atol(env);  // tuning
+    if (lay_rows / lay.n_experts >= 192 &&
+        m_tiles_224 * ((2 * lay.ffn + 255) / 256) >= min_rounds * 256) v_gate_up = v_down = V_WALK_PLAIN;
   } else {
     if (few_gate_up) v_gate_up = V_FIT256;
     else if (d.hidden < 4096 && a.n_rows <= 32 * d.n_experts) v_gate_up = V_FIT4;

@@ -4,6 +4,8 @@ Integer results (top-k ids, permutation, offsets, slot maps) must match bit for 
 point within the stated tolerance."""
 import sys
 
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -224,6 +226,42 @@ def test_ffn_every_prefill_tile_shape(hm, variant, monkeypatch):
         shape = wl.small_shape(dtype=wl.BF16, hidden=hidden, ffn=ffn, n_experts=4, top_k=2)
         got, ref = _ffn_case(hm, shape, [130, 0, 7, 128], 3, seed=variant + hidden)
         assert max_rel_err(got, ref) < TOL[wl.BF16]
+
+
+def test_cache_set_layer_checks_and_changes_no_result(hm):
+    """hmoe_cache_set_layer: only a one-expert cache of the layer's hidden size and dtype takes it; a dense FFN over
+    such a cache then chooses its prefill kernels as the routed layer does (here: the walking blocks, which the dense
+    launch alone would not take) and gives the same bits."""
+    say("cache set layer")
+    routed = wl.small_shape(dtype=wl.BF16, hidden=128, ffn=1024, n_experts=32, top_k=8)
+    dense = wl.small_shape(dtype=wl.BF16, hidden=128, ffn=256, n_experts=1, top_k=1)
+    T = 5600   # routed: 44800 rows, 1400 per expert, (200 + 32) * 8 = 1856 tiles of 224 x 256 >= 7 * 256
+    lay = wl.make_layer(dense, 3, n_tokens=1)
+    d = desc_of(hm, dense, n_slots=1)
+    rng = np.random.default_rng(11)
+    x = wl.store(rng.standard_normal((T, dense.hidden)).astype(np.float32), dense.dtype)
+    layer = hm.MoELayer(d, lay.experts, (), None, max_tokens=T + 1)
+    offsets = to_device(np.array([0, T], np.int32))
+    ws_bytes = hm.hmoe_ffn_workspace_bytes(d, T)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    outs = []
+    for beside in (None, desc_of(hm, routed, n_slots=32), None):
+        hm.hmoe_cache_set_layer(layer.cache, beside)
+        o = torch.zeros(T, dense.hidden, dtype=layer.dt, device=DEV)
+        hm.hmoe_expert_ffn_grouped(d, layer.cache, to_device(x), offsets, T, None, o, ws, ws_bytes, 3)
+        torch.cuda.synchronize()
+        outs.append(o.view(torch.int16).cpu().numpy().copy())
+    assert (outs[0] == outs[1]).all() and (outs[0] == outs[2]).all()
+    ref = orc.expert_ffn(wl.as_f64(x[:256]), *(wl.as_f64(m) for m in lay.experts[0]))
+    assert max_rel_err(to_host_f32(o)[:256], ref) < TOL[wl.BF16]
+    other = desc_of(hm, wl.small_shape(dtype=wl.BF16, hidden=256, ffn=1024, n_experts=32, top_k=8), n_slots=32)
+    assert hm._lib.hmoe_cache_set_layer(layer.cache, ctypes.byref(other)) == hm.HMOE_ERR_INVALID_ARG   # another hidden size
+    layer.close()
+    two = wl.small_shape(dtype=wl.BF16, hidden=128, ffn=64, n_experts=2, top_k=1)
+    lay2 = wl.make_layer(two, 4, n_tokens=1)
+    layer2 = hm.MoELayer(desc_of(hm, two, n_slots=2), lay2.experts, (), None, max_tokens=4)
+    assert hm._lib.hmoe_cache_set_layer(layer2.cache, ctypes.byref(desc_of(hm, routed, n_slots=32))) == hm.HMOE_ERR_INVALID_ARG
+    layer2.close()
 
 
 @pytest.mark.parametrize("blocks", [8, 24])

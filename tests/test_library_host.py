@@ -147,3 +147,4 @@ def test_new_entry_points_reject_bad_arguments_on_the_host(hm):
     sargs[0] = ctypes.byref(ok)
     sargs[5], sargs[10], sargs[11] = 0, 0, 0
     assert lib.hmoe_expert_ffn_staged(*sargs) == hm.HMOE_ERR_INVALID_ARG          # no cache, no counts, no plan arrays
+    assert lib.hmoe_cache_set_layer(None, ctypes.byref(ok)) == hm.HMOE_ERR_INVALID_ARG      # no cache
