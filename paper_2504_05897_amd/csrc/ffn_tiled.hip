@@ -445,7 +445,7 @@ struct StreamTile {
       for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
     const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
     const int n_out = c.ffn;
-    const int m0 = loc.mt * MSTRIDE;
+    const int m0 = loc.m0;
     const int half = lane / 32, col = lane % 32;
     bf16_t* block = (bf16_t*)(staging + (wave / 2) * FM * 32 * 8);  // [FM * 32 rows][64 columns]
     // (scheduling fences: left alone the scheduler spreads the whole tile's arithmetic over every register it can
@@ -522,7 +522,7 @@ struct StreamTile {
       for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
     const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
     const int n_out = c.hidden;
-    const int m0 = loc.mt * MSTRIDE;
+    const int m0 = loc.m0;
     const int half = lane / 32, col = lane % 32;
     bf16_t* block = (bf16_t*)(staging + wave * 64 * 8);  // [64 rows][64 columns]
     const int n = nt * BN + wave * 64 + (lane % 8) * 8;
@@ -734,7 +734,7 @@ __device__ __forceinline__ void walk_wait_ring(u32x4 (&r)[8][2]) {
 
 template <bool GATEUP, bool NT, int FM>
 __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
-                                              const TileWalk<224>& walk, int xcd, int stride, int wave, int lane, int k_steps,
+                                              const TileWalk<4>& walk, int xcd, int stride, int wave, int lane, int k_steps,
                                               u32x4* lds, uint32_t lds0, TileLoc& loc, int& idx, int& fm, bool& more,
                                               const u32x4* (&a_src)[7], const u32x4* (&b_src)[2], u32x4 (&ring)[8][2]) {
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, FM, 2, true> TILE;
@@ -756,17 +756,13 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
   const TileLoc done = loc;
   idx += stride;
   more = walk.at(xcd, idx, loc);  // leaves loc as it is when there is no further tile
-  if (more) {
-    const int tiles = (loc.m_rows + 223) / 224;
-    const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;
-    fm = fragments < 4 ? 4 : fragments;
-  }
+  fm = loc.fm;
   {
     // (an opaque copy of the lane id: what is derived from it here is recomputed per tile instead of being kept in
     // registers over the K loop, where registers are short)
     int lane_here = lane;
     asm volatile("" : "+v"(lane_here));
-    FULL::set_sources(c, in, loc, loc.mt * 32 * fm, 0, wave, lane_here, a_src, b_src);
+    FULL::set_sources(c, in, loc, loc.m0, 0, wave, lane_here, a_src, b_src);
     walk_issue_prologue<NT>(a_src, b_src, lds0, wave, k_steps, fm, ring);
   }
   int lane_there = lane;
@@ -784,11 +780,11 @@ __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true> FULL;
   constexpr int STAGING = 2 * 7 * 32 * 8;  // two [224][64] bf16 blocks, in 16-byte units
   __shared__ u32x4 lds[FULL::LDS_VEC + STAGING];
-  __shared__ int walk_table[TileWalk<224>::TABLE_INTS];
+  __shared__ int walk_table[TileWalk<4>::TABLE_INTS];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
-  TileWalk<224> walk;
+  TileWalk<4> walk;
   walk.init(c, walk_table);
   const int xcd = blockIdx.x % 8, stride = gridDim.x / 8;
   int idx = blockIdx.x / 8;
@@ -798,10 +794,8 @@ __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf
   const u32x4* a_src[7];
   const u32x4* b_src[2];
   u32x4 ring[8][2];
-  const int tiles = (loc.m_rows + 223) / 224;
-  const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;
-  int fm = fragments < 4 ? 4 : fragments;
-  FULL::set_sources(c, in, loc, loc.mt * 32 * fm, 0, wave, lane, a_src, b_src);
+  int fm = loc.fm;
+  FULL::set_sources(c, in, loc, loc.m0, 0, wave, lane, a_src, b_src);
   walk_issue_prologue<NT>(a_src, b_src, lds0, wave, k_steps, fm, ring);
   walk_wait_ring(ring);
   bool more = true;
@@ -817,7 +811,16 @@ template <bool GATEUP, bool NT>
 static void launch_tiles_walk(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
   const int n_total = GATEUP ? 2 * c.ffn : c.hidden;
   c.n_tiles_n = (n_total + 255) / 256;
-  const long bound = (tiles_upper_bound(c, n_rows, 224) + 7) / 8 * 8;
+  // The most fragments an m-tile may have.  Lower heights for launches of few rounds (whose partly filled last round
+  // weighs more) were measured: a dense expert alone gains 10-23 %, routed experts lose 8 %, and the layer, whose
+  // two FFNs overlap, stays where it is; 7 is kept.
+  int cap = 7;
+  if (const char* env = getenv("HMOE_WALK_CAP")) {  // tuning
+    const int want = atoi(env);
+    if (want >= 4 && want <= 7) cap = want;
+  }
+  c.walk_bm = 32 * cap;
+  const long bound = (tiles_upper_bound(c, n_rows, c.walk_bm) + 7) / 8 * 8;
   long blocks = bound < 256 ? bound : 256;  // one per CU
   if (const char* env = getenv("HMOE_WALK_BLOCKS")) {  // tuning and tests: fewer blocks, more tiles each
     const long want = atol(env) / 8 * 8;

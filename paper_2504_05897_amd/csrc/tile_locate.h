@@ -16,6 +16,7 @@ struct TiledCtx {
   int grid_padded;  // blocks launched: an upper bound of the tile count, a multiple of 8
   const int32_t* row_map;  // gate/up only: input row of sorted row p is row_map[p] / map_div
   int map_div;
+  int walk_bm = 224;  // blocks that walk through tiles: the most rows an m-tile may have (a multiple of 32)
 };
 
 // The tile a block works on.  The logical tile list is: for each busy expert in ascending id (rows > 0,
@@ -27,6 +28,7 @@ struct TiledCtx {
 // experts, and every wave of the block computes the same answer.  Returns false for surplus blocks.
 struct TileLoc {
   int e, row_first, m_rows, mt, nt;
+  int m0, fm;  // TileWalk only: first row of the tile within the expert, and its height in 32-row fragments
 };
 template <int BM>
 __device__ __forceinline__ bool locate_tile(const TiledCtx& c, TileLoc& t) {
@@ -80,16 +82,17 @@ __device__ __forceinline__ bool locate_tile(const TiledCtx& c, TileLoc& t) {
 // The same tile list for a block that works through several tiles: the per-expert prefix sums are computed once into
 // a table in LDS (3 * HMOE_MAX_EXPERTS ints: first row, rows, inclusive tile count), and entry idx of the xcd-th eighth
 // of the list is looked up on demand.  Every wave of the block computes and writes the same table.
-template <int BM>
+template <int MIN_FM>
 struct TileWalk {
   static constexpr int CH = HMOE_MAX_EXPERTS / 64;
   static constexpr int TABLE_INTS = 3 * HMOE_MAX_EXPERTS;
-  int total, per_xcd, n_tiles_n;
+  int total, per_xcd, n_tiles_n, bm;
   int* tab;
   __device__ __forceinline__ void init(const TiledCtx& c, int* table) {
     const int lane = threadIdx.x % 64;
     tab = table;
     n_tiles_n = c.n_tiles_n;
+    bm = c.walk_bm;
     int sum = 0;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
@@ -100,7 +103,7 @@ struct TileWalk {
           first = c.offsets[i];
           rows = c.offsets[i + 1] - first;
         }
-        int v = (rows + BM - 1) / BM * c.n_tiles_n;
+        int v = (rows + bm - 1) / bm * c.n_tiles_n;
 #pragma unroll
         for (int d = 1; d < 64; d *= 2) {
           const int below = __shfl_up(v, d);
@@ -129,10 +132,17 @@ struct TileWalk {
         t.e = e;
         t.row_first = __builtin_amdgcn_readfirstlane(tab[e]);
         t.m_rows = __builtin_amdgcn_readfirstlane(tab[HMOE_MAX_EXPERTS + e]);
-        const int mts = (t.m_rows + BM - 1) / BM;
+        const int mts = (t.m_rows + bm - 1) / bm;
         const int within = tile_id - (__builtin_amdgcn_readfirstlane(tab[2 * HMOE_MAX_EXPERTS + e]) - mts * n_tiles_n);
         t.nt = within / mts;
         t.mt = within % mts;
+        // The expert's 32-row fragments are dealt to its m-tiles as evenly as whole fragments allow (heights differ
+        // by at most one fragment): at most 31 padded rows per expert.  A lone tile has at least MIN_FM fragments.
+        const int frags = (t.m_rows + 31) / 32;
+        const int base = frags / mts, rem = frags % mts;
+        t.fm = base + (t.mt < rem ? 1 : 0);
+        t.m0 = 32 * (t.mt * base + (t.mt < rem ? t.mt : rem));
+        if (t.fm < MIN_FM) t.fm = MIN_FM;  // (only when mts == 1)
         return true;
       }
     }
