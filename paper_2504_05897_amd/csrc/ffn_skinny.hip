@@ -353,6 +353,7 @@ int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense, const CombineArgs*
   if (d.dtype != HMOE_BF16) return HMOE_ERR_UNSUPPORTED;
   if (dense && (dense->desc->dtype != HMOE_BF16 || dense->desc->hidden != d.hidden)) return HMOE_ERR_UNSUPPORTED;
   if (dense && dense->n_rows == 0) dense = nullptr;
+  if (combine && a.n_rows == 0) return HMOE_ERR_INVALID_ARG;  // without routed rows nothing would draw the tickets
   if (a.n_rows == 0 && !dense) return HMOE_OK;
   SkinnyCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 1, a.row_map, a.map_div, {}, {}};
   int ffn_dense = 0;
@@ -369,7 +370,6 @@ int launch_ffn_skinny(const FfnArgs& a, const FfnArgs* dense, const CombineArgs*
   probe_after(a.stream);
   probe_before(a.stream);
   if (combine) {
-    if (a.n_rows == 0) return HMOE_ERR_INVALID_ARG;  // without routed rows nothing would draw the tickets
     c.combine = SkinnyCombine{combine->inv_perm, combine->topk_w, (const bf16_t*)a.o_perm, dense ? (const bf16_t*)dense->o_perm : nullptr,
                               (bf16_t*)combine->y, combine->tickets, combine->n_tokens, d.top_k, 1};
   }

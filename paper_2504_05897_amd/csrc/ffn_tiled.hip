@@ -601,7 +601,7 @@ __device__ __forceinline__ void run_tile(const TiledCtx& c, const bf16_t* __rest
                                          const TileLoc& loc, u32x4* lds) {
   typename TILE::Acc acc;
   zero_acc<TILE>(acc);
-  // A 256-row tile with two weight groups per wave keeps its accumulators in the second half of the register file
+  // A 224-row tile with two weight groups per wave keeps its accumulators in the second half of the register file
   // (one wave per SIMD, 512 registers).  A fitted instantiation needs fewer of them than the full tile, and the
   // register allocator would park weight-ring values in the free ones -- copying a register whose hand-issued load
   // has not landed.  Holding the unused accumulator registers over the tile leaves it nowhere to park.
@@ -675,9 +675,12 @@ static void launch_tiles_fit256(TiledCtx c, int n_rows, const bf16_t* in, bf16_t
   hipLaunchKernelGGL((ffn_tile_fit256_kernel<GATEUP, NWV, NT>), dim3((unsigned)c.grid_padded), dim3(64 * NWV), 0, s, c, in, out);
 }
 
-// Tiles of up to 256 rows with TWO weight groups per wave: 256x256 with four waves, one wave per SIMD, the 256
-// accumulator registers of a wave in the second half of its register file.  A CU then pulls (256 + 256) * 2 bytes
-// per k for 256 x 256 products, two thirds of what two resident 128x256 blocks pull.
+// Tiles of up to 224 rows with TWO weight groups per wave: 224x256 with four waves, one wave per SIMD, the 224
+// accumulator registers of a wave in the second half of its register file (256 rows would fill that half to the last
+// register, which the register allocator does not manage without spilling).  A CU then pulls (224 + 256) * 2 bytes
+// per k for 224 x 256 products, against (128 + 256) * 2 for 128 x 256 with two resident 128x256 blocks.  With one
+// wave per SIMD nothing hides what a wave issues between its matrix instructions: see ILV in StreamTile::steps.
+// Gate/up only (a tuning variant; the walking blocks below are what the library chooses).
 template <bool GATEUP, bool NT>
 __global__ __launch_bounds__(256) void ffn_tile_fit256w_kernel(TiledCtx c, const bf16_t* __restrict__ in,
                                                                 bf16_t* __restrict__ out) {
@@ -686,7 +689,7 @@ __global__ __launch_bounds__(256) void ffn_tile_fit256w_kernel(TiledCtx c, const
   TileLoc loc;
   if (!locate_tile<224>(c, loc)) return;  // uniform over the block
   const int tiles = (loc.m_rows + 223) / 224;
-  const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;  // per m-tile, 1..8; uniform
+  const int fragments = ((loc.m_rows + tiles - 1) / tiles + 31) / 32;  // per m-tile, 1..7; uniform
   if (fragments > 6) run_tile<FULL>(c, in, out, loc, lds);
   else if (fragments > 5) run_tile<StreamTile<GATEUP, 224, 4, 4, NT, 8, 6, 2, true>>(c, in, out, loc, lds);
   else if (fragments > 4) run_tile<StreamTile<GATEUP, 224, 4, 4, NT, 8, 5, 2, true>>(c, in, out, loc, lds);
@@ -704,7 +707,9 @@ static void launch_tiles_fit256w(TiledCtx c, int n_rows, const bf16_t* in, bf16_
 // The 224x256 tile in a block that works through several tiles (one block per CU, every eighth of the tile list dealt
 // to the blocks of one XCD in turn): before a tile's epilogue the block issues the first loads and copies of its next
 // tile, so their latency passes under the epilogue's arithmetic instead of in front of the next K loop.  The
-// activation ring has three stages and the epilogue a staging region of its own.
+// activation ring has three stages and the epilogue a staging region of its own; every vector-memory operation of
+// the kernel after the tile table is issued by hand.
+//
 // first loads and copies of a 224-row tile of fm fragments (fm copies per thread and stage, stages of fm * 256 chunks)
 template <bool NT>
 __device__ __forceinline__ void walk_issue_prologue(const u32x4* (&a_src)[7], const u32x4* (&b_src)[2], uint32_t lds0, int wave,
@@ -774,7 +779,10 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
   for (int i = 0; i < HELD; ++i) asm volatile("" ::"a"(held[i]));
 }
 
-template <bool GATEUP, bool NT>
+// DENSE: the launch is a single expert over all rows (a layer's shared experts).  The code is the same; the two are
+// separate kernels so that traces and counter runs tell the shared experts' launches from the routed ones, which
+// have the same grid.
+template <bool GATEUP, bool NT, bool DENSE>
 __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf16_t* __restrict__ in,
                                                              bf16_t* __restrict__ out) {
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true> FULL;
@@ -827,7 +835,10 @@ static void launch_tiles_walk(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* 
     if (want >= 8 && want < blocks) blocks = want;
   }
   c.grid_padded = (int)blocks;
-  hipLaunchKernelGGL((ffn_tile_walk_kernel<GATEUP, NT>), dim3((unsigned)c.grid_padded), dim3(256), 0, s, c, in, out);
+  if (!NT && c.n_experts == 1)  // (what the library itself chooses for shared experts: plain loads)
+    hipLaunchKernelGGL((ffn_tile_walk_kernel<GATEUP, false, true>), dim3((unsigned)c.grid_padded), dim3(256), 0, s, c, in, out);
+  else
+    hipLaunchKernelGGL((ffn_tile_walk_kernel<GATEUP, NT, false>), dim3((unsigned)c.grid_padded), dim3(256), 0, s, c, in, out);
 }
 
 // Tile shapes built into the library.  hmoe picks one from the average rows per expert; the
@@ -848,7 +859,7 @@ enum {
   V_FIT4_PLAIN = 3,
   V_FIT256 = 4,         // tiles of up to 256 rows, one weight group per wave: 256x256 (gate/up, 8 waves), 256x128 (down, 4 waves)
   V_FIT256_PLAIN = 5,
-  V_FIT256W = 6,        // 256x256, 4 waves, two weight groups per wave, one wave per SIMD
+  V_FIT256W = 6,        // gate/up: 224x256, 4 waves, two weight groups per wave, one wave per SIMD (down: as 0 / 1)
   V_FIT256W_PLAIN = 7,
   V_WALK = 8,           // the same tile in blocks that work through several tiles each
   V_WALK_PLAIN = 9
