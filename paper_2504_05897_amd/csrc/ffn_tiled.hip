@@ -148,22 +148,39 @@ struct StreamTile {
   // of this thread moves (rows past the expert's end clamped to its last row), b_src[j] the thread's piece of the
   // first weight tile of the wave's group j (groups past N clamped to group 0).  m0 is the tile's first row within
   // the expert.  NA may exceed A_OPS (a caller that serves tile types of several heights with one set of pointers).
+  // In two steps, so that a caller can put other work between the lookups and their use.
+  //
+  // Sorted rows of the thread's copies, and with a row map (the gather folded into gate/up) what the map holds for
+  // them: all lookups are issued before the first is used, one trip to memory per tile.
   template <int NA>
-  static __device__ __forceinline__ void set_sources(const TiledCtx& c, const bf16_t* __restrict__ in, const TileLoc& loc,
-                                                     int m0, int k_begin, int wave, int lane, const u32x4* (&a_src)[NA],
-                                                     const u32x4* (&b_src)[FN]) {
+  static __device__ __forceinline__ void fetch_rows(const TiledCtx& c, const TileLoc& loc, int m0, int wave, int lane,
+                                                    int (&rows)[NA]) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+      const int r = ((i * NWV + wave) * 64 + lane) / CPR;
+      rows[i] = loc.row_first + (m0 + r < loc.m_rows ? m0 + r : loc.m_rows - 1);
+    }
+    if (GATEUP && c.row_map) {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) rows[i] = c.row_map[rows[i]];
+    }
+  }
+  // ... and the pointers from them
+  template <int NA>
+  static __device__ __forceinline__ void set_sources_from(const TiledCtx& c, const bf16_t* __restrict__ in, const TileLoc& loc,
+                                                          const int (&rows)[NA], int k_begin, int wave, int lane,
+                                                          const u32x4* (&a_src)[NA], const u32x4* (&b_src)[FN]) {
     const int K = GATEUP ? c.hidden : c.ffn;
     const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;
     const int kt16 = K / TILE_K;
-    const char* slot = c.slots + (size_t)c.slot_of[loc.e] * c.slot_bytes;
+    const char* slot = c.slots + (size_t)loc.slot * c.slot_bytes;
     const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
       const int ci = (i * NWV + wave) * 64 + lane;
       const int r = ci / CPR, sl = ci % CPR;
       const int chunk = sl ^ ((r / RP) % CPR);
-      const int row = m0 + r < loc.m_rows ? m0 + r : loc.m_rows - 1;
-      const int in_row = GATEUP ? mapped_row(c.row_map, c.map_div, loc.row_first + row) : loc.row_first + row;
+      const int in_row = GATEUP && c.row_map ? rows[i] / c.map_div : rows[i];
       a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk + (size_t)k_begin * CPR;
     }
 #pragma unroll
@@ -171,6 +188,14 @@ struct StreamTile {
       const int g = loc.nt * (BN / TILE_N) + wave * FN + j;
       b_src[j] = w + ((size_t)(g < n_groups ? g : 0) * kt16 + (size_t)k_begin * KK) * 64 + lane;
     }
+  }
+  template <int NA>
+  static __device__ __forceinline__ void set_sources(const TiledCtx& c, const bf16_t* __restrict__ in, const TileLoc& loc,
+                                                     int m0, int k_begin, int wave, int lane, const u32x4* (&a_src)[NA],
+                                                     const u32x4* (&b_src)[FN]) {
+    int rows[NA];
+    fetch_rows(c, loc, m0, wave, lane, rows);
+    set_sources_from(c, in, loc, rows, k_begin, wave, lane, a_src, b_src);
   }
   // copy `op` of this thread for K step `kstep` (clamped to the last step) into ring stage `stage`
   template <int NA>
@@ -744,13 +769,26 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
                                               const u32x4* (&a_src)[7], const u32x4* (&b_src)[2], u32x4 (&ring)[8][2]) {
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, FM, 2, true> TILE;
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true> FULL;
+  // The next tile is looked up before this tile's K loop, and the row-map entries of its copies are requested here,
+  // where nothing issued by hand is in flight: they arrive during the K loop, and between the K loop and the next
+  // tile's first loads only arithmetic is left.  A block at its last tile looks that tile up once more.
+  const TileLoc done = loc;
+  idx += stride;
+  more = walk.at(xcd, idx, loc);  // leaves loc as it is when there is no further tile
+  fm = loc.fm;
+  int rows_next[7];
+  {
+    int lane_rows = lane;  // (opaque copies of the lane id: what is derived from it is recomputed where it is used)
+    asm volatile("" : "+v"(lane_rows));
+    FULL::fetch_rows(c, loc, loc.m0, wave, lane_rows, rows_next);
+  }
   typename TILE::Acc acc;
   zero_acc<TILE>(acc);
   constexpr int HELD = 14 - 2 * FM;  // see run_tile
   f32x16_t held[HELD > 0 ? HELD : 1];
 #pragma unroll
   for (int i = 0; i < HELD; ++i) asm volatile("" : "=a"(held[i]));
-  int lane_steps = lane;  // (opaque, like the two below: the fragment addresses of the four tile heights are not all kept)
+  int lane_steps = lane;
   asm volatile("" : "+v"(lane_steps));
   TILE::steps(a_src, b_src, lds, wave, lane_steps, k_steps, ring, acc);
   block_barrier();  // every wave is through with the activation stages
@@ -758,16 +796,14 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
   // epilogue: registers with a load in flight never cross a branch (the compiler may copy a value where control flow
   // merges, and a copy of such a register reads what has not arrived).  A block at its last tile issues that tile's
   // first loads once more, unused.
-  const TileLoc done = loc;
-  idx += stride;
-  more = walk.at(xcd, idx, loc);  // leaves loc as it is when there is no further tile
-  fm = loc.fm;
   {
-    // (an opaque copy of the lane id: what is derived from it here is recomputed per tile instead of being kept in
-    // registers over the K loop, where registers are short)
+    // the looked-up rows are used from here on only (not divided and turned into pointers ahead of the K loop, which
+    // would hold twice the registers over it)
+#pragma unroll
+    for (int i = 0; i < 7; ++i) asm volatile("" : "+v"(rows_next[i]));
     int lane_here = lane;
     asm volatile("" : "+v"(lane_here));
-    FULL::set_sources(c, in, loc, loc.m0, 0, wave, lane_here, a_src, b_src);
+    FULL::set_sources_from(c, in, loc, rows_next, 0, wave, lane_here, a_src, b_src);
     walk_issue_prologue<NT>(a_src, b_src, lds0, wave, k_steps, fm, ring);
   }
   int lane_there = lane;

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(64 * W4T_WAVES) void ffn_tile_w4_kernel(TiledCtx c,
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
   const int j = lane % 16, kblk = lane / 16;
 
-  const char* slot = c.slots + (size_t)c.slot_of[loc.e] * c.slot_bytes;
+  const char* slot = c.slots + (size_t)loc.slot * c.slot_bytes;
   const W4Offsets off = w4_offsets((size_t)c.hidden, (size_t)c.ffn);
   const u32x4* units = (const u32x4*)(slot + (GATEUP ? 0 : off.down_units));
   const bf16_t* scales = (const bf16_t*)(slot + (GATEUP ? off.gate_up_scales : off.down_scales));

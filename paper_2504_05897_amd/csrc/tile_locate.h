@@ -28,21 +28,24 @@ struct TiledCtx {
 // experts, and every wave of the block computes the same answer.  Returns false for surplus blocks.
 struct TileLoc {
   int e, row_first, m_rows, mt, nt;
+  int slot;  // cache slot that holds expert e
   int m0, fm;  // TileWalk only: first row of the tile within the expert, and its height in 32-row fragments
 };
 template <int BM>
 __device__ __forceinline__ bool locate_tile(const TiledCtx& c, TileLoc& t) {
   constexpr int CH = HMOE_MAX_EXPERTS / 64;
   const int lane = threadIdx.x % 64;
-  int first[CH], rows[CH], incl[CH];
+  int first[CH], rows[CH], incl[CH], slot[CH];
   int total = 0;
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
     first[j] = rows[j] = 0;
+    slot[j] = -1;
     incl[j] = total;
     if (j * 64 < c.n_experts) {  // uniform
       const int i = j * 64 + lane;
-      if (i < c.n_experts && ((c.active.w[j] >> lane) & 1ull) && c.slot_of[i] >= 0) {
+      if (i < c.n_experts) slot[j] = c.slot_of[i];
+      if (i < c.n_experts && ((c.active.w[j] >> lane) & 1ull) && slot[j] >= 0) {
         first[j] = c.offsets[i];
         rows[j] = c.offsets[i + 1] - first[j];
       }
@@ -69,6 +72,7 @@ __device__ __forceinline__ bool locate_tile(const TiledCtx& c, TileLoc& t) {
       t.e = j * 64 + src;
       t.row_first = __builtin_amdgcn_readfirstlane(__shfl(first[j], src));
       t.m_rows = __builtin_amdgcn_readfirstlane(__shfl(rows[j], src));
+      t.slot = __builtin_amdgcn_readfirstlane(__shfl(slot[j], src));
       const int mts = (t.m_rows + BM - 1) / BM;
       const int within = __builtin_amdgcn_readfirstlane(tile_id - (__shfl(incl[j], src) - mts * c.n_tiles_n));
       t.nt = within / mts;
@@ -80,12 +84,12 @@ __device__ __forceinline__ bool locate_tile(const TiledCtx& c, TileLoc& t) {
 }
 
 // The same tile list for a block that works through several tiles: the per-expert prefix sums are computed once into
-// a table in LDS (3 * HMOE_MAX_EXPERTS ints: first row, rows, inclusive tile count), and entry idx of the xcd-th eighth
+// a table in LDS (4 * HMOE_MAX_EXPERTS ints: first row, rows, inclusive tile count, slot), and entry idx of the xcd-th eighth
 // of the list is looked up on demand.  Every wave of the block computes and writes the same table.
 template <int MIN_FM>
 struct TileWalk {
   static constexpr int CH = HMOE_MAX_EXPERTS / 64;
-  static constexpr int TABLE_INTS = 3 * HMOE_MAX_EXPERTS;
+  static constexpr int TABLE_INTS = 4 * HMOE_MAX_EXPERTS;
   int total, per_xcd, n_tiles_n, bm;
   int* tab;
   __device__ __forceinline__ void init(const TiledCtx& c, int* table) {
@@ -96,10 +100,11 @@ struct TileWalk {
     int sum = 0;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-      int first = 0, rows = 0, incl = sum;
+      int first = 0, rows = 0, incl = sum, slot = -1;
       if (j * 64 < c.n_experts) {  // uniform
         const int i = j * 64 + lane;
-        if (i < c.n_experts && ((c.active.w[j] >> lane) & 1ull) && c.slot_of[i] >= 0) {
+        if (i < c.n_experts) slot = c.slot_of[i];
+        if (i < c.n_experts && ((c.active.w[j] >> lane) & 1ull) && slot >= 0) {
           first = c.offsets[i];
           rows = c.offsets[i + 1] - first;
         }
@@ -115,6 +120,7 @@ struct TileWalk {
       tab[j * 64 + lane] = first;
       tab[HMOE_MAX_EXPERTS + j * 64 + lane] = rows;
       tab[2 * HMOE_MAX_EXPERTS + j * 64 + lane] = incl;
+      tab[3 * HMOE_MAX_EXPERTS + j * 64 + lane] = slot;
     }
     total = __builtin_amdgcn_readfirstlane(sum);
     per_xcd = (total + 7) / 8;
@@ -132,6 +138,7 @@ struct TileWalk {
         t.e = e;
         t.row_first = __builtin_amdgcn_readfirstlane(tab[e]);
         t.m_rows = __builtin_amdgcn_readfirstlane(tab[HMOE_MAX_EXPERTS + e]);
+        t.slot = __builtin_amdgcn_readfirstlane(tab[3 * HMOE_MAX_EXPERTS + e]);
         const int mts = (t.m_rows + bm - 1) / bm;
         const int within = tile_id - (__builtin_amdgcn_readfirstlane(tab[2 * HMOE_MAX_EXPERTS + e]) - mts * n_tiles_n);
         t.nt = within / mts;
