@@ -39,6 +39,14 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return (bf16_t)(u >> 16);
 }
 
+// two at once: the low half of the result is a, the high half b (same rounding; one instruction on gfx950)
+typedef __bf16 bf16x2_hw_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32_to_bf16_pair(float a, float b) {
+  const f32x2_hw_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw_t));
+}
+
 // source row of sorted row p (gather fused into the FFN's first GEMM when a row map is given)
 __device__ __forceinline__ int mapped_row(const int32_t* __restrict__ row_map, int map_div, int p) {
   return row_map ? row_map[p] / map_div : p;

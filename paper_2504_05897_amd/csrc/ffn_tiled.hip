@@ -116,14 +116,17 @@ __device__ __forceinline__ void wait_vmcnt_regs(u32x4& a) {
 // twice in two blocks that must keep pace to share them through L2); the gate and the up half of a SwiGLU pair then
 // sit in neighbouring waves and meet through LDS in the epilogue.  Tiles higher than 128 rows copy only the rows
 // they multiply (rounded up to what one copy instruction per thread moves).
-template <bool GATEUP_, int BM_, int NWV, int SA, bool NT, int DB = 8, int FMC = 0, int FN_ = 2, bool ILV = false>
+// TR (with ILV): the weight tile is the first operand of the matrix instruction, so the accumulators hold the transposed
+// block: a lane owns one row per fragment and, per weight group, four runs of four consecutive columns, which the
+// epilogues turn into 8-byte pieces of an output row (a quarter of the conversions and LDS writes of the other form).
+template <bool GATEUP_, int BM_, int NWV, int SA, bool NT, int DB = 8, int FMC = 0, int FN_ = 2, bool ILV = false, bool TR = false>
 struct StreamTile {
   static constexpr bool GATEUP = GATEUP_;
   static constexpr int BM = BM_;
   static constexpr int FN = FN_, BN = NWV * 32 * FN, BKT = 64, KK = 4;
   static constexpr int FM = FMC > 0 ? FMC : BM / 32;   // fragments multiplied
   static constexpr int MSTRIDE = 32 * FM;              // rows between the starts of consecutive m-tiles
-  static_assert(FM * 32 <= BM && (FN == 1 || FN == 2), "");
+  static_assert(FM * 32 <= BM && (FN == 1 || FN == 2) && (!TR || (ILV && FN == 2)), "");
   static_assert(DB % KK == 0, "the weight ring holds whole K steps");
   static constexpr int CPR = BKT / 8, RP = 256 / (BKT * 2);
   static constexpr int ROWS_PER_OP = 64 * NWV / CPR;   // rows one copy instruction of every thread moves
@@ -306,7 +309,8 @@ struct StreamTile {
 #pragma unroll
               for (int m = 0; m < 2 * FM; ++m) {
                 const int i = m % FM, j = m / FM;
-                acc[i][j] = mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
+                acc[i][j] = TR ? mfma_32x32x16_bf16(ring[sl][j], fa[kk & 1][i], acc[i][j])
+                               : mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
                 if (m < FM) fa[(kk + 1) & 1][m] = kk == KK - 1 ? read_frag(next_stage, 0, m) : read_frag(stage, kk + 1, m);
                 if (m == FM) ring[sl][0] = load_stream_16<NT>(b_src[0] + w_next);
 #pragma unroll
@@ -457,45 +461,6 @@ struct StreamTile {
       if (m < m_rows && f < n_out) *(u32x4*)(out + (size_t)(row_first + m) * n_out + f) = v;
     }
   }
-  // The same for a block that goes on to another tile: the staging blocks lie in a region of their own (`staging`, the
-  // activation ring is already being filled for the next tile) and the stores are issued by hand.  The previous tile's
-  // reads of the staging blocks are separated from these writes by that tile's whole K loop.
-  static __device__ __forceinline__ void epilogue_lines_walk(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
-                                                             Acc& acc, u32x4* staging, int wave, int lane) {
-    // The accumulators stay where they are until here: without this the compiler starts to copy them out of the
-    // second register file before the next tile's loads are issued, into registers it frees by moving others.
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-      for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
-    const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
-    const int n_out = c.ffn;
-    const int m0 = loc.m0;
-    const int half = lane / 32, col = lane % 32;
-    bf16_t* block = (bf16_t*)(staging + (wave / 2) * FM * 32 * 8);  // [FM * 32 rows][64 columns]
-    // (scheduling fences: left alone the scheduler spreads the whole tile's arithmetic over every register it can
-    // find, and the registers of the next tile's loads in flight would be moved out of its way)
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = i * 32 + (r / 4) * 8 + half * 4 + (r % 4);
-        block[row * 64 + (wave % 2) * 32 + col] = f32_to_bf16(silu_f32(acc[i][0][r]) * acc[i][1][r]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-    block_barrier();
-    const int f = nt * (BN / 2) + (wave / 2) * 64 + (lane % 8) * 8;
-#pragma unroll
-    for (int k = 0; k < 2 * FM; ++k) {
-      const int row = (wave % 2) * FM * 16 + k * 8 + lane / 8;
-      const u32x4 v = *(const u32x4*)(block + row * 64 + (lane % 8) * 8);
-      const int m = m0 + row;
-      if (m < m_rows && f < n_out) store_16(out + (size_t)(row_first + m) * n_out + f, v);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  }
   // Down projection with two weight groups per wave: the wave's 64 columns are one 128-byte line per row.  The wave
   // turns its accumulators into rows in a block of its own in the idle activation ring, two fragments (64 rows) at a
   // time, and stores whole lines, 16 bytes per lane.  (LDS serves a wave's accesses in order: no barrier in between.)
@@ -536,11 +501,58 @@ struct StreamTile {
       __builtin_amdgcn_s_waitcnt(0xC07F);  // the rows are in registers before the next pass overwrites the block
     }
   }
-  // The same for a block that goes on to another tile (see epilogue_lines_walk): staging blocks in a region of their
-  // own, stores issued by hand.
-  static __device__ __forceinline__ void epilogue_lines_down_walk(const TiledCtx& c, bf16_t* __restrict__ out,
-                                                                  const TileLoc& loc, Acc& acc, u32x4* staging, int wave,
-                                                                  int lane) {
+  // The two epilogues of a block that goes on to another tile (transposed product, TR).  The staging blocks lie in a
+  // region of their own (`staging`: the activation ring is already being filled for the next tile) and the stores are
+  // issued by hand; the previous tile's reads of the staging blocks are separated from these writes by that tile's
+  // whole K loop.  The accumulators are pinned where they are on entry: without that the compiler starts to copy them
+  // out of the second register file before the next tile's loads are issued, into registers it frees by moving
+  // others; the scheduling fences keep the tile's arithmetic from spreading over the registers of loads in flight.
+  // Staging blocks are rows of 128 bytes in eight 16-byte slots; row r keeps slot s at s ^ ((r / 2) % 8), so that the 8-byte writes of a wave (32 rows, two
+  // neighbouring half slots each) and the 16-byte reads (8 rows x 8 slots) both spread over all banks.
+  static __device__ __forceinline__ uint32_t staged_at(int row, int slot) {
+    return (uint32_t)(row * 128 + ((slot ^ ((row >> 1) & 7)) << 4));
+  }
+  static __device__ __forceinline__ void epilogue_lines_walk_tr(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
+                                                                Acc& acc, u32x4* staging, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
+    const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
+    const int n_out = c.ffn;
+    const int m0 = loc.m0;
+    const int half = lane / 32, rl = lane % 32;
+    char* block = (char*)(staging + (wave / 2) * FM * 32 * 8);  // [FM * 32 rows][64 columns] of waves 2p, 2p+1
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int row = i * 32 + rl;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float v[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = silu_f32(acc[i][0][q * 4 + t]) * acc[i][1][q * 4 + t];
+        uint2 pk;
+        pk.x = f32_to_bf16_pair(v[0], v[1]);
+        pk.y = f32_to_bf16_pair(v[2], v[3]);
+        *(uint2*)(block + staged_at(row, (wave % 2) * 4 + q) + half * 8) = pk;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    block_barrier();
+    const int f = nt * (BN / 2) + (wave / 2) * 64 + (lane % 8) * 8;
+#pragma unroll
+    for (int k = 0; k < 2 * FM; ++k) {
+      const int row = (wave % 2) * FM * 16 + k * 8 + lane / 8;
+      const u32x4 v = *(const u32x4*)(block + staged_at(row, lane % 8));
+      const int m = m0 + row;
+      if (m < m_rows && f < n_out) store_16(out + (size_t)(row_first + m) * n_out + f, v);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  static __device__ __forceinline__ void epilogue_lines_down_walk_tr(const TiledCtx& c, bf16_t* __restrict__ out,
+                                                                     const TileLoc& loc, Acc& acc, u32x4* staging, int wave,
+                                                                     int lane) {
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -548,8 +560,8 @@ struct StreamTile {
     const int row_first = loc.row_first, m_rows = loc.m_rows, nt = loc.nt;
     const int n_out = c.hidden;
     const int m0 = loc.m0;
-    const int half = lane / 32, col = lane % 32;
-    bf16_t* block = (bf16_t*)(staging + wave * 64 * 8);  // [64 rows][64 columns]
+    const int half = lane / 32, rl = lane % 32;
+    char* block = (char*)(staging + wave * 64 * 8);  // [64 rows][64 columns], the wave's own
     const int n = nt * BN + wave * 64 + (lane % 8) * 8;
 #pragma unroll
     for (int pass = 0; pass < (FM + 1) / 2; ++pass) {
@@ -557,11 +569,16 @@ struct StreamTile {
       for (int ii = 0; ii < 2; ++ii) {
         const int i = pass * 2 + ii;
         if (i < FM) {
+          const int row = ii * 32 + rl;
 #pragma unroll
           for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-              block[(ii * 32 + (r / 4) * 8 + half * 4 + (r % 4)) * 64 + j * 32 + col] = f32_to_bf16(acc[i][j][r]);
+            for (int q = 0; q < 4; ++q) {
+              uint2 pk;
+              pk.x = f32_to_bf16_pair(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1]);
+              pk.y = f32_to_bf16_pair(acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+              *(uint2*)(block + staged_at(row, j * 4 + q) + half * 8) = pk;
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -570,7 +587,7 @@ struct StreamTile {
       for (int k = 0; k < 8; ++k) {
         const int row = k * 8 + lane / 8;
         if (pass * 2 + row / 32 < FM) {  // uniform per k: the second fragment of the last pass may not exist
-          const u32x4 v = *(const u32x4*)(block + row * 64 + (lane % 8) * 8);
+          const u32x4 v = *(const u32x4*)(block + staged_at(row, lane % 8));
           const int m = m0 + pass * 64 + row;
           if (m < m_rows && n < n_out) store_16(out + (size_t)(row_first + m) * n_out + n, v);
         }
@@ -762,13 +779,23 @@ __device__ __forceinline__ void walk_wait_ring(u32x4 (&r)[8][2]) {
                : "memory");
 }
 
+#ifdef HMOE_WALK_TIMING
+__device__ unsigned long long hmoe_walk_times[2][256][8];
+#define WT_STAMP(i) { const unsigned long long now_ = __builtin_readcyclecounter(); tacc[i] += now_ - tprev; tprev = now_; }
+#else
+#define WT_STAMP(i)
+#endif
 template <bool GATEUP, bool NT, int FM>
 __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
                                               const TileWalk<4>& walk, int xcd, int stride, int wave, int lane, int k_steps,
                                               u32x4* lds, uint32_t lds0, TileLoc& loc, int& idx, int& fm, bool& more,
-                                              const u32x4* (&a_src)[7], const u32x4* (&b_src)[2], u32x4 (&ring)[8][2]) {
-  typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, FM, 2, true> TILE;
-  typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true> FULL;
+                                              const u32x4* (&a_src)[7], const u32x4* (&b_src)[2], u32x4 (&ring)[8][2]
+#ifdef HMOE_WALK_TIMING
+                                              , unsigned long long (&tacc)[8], unsigned long long& tprev
+#endif
+                                              ) {
+  typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, FM, 2, true, true> TILE;
+  typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true, true> FULL;
   // The next tile is looked up before this tile's K loop, and the row-map entries of its copies are requested here,
   // where nothing issued by hand is in flight: they arrive during the K loop, and between the K loop and the next
   // tile's first loads only arithmetic is left.  A block at its last tile looks that tile up once more.
@@ -782,6 +809,7 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
     asm volatile("" : "+v"(lane_rows));
     FULL::fetch_rows(c, loc, loc.m0, wave, lane_rows, rows_next);
   }
+  WT_STAMP(0)
   typename TILE::Acc acc;
   zero_acc<TILE>(acc);
   constexpr int HELD = 14 - 2 * FM;  // see run_tile
@@ -791,7 +819,9 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
   int lane_steps = lane;
   asm volatile("" : "+v"(lane_steps));
   TILE::steps(a_src, b_src, lds, wave, lane_steps, k_steps, ring, acc);
+  WT_STAMP(1)
   block_barrier();  // every wave is through with the activation stages
+  WT_STAMP(2)
   // The next tile's first loads and copies are issued here, without a condition, and waited for below, behind the
   // epilogue: registers with a load in flight never cross a branch (the compiler may copy a value where control flow
   // merges, and a copy of such a register reads what has not arrived).  A block at its last tile issues that tile's
@@ -806,13 +836,18 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
     FULL::set_sources_from(c, in, loc, rows_next, 0, wave, lane_here, a_src, b_src);
     walk_issue_prologue<NT>(a_src, b_src, lds0, wave, k_steps, fm, ring);
   }
+  WT_STAMP(3)
   int lane_there = lane;
   asm volatile("" : "+v"(lane_there));
-  if constexpr (GATEUP) TILE::epilogue_lines_walk(c, out, done, acc, lds + FULL::LDS_VEC, wave, lane_there);
-  else TILE::epilogue_lines_down_walk(c, out, done, acc, lds + FULL::LDS_VEC, wave, lane_there);
+  if constexpr (GATEUP) TILE::epilogue_lines_walk_tr(c, out, done, acc, lds + FULL::LDS_VEC, wave, lane_there);
+  else TILE::epilogue_lines_down_walk_tr(c, out, done, acc, lds + FULL::LDS_VEC, wave, lane_there);
   walk_wait_ring(ring);
+  WT_STAMP(4)
 #pragma unroll
   for (int i = 0; i < HELD; ++i) asm volatile("" ::"a"(held[i]));
+#ifdef HMOE_WALK_TIMING
+  tacc[6] += 1;
+#endif
 }
 
 // DENSE: the launch is a single expert over all rows (a layer's shared experts).  The code is the same; the two are
@@ -821,7 +856,7 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
 template <bool GATEUP, bool NT, bool DENSE>
 __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf16_t* __restrict__ in,
                                                              bf16_t* __restrict__ out) {
-  typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true> FULL;
+  typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true, true> FULL;
   constexpr int STAGING = 2 * 7 * 32 * 8;  // two [224][64] bf16 blocks, in 16-byte units
   __shared__ u32x4 lds[FULL::LDS_VEC + STAGING];
   __shared__ int walk_table[TileWalk<4>::TABLE_INTS];
@@ -843,13 +878,34 @@ __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf
   walk_issue_prologue<NT>(a_src, b_src, lds0, wave, k_steps, fm, ring);
   walk_wait_ring(ring);
   bool more = true;
+#ifdef HMOE_WALK_TIMING
+  unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  unsigned long long tprev = __builtin_readcyclecounter();
+  const unsigned long long tstart = tprev;
+#define WT_ARGS , tacc, tprev
+#else
+#define WT_ARGS
+#endif
   while (more) {
-    if (fm == 7) walk_one_tile<GATEUP, NT, 7>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring);
-    else if (fm == 6) walk_one_tile<GATEUP, NT, 6>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring);
-    else if (fm == 5) walk_one_tile<GATEUP, NT, 5>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring);
-    else walk_one_tile<GATEUP, NT, 4>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring);
+    if (fm == 7) walk_one_tile<GATEUP, NT, 7>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring WT_ARGS);
+    else if (fm == 6) walk_one_tile<GATEUP, NT, 6>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring WT_ARGS);
+    else if (fm == 5) walk_one_tile<GATEUP, NT, 5>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring WT_ARGS);
+    else walk_one_tile<GATEUP, NT, 4>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring WT_ARGS);
   }
+#ifdef HMOE_WALK_TIMING
+  if (!DENSE && tid == 0) {
+    tacc[7] = tprev - tstart;
+    for (int i = 0; i < 8; ++i) hmoe_walk_times[GATEUP ? 0 : 1][blockIdx.x][i] = tacc[i];
+  }
+#endif
 }
+#ifdef HMOE_WALK_TIMING
+}  // namespace hmoe
+extern "C" int hmoe_debug_walk_times(unsigned long long* out) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(hmoe::hmoe_walk_times), sizeof(hmoe::hmoe_walk_times));
+}
+namespace hmoe {
+#endif
 
 template <bool GATEUP, bool NT>
 static void launch_tiles_walk(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
