@@ -96,6 +96,16 @@ __device__ __forceinline__ u32x4 load_stream_16(const void* gptr) {
     asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(gptr) : "memory");
   return v;
 }
+// the same from a wave-uniform address (held in scalar registers) plus a byte offset per lane
+template <bool NT>
+__device__ __forceinline__ u32x4 load_stream_16(const void* uniform, uint32_t lane_bytes) {
+  u32x4 v;
+  if (NT)
+    asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(v) : "v"(lane_bytes), "s"(uniform) : "memory");
+  else
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(lane_bytes), "s"(uniform) : "memory");
+  return v;
+}
 // wait until at most N younger vector-memory operations are outstanding; the operands tie the wait
 // to the registers whose loads it covers, so their uses cannot be scheduled above it
 template <int N>
@@ -144,7 +154,10 @@ struct StreamTile {
   // The count uses the largest piece of copies, so it is exact or one operation stricter.
   static constexpr int N_B_ILV = N_B - (A_OPS + KK - 1) / KK;
   static constexpr int THREADS = 64 * NWV;
-  static constexpr int LDS_VEC = SA * A_CHUNKS;  // 16-byte units
+  // 16-byte units between ring stages: the tile's own rows, or with TR (blocks that go from tile to tile, whose next
+  // tile is already being copied in while this one is multiplied) the rows of the highest tile, whatever FM is
+  static constexpr int STAGE_CHUNKS = TR ? BM * CPR : A_CHUNKS;
+  static constexpr int LDS_VEC = SA * STAGE_CHUNKS;  // 16-byte units
   typedef f32x16_t Acc[FM][FN];
 
   // Where a thread's copies and weight loads start: a_src[i] is the 16-byte chunk of the activation tile that copy i
@@ -168,7 +181,15 @@ struct StreamTile {
       for (int i = 0; i < NA; ++i) rows[i] = c.row_map[rows[i]];
     }
   }
-  // ... and the pointers from them
+  // ... the input rows from what the map holds
+  template <int NA>
+  static __device__ __forceinline__ void input_rows(const TiledCtx& c, int (&rows)[NA]) {
+    if (GATEUP && c.row_map) {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) rows[i] = div_by_map(c, rows[i]);
+    }
+  }
+  // ... and the pointers from the input rows
   template <int NA>
   static __device__ __forceinline__ void set_sources_from(const TiledCtx& c, const bf16_t* __restrict__ in, const TileLoc& loc,
                                                           const int (&rows)[NA], int k_begin, int wave, int lane,
@@ -183,8 +204,7 @@ struct StreamTile {
       const int ci = (i * NWV + wave) * 64 + lane;
       const int r = ci / CPR, sl = ci % CPR;
       const int chunk = sl ^ ((r / RP) % CPR);
-      const int in_row = GATEUP && c.row_map ? rows[i] / c.map_div : rows[i];
-      a_src[i] = (const u32x4*)(in + (size_t)in_row * K) + chunk + (size_t)k_begin * CPR;
+      a_src[i] = (const u32x4*)(in + (size_t)rows[i] * K) + chunk + (size_t)k_begin * CPR;
     }
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
@@ -198,15 +218,19 @@ struct StreamTile {
                                                      const u32x4* (&b_src)[FN]) {
     int rows[NA];
     fetch_rows(c, loc, m0, wave, lane, rows);
+    input_rows(c, rows);
     set_sources_from(c, in, loc, rows, k_begin, wave, lane, a_src, b_src);
   }
   // copy `op` of this thread for K step `kstep` (clamped to the last step) into ring stage `stage`
   template <int NA>
   static __device__ __forceinline__ void issue_a_op(const u32x4* (&a_src)[NA], uint32_t lds0, int wave, int k_steps,
                                                     int stage, int kstep, int op) {
-    const uint32_t base = lds0 + (uint32_t)stage * A_CHUNKS * 16;
-    const size_t koff = (size_t)(kstep < k_steps ? kstep : k_steps - 1) * CPR;
-    load_to_lds_16(a_src[op] + koff, base + (uint32_t)((op * NWV + wave) * 64) * 16);
+    copy_to_stage(a_src[op] + (size_t)(kstep < k_steps ? kstep : k_steps - 1) * CPR, lds0, wave, stage, op);
+  }
+  // copy `op` of this thread, from `from`, into ring stage `stage`
+  static __device__ __forceinline__ void copy_to_stage(const u32x4* from, uint32_t lds0, int wave, int stage, int op) {
+    const uint32_t base = lds0 + (uint32_t)stage * STAGE_CHUNKS * 16;
+    load_to_lds_16(from, base + (uint32_t)((op * NWV + wave) * 64) * 16);
   }
   // piece `piece` (of KK) of the copies of one stage
   template <int NA>
@@ -247,6 +271,70 @@ struct StreamTile {
     steps(a_src, b_src, lds, wave, lane, k_steps, ring, acc);
   }
 
+  // fragment i (rows 32 i ..) of k-substep kk of a ring stage, for the lane that owns (half, col) of the operand
+  static __device__ __forceinline__ u32x4 read_fragment(const u32x4* lds, int stage, int kk, int i, int half, int col) {
+    const int r = i * 32 + col;
+    return lds[stage * STAGE_CHUNKS + r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
+  }
+  // One k-substep of a wave that has its SIMD to itself (ILV): nothing else fills the matrix pipe while this wave issues
+  // anything else, so all other work of the substep sits between its matrix instructions, one piece behind each: the
+  // next substep's fragment reads behind the first FM, which multiply weight group 0; then the reload of group 0's
+  // ring slot, this substep's activation copies, and behind the last one the reload of group 1.  Vector-memory order
+  // per substep: [group 0] [copies] [group 1].  kk: substep within the K step; sl: its ring slot; w_next: where the
+  // reloads read (16-byte units from b_src); koff: where the copies read (from a_src), into fill_stage.
+  // Where the operands of a tile come from.  As pointers per thread: a[op] is the thread's 16 bytes of copy op at the
+  // tile's first K step, b[j] its piece of the first weight tile of group j.
+  template <int NA>
+  struct PtrSrc {
+    const u32x4* (&a)[NA];
+    const u32x4* (&b)[FN];
+    __device__ __forceinline__ const u32x4* a_at(int op, size_t koff) const { return a[op] + koff; }
+    __device__ __forceinline__ u32x4 b_at(int j, size_t w) const { return load_stream_16<NT>(b[j] + w); }
+  };
+  // Or, for a block that goes from tile to tile and holds two tiles' sources over a K loop, in half the registers:
+  // the input ROW of each copy (the thread's place within a row, a_lane, is the same for every copy and tile), and
+  // wave-uniform weight addresses in scalar registers with the lane's offset added by the load.
+  struct RowSrc {
+    const u32x4* a_lane;  // input + the thread's chunk within a row
+    uint32_t pitch;       // 16-byte units per input row
+    const int (&rows)[7];
+    const u32x4* b[2];    // wave-uniform
+    uint32_t lane_bytes;
+    __device__ __forceinline__ const u32x4* a_at(int op, size_t koff) const {
+      return a_lane + ((size_t)(uint32_t)rows[op] * pitch + koff);
+    }
+    __device__ __forceinline__ u32x4 b_at(int j, size_t w) const { return load_stream_16<NT>(b[j] + w, lane_bytes); }
+  };
+  template <class SRC, int NF>
+  static __device__ __forceinline__ void ilv_substep(int kk, int sl, int stage, int next_stage, int fill_stage, size_t w_next,
+                                                     size_t koff, const SRC& src, const u32x4* lds, uint32_t lds0, int wave,
+                                                     int half, int col, u32x4 (&ring)[DB][FN], u32x4 (&fa)[NF][FM],
+                                                     Acc& acc) {
+    static_assert(FN == 2 && NF == 2, "");
+    wait_vmcnt_regs<N_B_ILV>(ring[sl][0], ring[sl][1]);
+#pragma unroll
+    for (int m = 0; m < 2 * FM; ++m) {
+      const int i = m % FM, j = m / FM;
+      acc[i][j] = TR ? mfma_32x32x16_bf16(ring[sl][j], fa[kk & 1][i], acc[i][j])
+                     : mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
+      if (m < FM)
+        fa[(kk + 1) & 1][m] = kk == KK - 1 ? read_fragment(lds, next_stage, 0, m, half, col)
+                                           : read_fragment(lds, stage, kk + 1, m, half, col);
+      if (m == FM) ring[sl][0] = src.b_at(0, w_next);
+#pragma unroll
+      for (int op = 0; op < A_OPS; ++op)
+        if (op >= A_OPS * kk / KK && op < A_OPS * (kk + 1) / KK) {
+          const int at = FM + 1 + (op - A_OPS * kk / KK);
+          if (m == (at < 2 * FM - 1 ? at : 2 * FM - 1)) copy_to_stage(src.a_at(op, koff), lds0, wave, fill_stage, op);
+        }
+      if (m == 2 * FM - 1) {
+        if (kk == KK - 1) mark_stage_issued();
+        ring[sl][1] = src.b_at(1, w_next);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
   // The K loop of a tile whose prologue has been issued (by this thread, into `ring` and the first SA-1 stages).
   // On return every vector-memory operation of the thread has completed.
   template <int NA>
@@ -259,12 +347,9 @@ struct StreamTile {
     // is multiplied); one set with one group, where a fragment feeds a single MFMA and is refilled right behind it.
     constexpr int FA_SETS = FN == 1 ? 1 : 2;
     u32x4 fa[FA_SETS][FM];
-    auto read_frag = [&](int stage, int kk, int i) {
-      const int r = i * 32 + col;
-      return lds[stage * A_CHUNKS + r * CPR + ((kk * 2 + half) ^ ((r / RP) % CPR))];
-    };
+    auto read_frag = [&](int stage, int kk, int i) { return read_fragment(lds, stage, kk, i, half, col); };
     auto read_a = [&](int buf, int stage, int kk) {
-      const u32x4* sa = lds + stage * A_CHUNKS;
+      const u32x4* sa = lds + stage * STAGE_CHUNKS;
 #pragma unroll
       for (int i = 0; i < FM; ++i) {
         const int r = i * 32 + col;
@@ -298,34 +383,11 @@ struct StreamTile {
             __builtin_amdgcn_sched_barrier(0);
             const int sl = h * KK + kk;  // ring slot of substep 4*tt + kk
             if constexpr (FN == 2 && ILV) {
-              // One wave per SIMD: nothing else fills the matrix pipe while this wave issues anything else, so all
-              // other work of the substep sits between its matrix instructions, one piece behind each: the next
-              // substep's fragment reads behind the first FM, which multiply weight group 0; then the reload of
-              // group 0's ring slot, this substep's activation copies, and behind the last one the reload of
-              // group 1.  Vector-memory order per substep: [group 0] [copies] [group 1].
-              wait_vmcnt_regs<N_B_ILV>(ring[sl][0], ring[sl][1]);
               const int s_next = tt * KK + kk + DB;
-              const size_t w_next = (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64;
-#pragma unroll
-              for (int m = 0; m < 2 * FM; ++m) {
-                const int i = m % FM, j = m / FM;
-                acc[i][j] = TR ? mfma_32x32x16_bf16(ring[sl][j], fa[kk & 1][i], acc[i][j])
-                               : mfma_32x32x16_bf16(fa[kk & 1][i], ring[sl][j], acc[i][j]);
-                if (m < FM) fa[(kk + 1) & 1][m] = kk == KK - 1 ? read_frag(next_stage, 0, m) : read_frag(stage, kk + 1, m);
-                if (m == FM) ring[sl][0] = load_stream_16<NT>(b_src[0] + w_next);
-#pragma unroll
-                for (int op = 0; op < A_OPS; ++op)
-                  if (op >= A_OPS * kk / KK && op < A_OPS * (kk + 1) / KK) {
-                    const int at = FM + 1 + (op - A_OPS * kk / KK);
-                    if (m == (at < 2 * FM - 1 ? at : 2 * FM - 1))
-                      issue_a_op(a_src, lds0, wave, k_steps, fill_stage, tt + SA - 1, op);
-                  }
-                if (m == 2 * FM - 1) {
-                  if (kk == KK - 1) mark_stage_issued();
-                  ring[sl][1] = load_stream_16<NT>(b_src[1] + w_next);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-              }
+              const int copy_step = tt + SA - 1;
+              ilv_substep(kk, sl, stage, next_stage, fill_stage, (size_t)(s_next < n_sub ? s_next : n_sub - 1) * 64,
+                          (size_t)(copy_step < k_steps ? copy_step : k_steps - 1) * CPR, PtrSrc<NA>{a_src, b_src}, lds, lds0, wave,
+                          half, col, ring, fa, acc);
             } else if constexpr (FN == 2) {
               wait_vmcnt_regs<N_B>(ring[sl][0], ring[sl][1]);
 #pragma unroll
@@ -378,6 +440,74 @@ struct StreamTile {
     for (int s = 0; s < DB; ++s)
 #pragma unroll
       for (int j = 0; j < FN; ++j) asm volatile("" ::"v"(ring[s][j]));
+  }
+
+  // The K loop of a block that goes from tile to tile (TR).  On entry the weight ring and the first two activation
+  // stages of the tile have landed (the thread's own part; a barrier here covers the other waves'): they were issued
+  // by the previous tile's last two K steps, or by the block's first prologue.  The last two K steps of this tile in
+  // turn issue the first loads of the NEXT tile, from the sources that `then()` returns (called when the other steps
+  // are through), in place of loads this tile has no use for: they run the same code with their step numbers counted
+  // from the next tile's start.  No operation changes its place in the
+  // vector-memory order, so every hand-counted wait stands.  The ring holds two K steps: k_steps must be even, and at
+  // least 4.
+  // stage: the ring stage of the tile's first step, on return that of the next tile's first step.
+  // On return the next tile's first loads and copies are in flight.
+  template <class THEN>
+  static __device__ __forceinline__ void steps_walk(const RowSrc& now, THEN then, u32x4* lds, int wave, int lane, int k_steps,
+                                                    int& stage, u32x4 (&ring)[DB][FN], Acc& acc) {
+    static_assert(TR && ILV && FN == 2 && DB == 2 * KK && SA == 3, "");
+    const int half = lane / 32, col = lane % 32;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
+    u32x4 fa[2][FM];
+    block_barrier();  // the copies of every wave into the first stage have landed (each waited for its own)
+#pragma unroll
+    for (int i = 0; i < FM; ++i) fa[0][i] = read_fragment(lds, stage, 0, i, half, col);
+    // one K step; hc: its place in the weight ring; first: the step that src counts from
+    auto k_step = [&](int tt, auto hc, const RowSrc& src, int first) __attribute__((always_inline)) {
+      constexpr int h = decltype(hc)::value;
+      const int next_stage = stage + 1 == SA ? 0 : stage + 1;
+      const int fill_stage = stage == 0 ? SA - 1 : stage - 1;  // held step tt-1, free since this step opened
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        if (kk == KK - 1) {
+          wait_vmcnt_opens_stage<N_A + FN - 1, SA>();  // open step tt+1
+          __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): this step's last fragments are in registers
+          block_barrier();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        ilv_substep(kk, h * KK + kk, stage, next_stage, fill_stage, (size_t)((tt - first) * KK + kk + DB) * 64,
+                    (size_t)(tt - first + SA - 1) * CPR, src, lds, lds0, wave, half, col, ring, fa, acc);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      stage = next_stage;
+    };
+    // (a loop that always runs: with a way round it, registers with loads in flight would meet at the far end)
+    int t = 0;
+#pragma nounroll
+    do {
+      k_step(t, std::integral_constant<int, 0>{}, now, 0);
+      k_step(t + 1, std::integral_constant<int, 1>{}, now, 0);
+      t += 2;
+    } while (t + 2 < k_steps);
+    const RowSrc after = then();
+    k_step(t, std::integral_constant<int, 0>{}, after, k_steps);
+    k_step(t + 1, std::integral_constant<int, 1>{}, after, k_steps);
+  }
+  // The sources of a tile, given the input rows of its copies
+  static __device__ __forceinline__ RowSrc row_sources(const TiledCtx& c, const bf16_t* __restrict__ in, const TileLoc& loc,
+                                                       const int (&rows)[7], int wave, int lane) {
+    const int K = GATEUP ? c.hidden : c.ffn;
+    const int n_groups = (GATEUP ? 2 * c.ffn : c.hidden) / TILE_N;
+    const int kt16 = K / TILE_K;
+    const char* slot = c.slots + (size_t)loc.slot * c.slot_bytes;
+    const u32x4* w = GATEUP ? (const u32x4*)slot : (const u32x4*)(slot + 4 * (size_t)c.ffn * c.hidden);
+    // the thread's chunk within a row: the same for every copy (32 rows apart, and the swizzle repeats every 16 rows)
+    const int ci = wave * 64 + lane;
+    const int chunk = (ci % CPR) ^ (((ci / CPR) / RP) % CPR);
+    const int g0 = loc.nt * (BN / TILE_N) + wave * FN;
+    return RowSrc{(const u32x4*)in + chunk, (uint32_t)(K / 8), rows,
+                  {w + (size_t)(g0 < n_groups ? g0 : 0) * kt16 * 64, w + (size_t)(g0 + 1 < n_groups ? g0 + 1 : 0) * kt16 * 64},
+                  (uint32_t)lane * 16};
   }
 
   static __device__ __forceinline__ void epilogue(const TiledCtx& c, bf16_t* __restrict__ out, const TileLoc& loc,
@@ -747,27 +877,25 @@ static void launch_tiles_fit256w(TiledCtx c, int n_rows, const bf16_t* in, bf16_
 }
 
 // The 224x256 tile in a block that works through several tiles (one block per CU, every eighth of the tile list dealt
-// to the blocks of one XCD in turn): before a tile's epilogue the block issues the first loads and copies of its next
-// tile, so their latency passes under the epilogue's arithmetic instead of in front of the next K loop.  The
-// activation ring has three stages and the epilogue a staging region of its own; every vector-memory operation of
-// the kernel after the tile table is issued by hand.
+// to the blocks of one XCD in turn).  A tile's last two K steps issue the first loads and copies of the block's next
+// tile (see StreamTile::steps_walk), so their latency passes under those steps and the epilogue instead of in front of
+// the next K loop.  The activation ring has three stages of the full tile height whatever the tile's own, and the
+// epilogue a staging region of its own; every vector-memory operation of the kernel after the tile table is issued
+// by hand, except the row-map lookups at the start of a tile, where nothing else is in flight.
 //
-// first loads and copies of a 224-row tile of fm fragments (fm copies per thread and stage, stages of fm * 256 chunks)
-template <bool NT>
-__device__ __forceinline__ void walk_issue_prologue(const u32x4* (&a_src)[7], const u32x4* (&b_src)[2], uint32_t lds0, int wave,
-                                                    int k_steps, int fm, u32x4 (&ring)[8][2]) {
-  const int n_sub = k_steps * 4;
+// first loads and copies of a block's first tile (fm copies per thread and stage, into stages 0 and 1)
+template <class TILE>
+__device__ __forceinline__ void walk_issue_prologue(const typename TILE::RowSrc& src, uint32_t lds0, int wave, int fm,
+                                                    u32x4 (&ring)[8][2]) {
 #pragma unroll
   for (int s = 0; s < 8; ++s)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) ring[s][j] = load_stream_16<NT>(b_src[j] + (size_t)(s < n_sub ? s : n_sub - 1) * 64);
+    for (int j = 0; j < 2; ++j) ring[s][j] = src.b_at(j, (size_t)s * 64);
 #pragma unroll
   for (int st = 0; st < 2; ++st)
 #pragma unroll
     for (int op = 0; op < 7; ++op)
-      if (op < fm)  // uniform
-        load_to_lds_16(a_src[op] + (size_t)(st < k_steps ? st : k_steps - 1) * 8,
-                       lds0 + (uint32_t)(st * fm * 256 + (op * 4 + wave) * 64) * 16);
+      if (op < fm) TILE::copy_to_stage(src.a_at(op, (size_t)st * 8), lds0, wave, st, op);  // uniform
 }
 // every vector-memory operation of the thread has completed; the operands tie the weight ring to the wait
 __device__ __forceinline__ void walk_wait_ring(u32x4 (&r)[8][2]) {
@@ -785,11 +913,14 @@ __device__ unsigned long long hmoe_walk_times[2][256][8];
 #else
 #define WT_STAMP(i)
 #endif
+// One tile of fm == FM fragments.  In: loc, ring, stage and the thread's seven input rows at rows_lds (a slot of its own
+// per thread and copy, in LDS: registers are short over the K loop) describe the tile, whose first loads have landed.
+// Out: the same for the block's next tile (more: whether there is one), its first loads landed as well.
 template <bool GATEUP, bool NT, int FM>
 __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
                                               const TileWalk<4>& walk, int xcd, int stride, int wave, int lane, int k_steps,
-                                              u32x4* lds, uint32_t lds0, TileLoc& loc, int& idx, int& fm, bool& more,
-                                              const u32x4* (&a_src)[7], const u32x4* (&b_src)[2], u32x4 (&ring)[8][2]
+                                              u32x4* lds, uint32_t lds0, TileLoc& loc, int& idx, int& fm, bool& more, int& stage,
+                                              int* rows_lds, u32x4 (&ring)[8][2]
 #ifdef HMOE_WALK_TIMING
                                               , unsigned long long (&tacc)[8], unsigned long long& tprev
 #endif
@@ -797,9 +928,12 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, FM, 2, true, true> TILE;
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true, true> FULL;
   // The next tile is looked up before this tile's K loop, and the row-map entries of its copies are requested here,
-  // where nothing issued by hand is in flight: they arrive during the K loop, and between the K loop and the next
-  // tile's first loads only arithmetic is left.  A block at its last tile looks that tile up once more.
+  // where nothing issued by hand is in flight.  A block at its last tile looks that tile up once more, and its last
+  // K steps load that tile's first steps once more, unused.
   const TileLoc done = loc;
+  int rows[7];
+#pragma unroll
+  for (int i = 0; i < 7; ++i) rows[i] = rows_lds[i * 256];
   idx += stride;
   more = walk.at(xcd, idx, loc);  // leaves loc as it is when there is no further tile
   fm = loc.fm;
@@ -812,36 +946,51 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
   WT_STAMP(0)
   typename TILE::Acc acc;
   zero_acc<TILE>(acc);
-  constexpr int HELD = 14 - 2 * FM;  // see run_tile
+  constexpr int HELD = 0;
   f32x16_t held[HELD > 0 ? HELD : 1];
 #pragma unroll
   for (int i = 0; i < HELD; ++i) asm volatile("" : "=a"(held[i]));
+  // The lookups are waited for here, before the first load issued by hand (a wait of the compiler's further down
+  // would count the hand-issued loads as its own and drain them), and turned into input rows.
+#pragma unroll
+  for (int i = 0; i < 7; ++i) asm volatile("" : "+v"(rows_next[i]));
+  FULL::input_rows(c, rows_next);
+#pragma unroll
+  for (int i = 0; i < 7; ++i) rows_lds[i * 256] = rows_next[i];
   int lane_steps = lane;
   asm volatile("" : "+v"(lane_steps));
-  TILE::steps(a_src, b_src, lds, wave, lane_steps, k_steps, ring, acc);
-  WT_STAMP(1)
-  block_barrier();  // every wave is through with the activation stages
-  WT_STAMP(2)
-  // The next tile's first loads and copies are issued here, without a condition, and waited for below, behind the
-  // epilogue: registers with a load in flight never cross a branch (the compiler may copy a value where control flow
-  // merges, and a copy of such a register reads what has not arrived).  A block at its last tile issues that tile's
-  // first loads once more, unused.
-  {
-    // the looked-up rows are used from here on only (not divided and turned into pointers ahead of the K loop, which
-    // would hold twice the registers over it)
+  auto then = [&]() __attribute__((always_inline)) {
+    // (read back here, so that the next tile's addresses are made after this tile's other steps, not held over them)
 #pragma unroll
-    for (int i = 0; i < 7; ++i) asm volatile("" : "+v"(rows_next[i]));
-    int lane_here = lane;
-    asm volatile("" : "+v"(lane_here));
-    FULL::set_sources_from(c, in, loc, rows_next, 0, wave, lane_here, a_src, b_src);
-    walk_issue_prologue<NT>(a_src, b_src, lds0, wave, k_steps, fm, ring);
-  }
-  WT_STAMP(3)
+    for (int i = 0; i < 7; ++i) {
+      rows_next[i] = rows_lds[i * 256];
+      asm volatile("" : "+v"(rows_next[i]));
+    }
+    int lane_then = lane;
+    asm volatile("" : "+v"(lane_then));
+    return TILE::row_sources(c, in, loc, rows_next, wave, lane_then);
+  };
+  TILE::steps_walk(TILE::row_sources(c, in, done, rows, wave, lane_steps), then, lds, wave, lane_steps, k_steps, stage, ring, acc);
+  WT_STAMP(1)
   int lane_there = lane;
   asm volatile("" : "+v"(lane_there));
   if constexpr (GATEUP) TILE::epilogue_lines_walk_tr(c, out, done, acc, lds + FULL::LDS_VEC, wave, lane_there);
   else TILE::epilogue_lines_down_walk_tr(c, out, done, acc, lds + FULL::LDS_VEC, wave, lane_there);
+  WT_STAMP(2)
   walk_wait_ring(ring);
+  WT_STAMP(3)
+  // A next tile that is higher than this one: its last rows were not copied (this tile's steps copy FM row blocks).
+  if (fm > FM) {  // uniform
+    const int s0 = stage, s1 = stage + 1 == 3 ? 0 : stage + 1;
+#pragma unroll
+    for (int op = FM; op < 7; ++op)
+      if (op < fm) {
+        const typename FULL::RowSrc src = FULL::row_sources(c, in, loc, rows_next, wave, lane_there);
+        FULL::copy_to_stage(src.a_at(op, 0), lds0, wave, s0, op);
+        FULL::copy_to_stage(src.a_at(op, 8), lds0, wave, s1, op);
+      }
+    wait_vmcnt<0>();
+  }
   WT_STAMP(4)
 #pragma unroll
   for (int i = 0; i < HELD; ++i) asm volatile("" ::"a"(held[i]));
@@ -860,6 +1009,7 @@ __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf
   constexpr int STAGING = 2 * 7 * 32 * 8;  // two [224][64] bf16 blocks, in 16-byte units
   __shared__ u32x4 lds[FULL::LDS_VEC + STAGING];
   __shared__ int walk_table[TileWalk<4>::TABLE_INTS];
+  __shared__ int walk_rows[7 * 256];  // input rows of the copies of the tile at hand, then of the next: [copy][thread]
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u32x4*)lds;
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -869,13 +1019,16 @@ __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf
   int idx = blockIdx.x / 8;
   TileLoc loc;
   if (!walk.at(xcd, idx, loc)) return;  // uniform over the block
-  const int k_steps = (GATEUP ? c.hidden : c.ffn) / 64;
-  const u32x4* a_src[7];
-  const u32x4* b_src[2];
+  const int k_steps = (GATEUP ? c.hidden : c.ffn) / 64;  // even, at least 4 (the launch sees to it)
+  int rows[7];  // input rows of the thread's copies
   u32x4 ring[8][2];
   int fm = loc.fm;
-  FULL::set_sources(c, in, loc, loc.m0, 0, wave, lane, a_src, b_src);
-  walk_issue_prologue<NT>(a_src, b_src, lds0, wave, k_steps, fm, ring);
+  int stage = 0;
+  FULL::fetch_rows(c, loc, loc.m0, wave, lane, rows);
+  FULL::input_rows(c, rows);
+#pragma unroll
+  for (int i = 0; i < 7; ++i) walk_rows[i * 256 + tid] = rows[i];
+  walk_issue_prologue<FULL>(FULL::row_sources(c, in, loc, rows, wave, lane), lds0, wave, fm, ring);
   walk_wait_ring(ring);
   bool more = true;
 #ifdef HMOE_WALK_TIMING
@@ -886,12 +1039,16 @@ __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf
 #else
 #define WT_ARGS
 #endif
+#define HMOE_WALK_TILE(FM_) \
+  walk_one_tile<GATEUP, NT, FM_>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, stage, walk_rows + tid, \
+                                 ring WT_ARGS)
   while (more) {
-    if (fm == 7) walk_one_tile<GATEUP, NT, 7>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring WT_ARGS);
-    else if (fm == 6) walk_one_tile<GATEUP, NT, 6>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring WT_ARGS);
-    else if (fm == 5) walk_one_tile<GATEUP, NT, 5>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring WT_ARGS);
-    else walk_one_tile<GATEUP, NT, 4>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, a_src, b_src, ring WT_ARGS);
+    if (fm == 7) HMOE_WALK_TILE(7);
+    else if (fm == 6) HMOE_WALK_TILE(6);
+    else if (fm == 5) HMOE_WALK_TILE(5);
+    else HMOE_WALK_TILE(4);
   }
+#undef HMOE_WALK_TILE
 #ifdef HMOE_WALK_TIMING
   if (!DENSE && tid == 0) {
     tacc[7] = tprev - tstart;
@@ -920,6 +1077,10 @@ static void launch_tiles_walk(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* 
     if (want >= 4 && want <= 7) cap = want;
   }
   c.walk_bm = 32 * cap;
+  if ((GATEUP ? c.hidden : c.ffn) % 128 != 0 || (GATEUP ? c.hidden : c.ffn) < 256) {  // they need an even number of K steps, 4 or more
+    launch_tiles_fit<GATEUP, 4, NT>(c, n_rows, in, out, s);
+    return;
+  }
   const long bound = (tiles_upper_bound(c, n_rows, c.walk_bm) + 7) / 8 * 8;
   long blocks = bound < 256 ? bound : 256;  // one per CU
   if (const char* env = getenv("HMOE_WALK_BLOCKS")) {  // tuning and tests: fewer blocks, more tiles each
@@ -975,6 +1136,7 @@ int launch_ffn_tiled(const FfnArgs& a) {
   if (d.dtype != HMOE_BF16) return HMOE_ERR_UNSUPPORTED;
   if (a.n_rows == 0) return HMOE_OK;
   TiledCtx c{a.offsets, a.slot_of, a.slots, a.slot_bytes, a.active, d.n_experts, d.hidden, d.ffn, 0, 0, a.row_map, a.map_div};
+  set_map_div(c);
   const bf16_t* x = (const bf16_t*)a.x_perm;
   bf16_t* h = (bf16_t*)a.h;
   bf16_t* o = (bf16_t*)a.o_perm;

@@ -17,7 +17,24 @@ struct TiledCtx {
   const int32_t* row_map;  // gate/up only: input row of sorted row p is row_map[p] / map_div
   int map_div;
   int walk_bm = 224;  // blocks that walk through tiles: the most rows an m-tile may have (a multiple of 32)
+  // map_div as a multiplication: for 0 <= x < 2^31, x / map_div == umulhi(x, map_mul) >> map_shift (map_div >= 2)
+  uint32_t map_mul = 0;
+  int map_shift = 0;
 };
+
+// Division by the invariant map_div (Granlund and Montgomery's round-up multiplier): with l = ceil(log2 d) and
+// m = ceil(2^(31+l) / d), which fits 32 bits, floor(x m / 2^(31+l)) = floor(x / d) for every 0 <= x < 2^31.
+static inline void set_map_div(TiledCtx& c) {
+  const uint32_t d = (uint32_t)c.map_div;
+  if (d < 2) return;
+  int l = 0;
+  while ((1u << l) < d) ++l;
+  c.map_mul = (uint32_t)(((1ull << (31 + l)) + d - 1) / d);
+  c.map_shift = l - 1;
+}
+__device__ __forceinline__ int div_by_map(const TiledCtx& c, int x) {
+  return c.map_div < 2 ? x : (int)(__umulhi((uint32_t)x, c.map_mul) >> c.map_shift);
+}
 
 // The tile a block works on.  The logical tile list is: for each busy expert in ascending id (rows > 0,
 // selected by the mask, resident), for each n-tile, every m-tile of BM rows.  The hardware deals
