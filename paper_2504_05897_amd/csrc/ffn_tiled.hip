@@ -449,7 +449,7 @@ struct StreamTile {
   // are through), in place of loads this tile has no use for: they run the same code with their step numbers counted
   // from the next tile's start.  No operation changes its place in the
   // vector-memory order, so every hand-counted wait stands.  The ring holds two K steps: k_steps must be even, and at
-  // least 4.
+  // least 6.
   // stage: the ring stage of the tile's first step, on return that of the next tile's first step.
   // On return the next tile's first loads and copies are in flight.
   template <class THEN>
@@ -481,8 +481,12 @@ struct StreamTile {
       }
       stage = next_stage;
     };
+    // The first two steps stand apart: the accumulators start at zero (the caller's zero_acc), so their first matrix
+    // instructions take the constant as their addend and nothing has to be cleared.
+    k_step(0, std::integral_constant<int, 0>{}, now, 0);
+    k_step(1, std::integral_constant<int, 1>{}, now, 0);
     // (a loop that always runs: with a way round it, registers with loads in flight would meet at the far end)
-    int t = 0;
+    int t = 2;
 #pragma nounroll
     do {
       k_step(t, std::integral_constant<int, 0>{}, now, 0);
@@ -670,14 +674,22 @@ struct StreamTile {
     }
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
     block_barrier();
+    // (the reads of up to four rows are issued together, then their stores: one trip to LDS per batch, not per store)
     const int f = nt * (BN / 2) + (wave / 2) * 64 + (lane % 8) * 8;
 #pragma unroll
-    for (int k = 0; k < 2 * FM; ++k) {
-      const int row = (wave % 2) * FM * 16 + k * 8 + lane / 8;
-      const u32x4 v = *(const u32x4*)(block + staged_at(row, lane % 8));
-      const int m = m0 + row;
-      if (m < m_rows && f < n_out) store_16(out + (size_t)(row_first + m) * n_out + f, v);
+    for (int k0 = 0; k0 < 2 * FM; k0 += 4) {
+      u32x4 v[4];
+#pragma unroll
+      for (int k = k0; k < k0 + 4 && k < 2 * FM; ++k)
+        v[k - k0] = *(const u32x4*)(block + staged_at((wave % 2) * FM * 16 + k * 8 + lane / 8, lane % 8));
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
       __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int k = k0; k < k0 + 4 && k < 2 * FM; ++k) {
+        const int m = m0 + (wave % 2) * FM * 16 + k * 8 + lane / 8;
+        if (m < m_rows && f < n_out) store_16(out + (size_t)(row_first + m) * n_out + f, v[k - k0]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
   static __device__ __forceinline__ void epilogue_lines_down_walk_tr(const TiledCtx& c, bf16_t* __restrict__ out,
@@ -712,19 +724,25 @@ struct StreamTile {
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      // (the reads of a fragment's rows are issued together, then their stores: one trip to LDS per four stores; LDS
+      // serves a wave's accesses in order, so the reads see the writes above)
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int row = k * 8 + lane / 8;
-        if (pass * 2 + row / 32 < FM) {  // uniform per k: the second fragment of the last pass may not exist
-          const u32x4 v = *(const u32x4*)(block + staged_at(row, lane % 8));
-          const int m = m0 + pass * 64 + row;
-          if (m < m_rows && n < n_out) store_16(out + (size_t)(row_first + m) * n_out + n, v);
+      for (int ii = 0; ii < 2; ++ii) {
+        if (pass * 2 + ii < FM) {  // the second fragment of the last pass may not exist
+          u32x4 v[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) v[k] = *(const u32x4*)(block + staged_at(ii * 32 + k * 8 + lane / 8, lane % 8));
+          __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int m = m0 + pass * 64 + ii * 32 + k * 8 + lane / 8;
+            if (m < m_rows && n < n_out) store_16(out + (size_t)(row_first + m) * n_out + n, v[k]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
-        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_s_waitcnt(0xC07F);  // the rows are in registers before the next pass overwrites the block
-      __builtin_amdgcn_sched_barrier(0);
+      // (the rows are in registers before the next pass overwrites the block: every read above has been waited for)
     }
   }
   // Down projection with one weight group per wave: a wave's 32 columns are a quarter of a line.  The block collects
@@ -931,43 +949,51 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
   // where nothing issued by hand is in flight.  A block at its last tile looks that tile up once more, and its last
   // K steps load that tile's first steps once more, unused.
   const TileLoc done = loc;
-  int rows[7];
-#pragma unroll
-  for (int i = 0; i < 7; ++i) rows[i] = rows_lds[i * 256];
   idx += stride;
   more = walk.at(xcd, idx, loc);  // leaves loc as it is when there is no further tile
   fm = loc.fm;
-  int rows_next[7];
-  {
+  // Input rows of this tile's copies and of the next tile's.  Gate/up (rows looked up in the row map): this tile's
+  // come from the thread's slots in LDS, where the next tile's then go until the K loop's other steps are through.
+  // Down projection: plain arithmetic, done where the rows are needed.
+  int rows[7], rows_next[7];
+  if constexpr (GATEUP) {
+#pragma unroll
+    for (int i = 0; i < 7; ++i) rows[i] = rows_lds[i * 256];
     int lane_rows = lane;  // (opaque copies of the lane id: what is derived from it is recomputed where it is used)
     asm volatile("" : "+v"(lane_rows));
     FULL::fetch_rows(c, loc, loc.m0, wave, lane_rows, rows_next);
+  } else {
+    int lane_rows = lane;
+    asm volatile("" : "+v"(lane_rows));
+    FULL::fetch_rows(c, done, done.m0, wave, lane_rows, rows);
   }
   WT_STAMP(0)
   typename TILE::Acc acc;
   zero_acc<TILE>(acc);
-  constexpr int HELD = 0;
-  f32x16_t held[HELD > 0 ? HELD : 1];
+  if constexpr (GATEUP) {
+    // The lookups are waited for here, before the first load issued by hand (a wait of the compiler's further down
+    // would count the hand-issued loads as its own and drain them), and turned into input rows.
 #pragma unroll
-  for (int i = 0; i < HELD; ++i) asm volatile("" : "=a"(held[i]));
-  // The lookups are waited for here, before the first load issued by hand (a wait of the compiler's further down
-  // would count the hand-issued loads as its own and drain them), and turned into input rows.
+    for (int i = 0; i < 7; ++i) asm volatile("" : "+v"(rows_next[i]));
+    FULL::input_rows(c, rows_next);
 #pragma unroll
-  for (int i = 0; i < 7; ++i) asm volatile("" : "+v"(rows_next[i]));
-  FULL::input_rows(c, rows_next);
-#pragma unroll
-  for (int i = 0; i < 7; ++i) rows_lds[i * 256] = rows_next[i];
+    for (int i = 0; i < 7; ++i) rows_lds[i * 256] = rows_next[i];
+  }
   int lane_steps = lane;
   asm volatile("" : "+v"(lane_steps));
   auto then = [&]() __attribute__((always_inline)) {
-    // (read back here, so that the next tile's addresses are made after this tile's other steps, not held over them)
-#pragma unroll
-    for (int i = 0; i < 7; ++i) {
-      rows_next[i] = rows_lds[i * 256];
-      asm volatile("" : "+v"(rows_next[i]));
-    }
+    // (made here, so that the next tile's addresses are not held over this tile's other steps)
     int lane_then = lane;
     asm volatile("" : "+v"(lane_then));
+    if constexpr (GATEUP) {
+#pragma unroll
+      for (int i = 0; i < 7; ++i) {
+        rows_next[i] = rows_lds[i * 256];
+        asm volatile("" : "+v"(rows_next[i]));
+      }
+    } else {
+      FULL::fetch_rows(c, loc, loc.m0, wave, lane_then, rows_next);
+    }
     return TILE::row_sources(c, in, loc, rows_next, wave, lane_then);
   };
   TILE::steps_walk(TILE::row_sources(c, in, done, rows, wave, lane_steps), then, lds, wave, lane_steps, k_steps, stage, ring, acc);
@@ -992,8 +1018,6 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
     wait_vmcnt<0>();
   }
   WT_STAMP(4)
-#pragma unroll
-  for (int i = 0; i < HELD; ++i) asm volatile("" ::"a"(held[i]));
 #ifdef HMOE_WALK_TIMING
   tacc[6] += 1;
 #endif
@@ -1019,7 +1043,7 @@ __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf
   int idx = blockIdx.x / 8;
   TileLoc loc;
   if (!walk.at(xcd, idx, loc)) return;  // uniform over the block
-  const int k_steps = (GATEUP ? c.hidden : c.ffn) / 64;  // even, at least 4 (the launch sees to it)
+  const int k_steps = (GATEUP ? c.hidden : c.ffn) / 64;  // even, at least 6 (the launch sees to it)
   int rows[7];  // input rows of the thread's copies
   u32x4 ring[8][2];
   int fm = loc.fm;
@@ -1077,7 +1101,7 @@ static void launch_tiles_walk(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* 
     if (want >= 4 && want <= 7) cap = want;
   }
   c.walk_bm = 32 * cap;
-  if ((GATEUP ? c.hidden : c.ffn) % 128 != 0 || (GATEUP ? c.hidden : c.ffn) < 256) {  // they need an even number of K steps, 4 or more
+  if ((GATEUP ? c.hidden : c.ffn) % 128 != 0 || (GATEUP ? c.hidden : c.ffn) < 384) {  // they need an even number of K steps, 6 or more
     launch_tiles_fit<GATEUP, 4, NT>(c, n_rows, in, out, s);
     return;
   }
