@@ -268,17 +268,35 @@ def test_cache_set_layer_checks_and_changes_no_result(hm):
 def test_ffn_blocks_that_walk_through_tiles(hm, blocks, monkeypatch):
     """The 224x256 tile in blocks that take several tiles each (variants 8 and 9, the choice for large routed
     launches): few blocks, so that every block walks through tiles of every height the tile comes in (4-7 fragments,
-    experts below 97 rows padded to 4), of several experts and n-tiles, with an odd and an even number of K steps,
-    and issues each next tile's first loads under the epilogue of the one before."""
+    experts below 97 rows padded to 4) in both directions (a higher next tile has its last rows copied after the K
+    loop), of several experts and n-tiles; K ranges of 6, 8 and 10 steps (one to four turns of the K loop between the
+    two steps that stand before it and the two that load the next tile; every rotation of the three activation stages
+    from tile to tile); and K ranges the walking blocks do not take (an odd number of steps, fewer than 6), which go
+    to the 4-wave tile."""
     say("ffn walking blocks", blocks)
     monkeypatch.setenv("HMOE_WALK_BLOCKS", str(blocks))
     counts = [225, 700, 31, 450, 0, 129, 224, 1, 600, 353, 161, 97, 900, 260, 0, 512]
-    for variant, hidden, ffn in ((9, 320, 384), (8, 512, 192), (9, 192, 640)):
+    for variant, hidden, ffn in ((9, 384, 640), (8, 512, 384), (9, 640, 512), (9, 320, 192)):
         monkeypatch.setenv("HMOE_TILED_VARIANT", str(variant))
         shape = wl.small_shape(dtype=wl.BF16, hidden=hidden, ffn=ffn, n_experts=len(counts), top_k=2)
         got, ref = _ffn_case(hm, shape, counts, 3, seed=blocks + hidden)
         assert max_rel_err(got, ref) < TOL[wl.BF16]
         assert np.abs(ref).max() > 1e-3
+
+
+def test_ffn_walking_blocks_equal_the_fitted_tiles_bit_for_bit(hm, monkeypatch):
+    """Same k order, same arithmetic: the walking blocks (weights as the first operand of the matrix instruction, the
+    accumulators transposed) give the bits of the 128-row tiles."""
+    say("ffn walking blocks against fitted tiles")
+    counts = [500, 33, 0, 224, 97, 1000, 7, 450]
+    shape = wl.small_shape(dtype=wl.BF16, hidden=512, ffn=384, n_experts=len(counts), top_k=2)
+    outs = []
+    for variant in (9, 3, 8, 0):
+        monkeypatch.setenv("HMOE_TILED_VARIANT", str(variant))
+        got, ref = _ffn_case(hm, shape, counts, 3, seed=5)
+        assert max_rel_err(got, ref) < TOL[wl.BF16]
+        outs.append(np.ascontiguousarray(got).view(np.uint32).copy())
+    assert all((o == outs[0]).all() for o in outs[1:])
 
 
 @pytest.mark.parametrize("hidden,ffn,counts", [
