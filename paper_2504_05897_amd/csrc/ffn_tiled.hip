@@ -925,12 +925,6 @@ __device__ __forceinline__ void walk_wait_ring(u32x4 (&r)[8][2]) {
                : "memory");
 }
 
-#ifdef HMOE_WALK_TIMING
-__device__ unsigned long long hmoe_walk_times[2][256][8];
-#define WT_STAMP(i) { const unsigned long long now_ = __builtin_readcyclecounter(); tacc[i] += now_ - tprev; tprev = now_; }
-#else
-#define WT_STAMP(i)
-#endif
 // One tile of fm == FM fragments.  In: loc, ring, stage and the thread's seven input rows at rows_lds (a slot of its own
 // per thread and copy, in LDS: registers are short over the K loop) describe the tile, whose first loads have landed.
 // Out: the same for the block's next tile (more: whether there is one), its first loads landed as well.
@@ -939,9 +933,6 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
                                               const TileWalk<4>& walk, int xcd, int stride, int wave, int lane, int k_steps,
                                               u32x4* lds, uint32_t lds0, TileLoc& loc, int& idx, int& fm, bool& more, int& stage,
                                               int* rows_lds, u32x4 (&ring)[8][2]
-#ifdef HMOE_WALK_TIMING
-                                              , unsigned long long (&tacc)[8], unsigned long long& tprev
-#endif
                                               ) {
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, FM, 2, true, true> TILE;
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true, true> FULL;
@@ -967,7 +958,6 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
     asm volatile("" : "+v"(lane_rows));
     FULL::fetch_rows(c, done, done.m0, wave, lane_rows, rows);
   }
-  WT_STAMP(0)
   typename TILE::Acc acc;
   zero_acc<TILE>(acc);
   if constexpr (GATEUP) {
@@ -997,14 +987,11 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
     return TILE::row_sources(c, in, loc, rows_next, wave, lane_then);
   };
   TILE::steps_walk(TILE::row_sources(c, in, done, rows, wave, lane_steps), then, lds, wave, lane_steps, k_steps, stage, ring, acc);
-  WT_STAMP(1)
   int lane_there = lane;
   asm volatile("" : "+v"(lane_there));
   if constexpr (GATEUP) TILE::epilogue_lines_walk_tr(c, out, done, acc, lds + FULL::LDS_VEC, wave, lane_there);
   else TILE::epilogue_lines_down_walk_tr(c, out, done, acc, lds + FULL::LDS_VEC, wave, lane_there);
-  WT_STAMP(2)
   walk_wait_ring(ring);
-  WT_STAMP(3)
   // A next tile that is higher than this one: its last rows were not copied (this tile's steps copy FM row blocks).
   if (fm > FM) {  // uniform
     const int s0 = stage, s1 = stage + 1 == 3 ? 0 : stage + 1;
@@ -1017,10 +1004,6 @@ __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* _
       }
     wait_vmcnt<0>();
   }
-  WT_STAMP(4)
-#ifdef HMOE_WALK_TIMING
-  tacc[6] += 1;
-#endif
 }
 
 // DENSE: the launch is a single expert over all rows (a layer's shared experts).  The code is the same; the two are
@@ -1055,17 +1038,9 @@ __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf
   walk_issue_prologue<FULL>(FULL::row_sources(c, in, loc, rows, wave, lane), lds0, wave, fm, ring);
   walk_wait_ring(ring);
   bool more = true;
-#ifdef HMOE_WALK_TIMING
-  unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  unsigned long long tprev = __builtin_readcyclecounter();
-  const unsigned long long tstart = tprev;
-#define WT_ARGS , tacc, tprev
-#else
-#define WT_ARGS
-#endif
 #define HMOE_WALK_TILE(FM_) \
   walk_one_tile<GATEUP, NT, FM_>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, stage, walk_rows + tid, \
-                                 ring WT_ARGS)
+                                 ring)
   while (more) {
     if (fm == 7) HMOE_WALK_TILE(7);
     else if (fm == 6) HMOE_WALK_TILE(6);
@@ -1073,20 +1048,7 @@ __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf
     else HMOE_WALK_TILE(4);
   }
 #undef HMOE_WALK_TILE
-#ifdef HMOE_WALK_TIMING
-  if (!DENSE && tid == 0) {
-    tacc[7] = tprev - tstart;
-    for (int i = 0; i < 8; ++i) hmoe_walk_times[GATEUP ? 0 : 1][blockIdx.x][i] = tacc[i];
-  }
-#endif
 }
-#ifdef HMOE_WALK_TIMING
-}  // namespace hmoe
-extern "C" int hmoe_debug_walk_times(unsigned long long* out) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(hmoe::hmoe_walk_times), sizeof(hmoe::hmoe_walk_times));
-}
-namespace hmoe {
-#endif
 
 template <bool GATEUP, bool NT>
 static void launch_tiles_walk(TiledCtx c, int n_rows, const bf16_t* in, bf16_t* out, hipStream_t s) {
