@@ -416,6 +416,21 @@ def test_small_layer_with_drawn_logits_and_many_experts(hm):
         assert err < TOL[wl.BF16]
 
 
+@pytest.mark.parametrize("top_k", [1, 3, 5, 6, 7])
+def test_layer_through_walking_blocks_with_the_gather_in_gate_up(hm, top_k, monkeypatch):
+    """The whole layer with both projections in walking blocks: the gather folded into gate/up finds the token of a
+    sorted row as perm / top_k, which those blocks compute by multiplication with a constant made on the host --
+    here for divisors that are and are not powers of two."""
+    say("layer through walking blocks, top_k", top_k)
+    monkeypatch.setenv("HMOE_TILED_VARIANT", "9")
+    monkeypatch.setenv("HMOE_WALK_BLOCKS", "16")
+    shape = wl.small_shape(dtype=wl.BF16, hidden=384, ffn=384, n_experts=8, top_k=top_k, shared_ffn=(128,),
+                           x_mode="rmsnorm")
+    err = _layer_case(hm, shape, 40 + top_k, 900, 3)
+    say("  err", err)
+    assert err < TOL[wl.BF16]
+
+
 # ----------------------------------------------------------------------------------------- cache
 def test_cache_slot_maps_and_outputs_follow_the_oracle_over_decode_steps(hm):
     """Partial cache (4 slots, 8 experts): over a sequence of calls the slot map must equal the
