@@ -932,8 +932,7 @@ template <bool GATEUP, bool NT, int FM>
 __device__ __forceinline__ void walk_one_tile(const TiledCtx& c, const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
                                               const TileWalk<4>& walk, int xcd, int stride, int wave, int lane, int k_steps,
                                               u32x4* lds, uint32_t lds0, TileLoc& loc, int& idx, int& fm, bool& more, int& stage,
-                                              int* rows_lds, u32x4 (&ring)[8][2]
-                                              ) {
+                                              int* rows_lds, u32x4 (&ring)[8][2]) {
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, FM, 2, true, true> TILE;
   typedef StreamTile<GATEUP, 224, 4, 3, NT, 8, 7, 2, true, true> FULL;
   // The next tile is looked up before this tile's K loop, and the row-map entries of its copies are requested here,
@@ -1039,8 +1038,8 @@ __global__ __launch_bounds__(256) void ffn_tile_walk_kernel(TiledCtx c, const bf
   walk_wait_ring(ring);
   bool more = true;
 #define HMOE_WALK_TILE(FM_) \
-  walk_one_tile<GATEUP, NT, FM_>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, stage, walk_rows + tid, \
-                                 ring)
+  walk_one_tile<GATEUP, NT, FM_>(c, in, out, walk, xcd, stride, wave, lane, k_steps, lds, lds0, loc, idx, fm, more, stage, \
+                                 walk_rows + tid, ring)
   while (more) {
     if (fm == 7) HMOE_WALK_TILE(7);
     else if (fm == 6) HMOE_WALK_TILE(6);
