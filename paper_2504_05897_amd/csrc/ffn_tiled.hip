@@ -703,46 +703,40 @@ struct StreamTile {
     const int n_out = c.hidden;
     const int m0 = loc.m0;
     const int half = lane / 32, rl = lane % 32;
-    char* block = (char*)(staging + wave * 64 * 8);  // [64 rows][64 columns], the wave's own
+    char* block = (char*)(staging + wave * 64 * 8);  // two [32 rows][64 columns] halves, the wave's own
     const int n = nt * BN + wave * 64 + (lane % 8) * 8;
+    // Fragment by fragment through the two halves in turn: the next fragment is converted and written while the reads
+    // of this one are on their way, so the trips to LDS overlap the conversions instead of following them.  (LDS
+    // serves a wave's accesses in order: the reads see the writes before them, and a half is written again only
+    // after its reads have come back, two fragments later.)
+    auto write_fragment = [&](int i) {
+      const int row = (i % 2) * 32 + rl;
 #pragma unroll
-    for (int pass = 0; pass < (FM + 1) / 2; ++pass) {
+      for (int j = 0; j < FN; ++j)
 #pragma unroll
-      for (int ii = 0; ii < 2; ++ii) {
-        const int i = pass * 2 + ii;
-        if (i < FM) {
-          const int row = ii * 32 + rl;
-#pragma unroll
-          for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              uint2 pk;
-              pk.x = f32_to_bf16_pair(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1]);
-              pk.y = f32_to_bf16_pair(acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
-              *(uint2*)(block + staged_at(row, j * 4 + q) + half * 8) = pk;
-            }
+        for (int q = 0; q < 4; ++q) {
+          uint2 pk;
+          pk.x = f32_to_bf16_pair(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1]);
+          pk.y = f32_to_bf16_pair(acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+          *(uint2*)(block + staged_at(row, j * 4 + q) + half * 8) = pk;
         }
+    };
+    write_fragment(0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      u32x4 v[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[k] = *(const u32x4*)(block + staged_at((i % 2) * 32 + k * 8 + lane / 8, lane % 8));
+      __builtin_amdgcn_sched_barrier(0);
+      if (i + 1 < FM) write_fragment(i + 1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int m = m0 + i * 32 + k * 8 + lane / 8;
+        if (m < m_rows && n < n_out) store_16(out + (size_t)(row_first + m) * n_out + n, v[k]);
         __builtin_amdgcn_sched_barrier(0);
       }
-      // (the reads of a fragment's rows are issued together, then their stores: one trip to LDS per four stores; LDS
-      // serves a wave's accesses in order, so the reads see the writes above)
-#pragma unroll
-      for (int ii = 0; ii < 2; ++ii) {
-        if (pass * 2 + ii < FM) {  // the second fragment of the last pass may not exist
-          u32x4 v[4];
-#pragma unroll
-          for (int k = 0; k < 4; ++k) v[k] = *(const u32x4*)(block + staged_at(ii * 32 + k * 8 + lane / 8, lane % 8));
-          __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const int m = m0 + pass * 64 + ii * 32 + k * 8 + lane / 8;
-            if (m < m_rows && n < n_out) store_16(out + (size_t)(row_first + m) * n_out + n, v[k]);
-            __builtin_amdgcn_sched_barrier(0);
-          }
-        }
-      }
-      // (the rows are in registers before the next pass overwrites the block: every read above has been waited for)
     }
   }
   // Down projection with one weight group per wave: a wave's 32 columns are a quarter of a line.  The block collects
