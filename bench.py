@@ -207,12 +207,24 @@ def main() -> int:
                 one_step(i)
             torch.cuda.synchronize()
             ms = hm.hmoe_probe_read(probe_steps * pairs_per_step)
-            for l, keep in zip(layers, saved):
-                l.overlap_shared, l.merge_shared, l.merge_combine = keep
             per_call = 4 if Fs else 2
             kern = {"gate_up": ms[0::per_call], "down": ms[1::per_call]}
             if Fs:
                 kern["shared_gate_up"], kern["shared_down"] = ms[2::per_call], ms[3::per_call]
+            if Fs and T <= 32 and not w4 and all(keep[1] for keep in saved):
+                # third pass, decode-sized batches: the launches the timed steps really make there, which carry the
+                # shared experts' FFN inside the routed experts' two launches
+                for l in layers:
+                    l.merge_shared = True
+                merged_pairs = (n_layers if stacked else 1) * 2
+                hm.hmoe_probe_arm(probe_steps * merged_pairs)
+                for i in range(probe_steps):
+                    one_step(i)
+                torch.cuda.synchronize()
+                ms = hm.hmoe_probe_read(probe_steps * merged_pairs)
+                kern["gate_up_with_shared"], kern["down_with_shared"] = ms[0::2], ms[1::2]
+            for l, keep in zip(layers, saved):
+                l.overlap_shared, l.merge_shared, l.merge_combine = keep
             # what the routed kernels touched (distinct experts with rows, last step's routing)
             used = range(n_layers) if stacked else range(min(n_layers, probe_steps))
             distinct = float(np.mean([(np.diff(layers[li].offsets.cpu().numpy()) > 0).sum() for li in used]))
@@ -238,6 +250,11 @@ def main() -> int:
             if Fs:
                 r["shared_gate_up"] = roof(2 * H * Fs * w_bytes + T * H * elem + T * Fs * elem, 4.0 * H * Fs * T, kern["shared_gate_up"])
                 r["shared_down"] = roof(H * Fs * w_bytes + T * Fs * elem + T * H * elem, 2.0 * H * Fs * T, kern["shared_down"])
+            if "gate_up_with_shared" in kern:   # the two launches of a decode step as it is timed: routed + shared work
+                r["gate_up_with_shared"] = roof((distinct * F + Fs) * 2 * H * w_bytes + (A + T) * H * elem + (A * F + T * Fs) * elem,
+                                                4.0 * H * (F * A + Fs * T), kern["gate_up_with_shared"])
+                r["down_with_shared"] = roof((distinct * F + Fs) * H * w_bytes + (A * F + T * Fs) * elem + (A + T) * H * elem,
+                                             2.0 * H * (F * A + Fs * T), kern["down_with_shared"])
             results[pname] = r
 
         # ---- staging: the workload's real cache size, misses copied from pinned host memory --------

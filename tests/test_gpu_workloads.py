@@ -194,6 +194,9 @@ def test_bench_line_contract():
         assert ph["ms_per_step_p10"] <= ph["ms_per_step"] <= ph["ms_per_step_p90"] and ph["blocks"] == 3
         for part in ("gate_up", "down", "layer"):
             assert ph[part]["bound"] in ("hbm", "mfma") and 0 < ph[part]["frac"] < 1.2, (name, part, ph[part])
+    for name in ("dsv2lite/decode1", "qwen2moe/decode4"):   # decode steps of layers with shared experts: the merged launches
+        for part in ("gate_up_with_shared", "down_with_shared"):
+            assert 0 < out["phases"][name][part]["frac"] < 1.2, (name, part)
     assert out["value"] == out["phases"]["stress/prefill16384"]["tokens_per_s"]
     refused = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                              timeout=120, cwd=root)
