@@ -52,6 +52,18 @@ def test_register_of_a_load_in_flight():
     assert len(check(lds)) == 3
 
 
+def test_load_from_a_scalar_base_with_a_lane_offset():
+    """The form the walking blocks issue their weight loads in (address in scalar registers, a 32-bit offset per lane):
+    its destination is tracked like the other form's, and its offset register is an address like any other."""
+    check = _load("asm_check").find_inflight_hazards
+    hand = "\t;;#ASMSTART\n\tglobal_load_dwordx4 v[10:13], v5, s[2:3]\n\t;;#ASMEND\n"
+    assert len(check(listing(hand + "\tv_mov_b32_e32 v12, 0\n\ts_waitcnt vmcnt(0)\n"))) == 1
+    assert check(listing(hand + "\ts_waitcnt vmcnt(0)\n\tv_mov_b32_e32 v12, 0\n")) == []
+    # the offset of a second load taken from the first one's destination while that is in flight
+    found = check(listing(hand + "\t;;#ASMSTART\n\tglobal_load_dwordx4 v[20:23], v11, s[2:3] nt\n\t;;#ASMEND\n\ts_waitcnt vmcnt(0)\n"))
+    assert len(found) == 1 and "reads v[11]" in found[0]
+
+
 def test_labels_without_fall_through():
     check = _load("asm_check").find_inflight_hazards
     tail = "\tv_mov_b32_e32 v10, 0\n\ts_waitcnt vmcnt(0)\n"
